@@ -1,0 +1,260 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+* a hand-worked example (tests/golden/hand_example.json; Sec. 3.1, Eq. 2 and Eq. 3),
+* a brute-force twin in the per-adapter ("loop-original", Sec. 3.3) form with a
+  rank-based one-hot mask, written with numpy matmuls in fp64,
+* special cases that reduce to one dense fp64 GEMM (Eq. 1 with a single adapter;
+  the average-merge baseline of Sec. 4.1 when all logits tie and k=N),
+* invariants of Eq. 2 / Eq. 3 and of the bucketing.
+
+Shapes are deliberately asymmetric (d_in != d_out, r != k, N prime) so that a
+transposed operand or a swapped index cannot pass.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from gen import inputs as gen
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _rand_layer(seed, T=7, d_in=12, d_out=20, N=5, r=3, dtype="f32", routing="uniform", k=2):
+    shape = gen.LayerShape(T, d_in, d_out, N, r, k, 2.0, dtype, routing, "pin")
+    ops = gen.make_layer(shape, seed)
+    # O(1) operands so errors are visible
+    ops["W_gate"] = ops["W_gate"] * np.float32(np.sqrt(d_in))
+    return shape, ops
+
+
+# ---------------------------------------------------------------- brute force
+def brute_force_layer(x, W, W_gate, bias, A, B, k, scale):
+    """Per-adapter evaluation: every adapter densely on its token set, one-hot top-k mask."""
+    x64, W64 = x.astype(np.float64), W.astype(np.float64)
+    g = x64 @ W_gate.astype(np.float64)
+    if bias is not None:
+        g = g + bias.astype(np.float64)
+    g = g.astype(np.float32)
+    T, N = g.shape
+    # rank of adapter j for token t = number of adapters that beat it
+    beats = (g[:, :, None] > g[:, None, :]) | \
+            ((g[:, :, None] == g[:, None, :]) & (np.arange(N)[:, None] < np.arange(N)[None, :]))
+    rank = beats.sum(axis=1)                    # [T, N]
+    mask = rank < k
+    g64 = g.astype(np.float64)
+    e = np.where(mask, np.exp(g64 - np.where(mask, g64, -np.inf).max(axis=1, keepdims=True)), 0.0)
+    w = e / e.sum(axis=1, keepdims=True)        # softmax restricted to the selected k
+    y = x64 @ W64.T
+    for i in range(N):                          # loop over adapters, gather X_i
+        sel = np.nonzero(mask[:, i])[0]
+        if sel.size == 0:
+            continue
+        Xi = x64[sel]
+        y[sel] += scale * w[sel, i:i + 1] * ((Xi @ A[i].astype(np.float64)) @ B[i].astype(np.float64))
+    return y, g, rank, w
+
+
+# ------------------------------------------------------------------ the pins
+def test_hand_worked_example():
+    with open(os.path.join(HERE, "golden", "hand_example.json")) as f:
+        ex = json.load(f)
+    x, Wg, W = (np.array(ex[n], dtype=np.float32) for n in ("x", "W_gate", "W"))
+    A, B = np.array(ex["A"], dtype=np.float32), np.array(ex["B"], dtype=np.float32)
+    exp = ex["expect"]
+    out = oracle.linear_forward(x, W, Wg, None, A, B, ex["k"], ex["scale"])
+    assert np.array_equal(out["logits"], np.array(exp["logits"], dtype=np.float32))
+    assert np.array_equal(out["idx"], np.array(exp["idx"]))
+    np.testing.assert_allclose(out["w"], exp["w"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(out["y"], exp["y"], rtol=0, atol=1e-14)
+    np.testing.assert_allclose(oracle.base(x, W), exp["base"], rtol=0, atol=0)
+    _, h = oracle.lora_delta(x, A, B, out["idx"], out["w"], ex["scale"], return_h=True)
+    np.testing.assert_allclose(h, exp["h"], rtol=0, atol=0)
+    c, o, tok, slot = oracle.bucket(out["idx"], 3)
+    assert c.tolist() == exp["counts"] and o.tolist() == exp["offsets"]
+    assert tok.tolist() == exp["bucket_tok"] and slot.tolist() == exp["bucket_slot"]
+
+
+@pytest.mark.parametrize("seed,k,routing", [(0, 1, "uniform"), (1, 2, "uniform"), (2, 3, "zipf"),
+                                            (3, 5, "uniform")])
+def test_brute_force_twin(seed, k, routing):
+    shape, o = _rand_layer(seed, k=k, routing=routing)
+    out = oracle.linear_forward(o["x"], o["W"], o["W_gate"], o["bias"], o["A"], o["B"], k, 2.0)
+    y, g, rank, w = brute_force_layer(o["x"], o["W"], o["W_gate"], o["bias"], o["A"], o["B"], k, 2.0)
+    np.testing.assert_allclose(out["logits"], g, rtol=0, atol=1e-6)
+    # selection: adapter idx[t, s] has rank s
+    for t in range(shape.T):
+        for s in range(k):
+            assert rank[t, out["idx"][t, s]] == s
+            assert abs(out["w"][t, s] - w[t, out["idx"][t, s]]) < 1e-14
+    np.testing.assert_allclose(out["y"], y, rtol=0, atol=1e-11)
+
+
+def test_row_subset_matches_full():
+    shape, o = _rand_layer(4, T=9)
+    full = oracle.linear_forward(o["x"], o["W"], o["W_gate"], None, o["A"], o["B"], 2, 2.0)
+    rows = np.array([8, 0, 3, 3], dtype=np.int32)
+    sub = oracle.linear_forward(o["x"], o["W"], o["W_gate"], None, o["A"], o["B"], 2, 2.0, rows=rows)
+    for n in ("y", "logits", "idx", "w"):
+        assert np.array_equal(sub[n], full[n][rows])
+
+
+def test_single_adapter_is_eq1_gemm():
+    """N=1, k=1: w=1 and the layer is x(W + s*A*B): one fp64 GEMM (Eq. 1; top-1 remark, App. A.1)."""
+    shape, o = _rand_layer(5, N=1, k=1)
+    out = oracle.linear_forward(o["x"], o["W"], o["W_gate"], None, o["A"], o["B"], 1, 2.0)
+    merged = o["W"].astype(np.float64).T + 2.0 * (o["A"][0].astype(np.float64) @ o["B"][0].astype(np.float64))
+    np.testing.assert_allclose(out["y"], o["x"].astype(np.float64) @ merged, rtol=0, atol=1e-12)
+    assert np.all(out["w"] == 1.0) and np.all(out["idx"] == 0)
+
+
+def test_all_tied_full_k_is_average_merge():
+    """W_gate=0, k=N: every logit ties, w=1/N, layer = x(W + (s/N) sum A_i B_i) (Avg-Merge, Sec. 4.1)."""
+    shape, o = _rand_layer(6, N=5, k=5)
+    Wg0 = np.zeros_like(o["W_gate"])
+    out = oracle.linear_forward(o["x"], o["W"], Wg0, None, o["A"], o["B"], 5, 2.0)
+    assert np.array_equal(out["idx"], np.tile(np.arange(5, dtype=np.int32), (shape.T, 1)))
+    np.testing.assert_allclose(out["w"], 0.2, rtol=0, atol=1e-16)
+    merged = o["W"].astype(np.float64).T + (2.0 / 5) * sum(
+        o["A"][i].astype(np.float64) @ o["B"][i].astype(np.float64) for i in range(5))
+    np.testing.assert_allclose(out["y"], o["x"].astype(np.float64) @ merged, rtol=0, atol=1e-12)
+
+
+def test_zero_B_gives_base_exactly():
+    shape, o = _rand_layer(7)
+    out = oracle.linear_forward(o["x"], o["W"], o["W_gate"], None, o["A"], np.zeros_like(o["B"]), 2, 2.0)
+    assert np.array_equal(out["y"], oracle.base(o["x"], o["W"]))
+    np.testing.assert_allclose(out["y"], o["x"].astype(np.float64) @ o["W"].astype(np.float64).T,
+                               rtol=0, atol=1e-12)
+
+
+def test_weights_positive_sum_to_one_and_match_full_softmax():
+    shape, o = _rand_layer(8, T=50, N=7, k=3)
+    g = oracle.gate_logits(o["x"], o["W_gate"]).astype(np.float32)
+    idx, w = oracle.topk_softmax(g, 3)
+    assert np.all(w > 0)
+    np.testing.assert_allclose(w.sum(axis=1), 1.0, rtol=0, atol=1e-15)
+    # softmax over all N, renormalised over the selected k, equals Eq. 3
+    g64 = g.astype(np.float64)
+    p = np.exp(g64 - g64.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    psel = np.take_along_axis(p, idx.astype(np.int64), axis=1)
+    np.testing.assert_allclose(w, psel / psel.sum(axis=1, keepdims=True), rtol=0, atol=1e-14)
+    # descending order of the selected logits
+    gs = np.take_along_axis(g, idx.astype(np.int64), axis=1)
+    assert np.all(gs[:, :-1] >= gs[:, 1:])
+
+
+def test_topk_matches_stable_argsort_and_tie_break():
+    rng = np.random.default_rng(0)
+    g = rng.integers(-3, 4, size=(200, 9)).astype(np.float32)      # many exact ties
+    for k in (1, 2, 4, 9):
+        idx, _ = oracle.topk_softmax(g, k)
+        ref = np.argsort(-g, axis=1, kind="stable")[:, :k]          # stable: lower index first
+        assert np.array_equal(idx, ref.astype(np.int32))
+    # duplicated gate column: identical logits, the lower index must come first
+    shape, o = _rand_layer(9, N=5)
+    Wg = o["W_gate"].copy()
+    Wg[:, 3] = Wg[:, 1]
+    gg = oracle.gate_logits(o["x"], Wg).astype(np.float32)
+    idx, _ = oracle.topk_softmax(gg, 5)
+    for t in range(shape.T):
+        pos = idx[t].tolist()
+        assert pos.index(1) + 1 == pos.index(3)
+
+
+def test_gate_logits_match_fp64_matmul_and_bias():
+    shape, o = _rand_layer(10, routing="zipf")
+    g = oracle.gate_logits(o["x"], o["W_gate"], o["bias"])
+    ref = o["x"].astype(np.float64) @ o["W_gate"].astype(np.float64) + o["bias"].astype(np.float64)
+    np.testing.assert_allclose(g, ref, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(o["bias"], 2 * np.log(1 / (np.arange(5) + 1.0)), rtol=1e-6)
+
+
+def test_temperature_reading():
+    g = np.array([[0.0, 3.0, 1.0]], dtype=np.float32)
+    idx, w = oracle.topk_softmax(g, 2, temperature=2.0)
+    assert idx.tolist() == [[1, 2]]
+    np.testing.assert_allclose(w, [[1 / (1 + np.exp(-1.0)), 1 - 1 / (1 + np.exp(-1.0))]], atol=1e-15)
+
+
+def test_permutation_invariances():
+    shape, o = _rand_layer(11, T=8, N=5)
+    ref = oracle.linear_forward(o["x"], o["W"], o["W_gate"], None, o["A"], o["B"], 2, 2.0)
+    perm = np.array([3, 0, 4, 1, 2])
+    out = oracle.linear_forward(o["x"], o["W"], o["W_gate"][:, perm], None, o["A"][perm], o["B"][perm], 2, 2.0)
+    np.testing.assert_allclose(out["y"], ref["y"], rtol=0, atol=1e-12)
+    assert np.array_equal(perm[out["idx"]], ref["idx"])
+    tperm = np.array([5, 2, 7, 0, 1, 6, 3, 4])
+    out = oracle.linear_forward(o["x"][tperm], o["W"], o["W_gate"], None, o["A"], o["B"], 2, 2.0)
+    assert np.array_equal(out["y"], ref["y"][tperm])
+
+
+def test_linear_in_scale_and_top1_ignores_gate_scale():
+    shape, o = _rand_layer(12)
+    f = lambda s, k=2, wg=o["W_gate"]: oracle.linear_forward(o["x"], o["W"], wg, None, o["A"], o["B"], k, s)["y"]
+    y0, y1, y3 = f(0.0), f(1.0), f(3.0)
+    np.testing.assert_allclose(y3 - y0, 3 * (y1 - y0), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(y0, oracle.base(o["x"], o["W"]), rtol=0, atol=0)
+    np.testing.assert_allclose(f(2.0, 1), f(2.0, 1, o["W_gate"] * np.float32(4.0)), rtol=0, atol=0)
+
+
+def test_lora_delta_matches_per_token_einsum():
+    """Eq. 5 (bmm form): entry (t,j) uses A_{I(t)_j}, B_{I(t)_j}, weight w[t,j]; sum over the k entries."""
+    shape, o = _rand_layer(13, T=6, N=5, r=3)
+    rng = np.random.default_rng(1)
+    idx = np.stack([rng.permutation(5)[:2] for _ in range(6)]).astype(np.int32)
+    w = rng.random((6, 2))
+    delta, h = oracle.lora_delta(o["x"], o["A"], o["B"], idx, w, 1.5, return_h=True)
+    A_sel = o["A"].astype(np.float64)[idx]            # [T,k,d,r]   (the gathered copies of bmm-torch)
+    B_sel = o["B"].astype(np.float64)[idx]            # [T,k,r,h]
+    h_ref = np.einsum("td,tkdr->tkr", o["x"].astype(np.float64), A_sel)
+    d_ref = 1.5 * np.einsum("tk,tkr,tkrh->th", w, h_ref, B_sel)
+    np.testing.assert_allclose(h, h_ref, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(delta, d_ref, rtol=0, atol=1e-12)
+
+
+def test_bucket_invariants_and_stable_sort():
+    rng = np.random.default_rng(2)
+    T, k, N = 300, 3, 11
+    idx = np.stack([rng.permutation(N)[:k] for _ in range(T)]).astype(np.int32)
+    idx[idx == 4] = 10                                           # make bucket 4 empty (may duplicate 10: allowed here)
+    counts, offsets, tok, slot = oracle.bucket(idx, N)
+    assert counts.sum() == T * k and counts[4] == 0
+    assert offsets[0] == 0 and np.array_equal(offsets[1:], np.cumsum(counts))
+    flat = idx.reshape(-1)
+    order = np.argsort(flat, kind="stable")                      # library routine: stable sort by adapter
+    assert np.array_equal(tok, (order // k).astype(np.int32))
+    assert np.array_equal(slot, (order % k).astype(np.int32))
+    for j in range(N):
+        seg = tok[offsets[j]:offsets[j + 1]]
+        assert np.all(np.diff(seg) >= 0)
+        assert np.all(idx[seg, slot[offsets[j]:offsets[j + 1]]] == j)
+
+
+def test_bf16_inputs_are_exact_in_bf16():
+    import torch
+    shape = gen.LayerShape(5, 64, 32, 3, 4, 2, 2.0, "bf16")
+    o = gen.make_layer(shape, 3)
+    for n in ("x", "W", "A", "B"):
+        t = torch.from_numpy(o[n])
+        assert torch.equal(t.to(torch.bfloat16).to(torch.float32), t)
+    raw = gen.make_layer(gen.LayerShape(5, 64, 32, 3, 4, 2, 2.0, "f32"), 3)["x"]
+    assert torch.equal(torch.from_numpy(raw).to(torch.bfloat16).to(torch.float32), torch.from_numpy(o["x"]))
+
+
+def test_margin_conditioning_removes_near_ties():
+    from oracle import margin
+    seed, layers = gen.config_layers(1)
+    shape = gen.LayerShape(2000, 64, 64, 28, 8, 2, 2.0, "bf16")
+    o = gen.make_layer(shape, seed, only=("x", "W_gate"))
+    before = margin.small_margin_rows(oracle.gate_logits(o["x"], o["W_gate"]), 2, 1e-3)
+    n = margin.condition_margins(shape, seed, 0, o["x"], o["W_gate"], None, 1e-3)
+    after = margin.small_margin_rows(oracle.gate_logits(o["x"], o["W_gate"]), 2, 1e-3)
+    assert n >= before.size and after.size == 0
+    # deterministic
+    o2 = gen.make_layer(shape, seed, only=("x", "W_gate"))
+    margin.condition_margins(shape, seed, 0, o2["x"], o2["W_gate"], None, 1e-3)
+    assert np.array_equal(o["x"], o2["x"])
