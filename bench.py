@@ -1,0 +1,142 @@
+"""Benchmark of the MeteoRA linear-layer forward on one MI355X.
+
+A "step" is one meteora_linear_forward over one batch of the workload (all stages of the hot
+path: gate, top-k, bucketing, shrink, base GEMM, expand).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layer 0] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+
+
+def algorithmic(shape):
+    """Algorithmic flops and bytes of each stage of one layer call (e = bytes per element)."""
+    s = shape
+    e = 2 if s.dtype == "bf16" else 4
+    T, di, do, N, r, k = s.T, s.d_in, s.d_out, s.N, s.r, s.k
+    return {
+        "gate": {"flops": 2.0 * T * di * N, "bytes": T * di * e + di * N * 4 + T * k * 8},
+        "shrink": {"flops": 2.0 * T * k * di * r, "bytes": T * di * e + N * di * r * e + T * k * r * 4},
+        "expand": {"flops": 2.0 * T * k * r * do, "bytes": T * k * r * 4 + N * r * do * e + T * do * e},
+        "gemm": {"flops": 2.0 * T * di * do, "bytes": T * di * e + di * do * e + T * do * e},
+    }
+
+
+def cpu_baseline(shape, ops, budget_s=15.0):
+    """Time the CPU oracle (as it stands) on a bounded sample of rows of the same workload."""
+    import numpy as np
+    import oracle
+    probe = np.arange(0, shape.T, max(1, shape.T // 16), dtype=np.int32)[:16]
+    t0 = time.perf_counter()
+    oracle.linear_forward(ops["x"], ops["W"], ops["W_gate"], ops["bias"], ops["A"], ops["B"], shape.k, shape.scale,
+                          rows=probe)
+    per_row = (time.perf_counter() - t0) / probe.size
+    n = int(max(16, min(shape.T, budget_s / max(per_row, 1e-9))))
+    rows = np.linspace(0, shape.T - 1, n).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.linear_forward(ops["x"], ops["W"], ops["W_gate"], ops["bias"], ops["A"], ops["B"], shape.k, shape.scale,
+                          rows=rows)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{n} of {shape.T} token rows (evenly strided) of the same layer, {dt:.1f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+                 "(the layer shards by tokens with no exchange step, see DESIGN.md)")
+
+    import numpy as np
+    import torch
+    import paper_2405_13053_amd as m
+    from gen import inputs as gen
+
+    torch.cuda.set_device(0)
+    seed, layers = gen.config_layers(args.config)
+    shape = layers[args.layer]
+    ops = gen.make_layer(shape, seed, args.layer)
+    dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    dev = {n: torch.from_numpy(ops[n]).cuda().to(dt) for n in ("x", "W", "A", "B")}
+    Wg = torch.from_numpy(ops["W_gate"]).cuda()
+    bias = None if ops["bias"] is None else torch.from_numpy(ops["bias"]).cuda()
+    out = torch.empty((shape.T, shape.d_out), dtype=dt, device="cuda")
+    ws = torch.empty(m.workspace_bytes(shape.T, shape.d_in, shape.d_out, shape.N, shape.r, shape.k, dt),
+                     dtype=torch.uint8, device="cuda")
+
+    def step():
+        m.linear_forward(dev["x"], dev["W"], Wg, bias, dev["A"], dev["B"], shape.k, shape.scale, out=out, ws=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_s = shape.T * args.steps / elapsed
+
+    # per-stage durations from hipEvents recorded by the library on the launch stream
+    m.stage_timing_enable(True)
+    n_prof = min(args.steps, 200)
+    for _ in range(n_prof):
+        step()
+    torch.cuda.synchronize()
+    stages, calls = m.stage_timing_read()
+    m.stage_timing_enable(False)
+    stage_us = {n: (ms / max(c, 1)) * 1e3 for n, (ms, c) in stages.items() if c > 0}
+
+    alg = algorithmic(shape)
+    gemm_us = stage_us["gemm"]
+    gemm_flops = alg["gemm"]["flops"] + (alg["expand"]["flops"] if "expand" not in stage_us else 0.0)
+    achieved = gemm_flops / (gemm_us * 1e-6) / 1e12
+    roofline = {"kernel": "base GEMM (bf16 MFMA)" if shape.dtype == "bf16" else "base GEMM (fp32)",
+                "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_MFMA_BF16_TFLOPS, "traffic": None}
+    per_stage = {}
+    for n, us in stage_us.items():
+        key = {"gate_logits": "gate", "gate_topk": None, "bucket": None}.get(n, n)
+        d = {"us": round(us, 2)}
+        if key and key in alg:
+            d["GB/s"] = round(alg[key]["bytes"] / (us * 1e-6) / 1e9, 1)
+            d["TFLOP/s"] = round(alg[key]["flops"] / (us * 1e-6) / 1e12, 2)
+            d["hbm_frac"] = round(alg[key]["bytes"] / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)
+        per_stage[n] = d
+
+    res = {
+        "metric": "MeteoRA-layer tokens/s at Llama3-8B shapes (28 LoRAs, top-2); % HBM/MFMA peak",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"config {args.config} / {shape.name}: T={shape.T}, {shape.d_in}->{shape.d_out}, "
+                               f"N={shape.N}, r={shape.r}, top-{shape.k}, s={shape.scale}, {shape.routing} routing",
+                   "inputs_resident_in_hbm": True},
+        "roofline": roofline,
+        "stages": per_stage,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(shape, ops)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

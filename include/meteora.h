@@ -1,0 +1,160 @@
+/*
+ * meteora.h - C ABI of the MI355X (gfx950) MeteoRA linear-layer forward.
+ *
+ * The layer (paper Sec. 3.1, Eq. 2 and Eq. 3; row-vector convention of Eq. 1):
+ *
+ *     G(x) = x * W_gate (+ bias)                      gate logits, fp32
+ *     I(x) = top-k adapters by logit (ties -> lower index)
+ *     w_i  = softmax over the k selected logits       Eq. 3
+ *     o    = x * W_base + scale * sum_{i in I(x)} w_i * ((x * A_i) * B_i)   Eq. 2
+ *
+ * with the n LoRA pairs stacked contiguously as in Sec. 3.3:
+ * A[N, d_in, r], B[N, r, d_out].
+ *
+ * Conventions common to every entry point
+ *  - Every pointer is a DEVICE pointer (HBM of the current HIP device) unless
+ *    it is marked "host".  All arrays are dense, row-major, 16-byte aligned.
+ *  - `dt` is the storage type of x, W, A, B and out: METEORA_BF16 (bfloat16,
+ *    fp32 accumulation) or METEORA_F32.  W_gate, gate_bias, logits and topk_w
+ *    are always fp32; indices are int32.
+ *  - Storage: x[T, d_in]; W[d_out, d_in] (o[t,c] = sum_i x[t,i] * W[c,i]);
+ *    W_gate[d_in, N]; gate_bias[N] or NULL; A[N, d_in, r]; B[N, r, d_out];
+ *    out[T, d_out].
+ *  - Ownership: the caller owns all memory.  The library never allocates,
+ *    frees or keeps device memory; scratch space is the caller's `ws`
+ *    (at least meteora_workspace_bytes(...) bytes, 256-byte aligned).
+ *    Inputs are only read; outputs are fully overwritten (except
+ *    accumulate=1).  Outputs must not alias inputs.
+ *  - Execution: all work is enqueued on `stream` (a hipStream_t passed as
+ *    void*; NULL = the default stream).  No call synchronises with the host.
+ *    Results are deterministic: same inputs -> bit-identical outputs.
+ *    Calls that share a workspace must be ordered on one stream.
+ *  - Errors: a status code is returned, nothing is thrown.  Arguments are
+ *    validated on the host before any launch, so an error status means that
+ *    nothing was enqueued.  T == 0 returns METEORA_OK without a launch.
+ *  - Limits: 1 <= k <= N <= 64, k <= 8, 1 <= r <= 64; d_in % 8 == 0 and
+ *    d_out % 8 == 0; T * k < 2^31.  Inputs must be finite.
+ */
+#ifndef METEORA_H
+#define METEORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    METEORA_OK = 0,
+    METEORA_ERR_INVALID_ARG = 1, /* null required pointer, negative size, k<1, k>N, non-finite scale */
+    METEORA_ERR_UNSUPPORTED = 2, /* shape/dtype/alignment outside the limits above */
+    METEORA_ERR_WORKSPACE = 3,   /* ws is NULL or ws_bytes too small */
+    METEORA_ERR_HIP = 4          /* a HIP launch reported an error */
+} meteora_status;
+
+typedef enum { METEORA_F32 = 0, METEORA_BF16 = 1 } meteora_dtype;
+
+/* A hipStream_t, passed as an opaque pointer so that this header needs no HIP include. */
+typedef void* meteora_stream;
+
+/* Library version (major*10000 + minor*100 + patch).  Host only. */
+int meteora_version(void);
+
+/* Text for a status code.  Host only; returns a static string. */
+const char* meteora_status_string(meteora_status s);
+
+/*
+ * Scratch bytes needed by meteora_gate_topk, meteora_bucket_tokens,
+ * meteora_lora_forward and meteora_linear_forward for this problem size (the
+ * maximum over the four; entry points that take no d_out or r accept the
+ * value computed with any legal d_out, r, e.g. 8 and 1).
+ * Host only, no HIP call.  Returns 0 for arguments outside the limits.
+ */
+size_t meteora_workspace_bytes(int T, int d_in, int d_out, int N, int r, int k, meteora_dtype dt);
+
+/*
+ * Gate network and top-k routing (Sec. 3.1: G(x), I(x); Eq. 3).
+ *   logits[t,j]  = sum_i x[t,i] * W_gate[i,j] (+ gate_bias[j]), fp32 accumulation
+ *   topk_idx[t,:] = the k adapters with the largest logits, listed by descending
+ *                   logit, equal logits by ascending adapter index
+ *   topk_w[t,:]   = exp(g - g_max) / sum over the k selected (Eq. 3), fp32
+ * `logits` ([T,N] fp32) may be NULL if the caller does not want them.
+ * inv_temperature scales the selected logits inside the softmax only
+ * (1.0f = Eq. 3 as printed; 1/tau for the temperature of App. A.6).
+ */
+meteora_status meteora_gate_topk(const void* x, const float* W_gate, const float* gate_bias,
+                                 int T, int d_in, int N, int k, meteora_dtype dt,
+                                 float inv_temperature,
+                                 int32_t* topk_idx /*[T,k]*/, float* topk_w /*[T,k]*/,
+                                 float* logits /*[T,N] or NULL*/,
+                                 void* ws, size_t ws_bytes, meteora_stream stream);
+
+/*
+ * Token-to-adapter bucketing: the per-adapter token sets {x | i in I(x)} of
+ * Sec. 3.3 as index lists instead of gathered copies.
+ *   counts[j]  = number of (token, slot) pairs routed to adapter j
+ *   offsets    = exclusive prefix sum of counts, offsets[N] = T*k
+ *   bucket_tok / bucket_slot [offsets[j] .. offsets[j+1]) = the pairs of adapter
+ *                j, ordered by ascending token, then ascending slot (stable)
+ * topk_idx values must lie in [0, N).
+ */
+meteora_status meteora_bucket_tokens(const int32_t* topk_idx /*[T,k]*/, int T, int k, int N,
+                                     int32_t* counts /*[N]*/, int32_t* offsets /*[N+1]*/,
+                                     int32_t* bucket_tok /*[T*k]*/, int32_t* bucket_slot /*[T*k]*/,
+                                     void* ws, size_t ws_bytes, meteora_stream stream);
+
+/*
+ * LoRA term of Eq. 2 for a given routing:
+ *   delta[t,:] = scale * sum_j topk_w[t,j] * ((x[t,:] * A[a]) * B[a]),  a = topk_idx[t,j]
+ *   accumulate = 0: out = delta;  accumulate = 1: out = out + delta.
+ * Runs bucketing, the grouped shrink (h = x*A_a, fp32) and the grouped expand.
+ */
+meteora_status meteora_lora_forward(const void* x, const void* A, const void* B,
+                                    const int32_t* topk_idx, const float* topk_w,
+                                    int T, int d_in, int d_out, int N, int r, int k,
+                                    float scale, meteora_dtype dt,
+                                    void* out /*[T,d_out]*/, int accumulate,
+                                    void* ws, size_t ws_bytes, meteora_stream stream);
+
+/*
+ * Whole layer, Eq. 2: out = x*W + scale * sum_{i in I(x)} w_i * ((x*A_i)*B_i),
+ * with I(x), w from the gate as in meteora_gate_topk (inv_temperature = 1).
+ * If topk_idx_out / topk_w_out are not NULL they receive the routing used.
+ */
+meteora_status meteora_linear_forward(const void* x, const void* W, const float* W_gate,
+                                      const float* gate_bias, const void* A, const void* B,
+                                      int T, int d_in, int d_out, int N, int r, int k,
+                                      float scale, meteora_dtype dt,
+                                      void* out /*[T,d_out]*/,
+                                      int32_t* topk_idx_out /*[T,k] or NULL*/,
+                                      float* topk_w_out /*[T,k] or NULL*/,
+                                      void* ws, size_t ws_bytes, meteora_stream stream);
+
+/*
+ * Base projection alone, first term of Eq. 1 / Eq. 2: out = x * W
+ * (W stored [d_out, d_in]).  Exposed so the dense contraction can be checked
+ * and timed on its own.
+ */
+meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, int d_out,
+                                 meteora_dtype dt, void* out /*[T,d_out]*/, meteora_stream stream);
+
+/*
+ * Optional per-stage timing, for benchmarks.  Host only; off by default.
+ * While enabled, meteora_lora_forward and meteora_linear_forward record
+ * hipEvents on `stream` around each stage (gate_logits, gate_topk, bucket,
+ * shrink, gemm, expand) for up to 256 calls.  meteora_stage_timing_read waits
+ * for those events, returns per stage the summed milliseconds and the number
+ * of timed launches (arrays of meteora_stage_count() entries, host memory)
+ * and the number of calls covered, and starts a new window.  Not thread-safe;
+ * enable/disable must not race with other calls.
+ */
+int meteora_stage_count(void);
+const char* meteora_stage_name(int stage);
+meteora_status meteora_stage_timing_enable(int on);
+meteora_status meteora_stage_timing_read(float* ms_sum /*host*/, int* launches /*host*/, int* calls /*host*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* METEORA_H */

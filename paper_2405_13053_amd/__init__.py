@@ -1,0 +1,8 @@
+"""MI355X-native forward pass of the MeteoRA linear layer (paper Sec. 3.1, Eq. 2).
+
+The compute lives in libmeteora.so (hand-written HIP for gfx950, C ABI in
+include/meteora.h).  This package is only the argument-marshalling binding.
+"""
+from .binding import (MeteoraError, base_gemm, bucket_tokens, gate_topk, library_path,  # noqa: F401
+                      linear_forward, load_library, lora_forward, stage_timing_enable,
+                      stage_timing_read, workspace_bytes)

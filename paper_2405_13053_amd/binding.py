@@ -1,0 +1,223 @@
+"""ctypes binding of libmeteora.so: same names as the C ABI, argument marshalling only.
+
+PyTorch is used for device memory and the current stream; every step of the
+layer runs inside the library's HIP kernels.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmeteora.so")
+_lib = None
+
+F32, BF16 = 0, 1
+
+
+class MeteoraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().meteora_status_string(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libmeteora.so built in-tree; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} not found: build it first (python -m paper_2405_13053_amd.build "
+            "or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(_LIB_PATH)
+    c = ctypes
+    vp, i, f, sz = c.c_void_p, c.c_int, c.c_float, c.c_size_t
+    lib.meteora_version.restype = i
+    lib.meteora_status_string.restype = c.c_char_p
+    lib.meteora_status_string.argtypes = [i]
+    lib.meteora_workspace_bytes.restype = sz
+    lib.meteora_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    lib.meteora_gate_topk.restype = i
+    lib.meteora_gate_topk.argtypes = [vp, vp, vp, i, i, i, i, i, f, vp, vp, vp, vp, sz, vp]
+    lib.meteora_bucket_tokens.restype = i
+    lib.meteora_bucket_tokens.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp, sz, vp]
+    lib.meteora_lora_forward.restype = i
+    lib.meteora_lora_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp, i, vp, sz, vp]
+    lib.meteora_linear_forward.restype = i
+    lib.meteora_linear_forward.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp, vp, vp, vp, sz, vp]
+    lib.meteora_base_gemm.restype = i
+    lib.meteora_base_gemm.argtypes = [vp, vp, i, i, i, i, vp, vp]
+    lib.meteora_stage_count.restype = i
+    lib.meteora_stage_name.restype = c.c_char_p
+    lib.meteora_stage_name.argtypes = [i]
+    lib.meteora_stage_timing_enable.restype = i
+    lib.meteora_stage_timing_enable.argtypes = [i]
+    lib.meteora_stage_timing_read.restype = i
+    lib.meteora_stage_timing_read.argtypes = [vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _chk(t: Optional[torch.Tensor], name: str, dtype=None, shape=None):
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def workspace_bytes(T, d_in, d_out, N, r, k, dtype) -> int:
+    dt = BF16 if dtype in (torch.bfloat16, BF16, "bf16") else F32
+    return int(load_library().meteora_workspace_bytes(T, d_in, d_out, N, r, k, dt))
+
+
+def _ws(ws: Optional[torch.Tensor], need: int, device) -> torch.Tensor:
+    if ws is None:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return ws
+
+
+def gate_topk(x, W_gate, gate_bias, k: int, inv_temperature: float = 1.0, want_logits: bool = False,
+              ws: Optional[torch.Tensor] = None):
+    """meteora_gate_topk: returns (topk_idx[T,k] i32, topk_w[T,k] f32, logits[T,N] f32 or None)."""
+    T, d_in = x.shape
+    N = W_gate.shape[1]
+    _chk(x, "x"); _chk(W_gate, "W_gate", torch.float32, (d_in, N)); _chk(gate_bias, "gate_bias", torch.float32, (N,))
+    idx = torch.empty((T, k), dtype=torch.int32, device=x.device)
+    w = torch.empty((T, k), dtype=torch.float32, device=x.device)
+    logits = torch.empty((T, N), dtype=torch.float32, device=x.device) if want_logits else None
+    ws = _ws(ws, workspace_bytes(T, d_in, 8, N, 1, k, x.dtype), x.device)
+    st = load_library().meteora_gate_topk(_p(x), _p(W_gate), _p(gate_bias), T, d_in, N, k, _dt(x),
+                                          float(inv_temperature), _p(idx), _p(w), _p(logits), _p(ws),
+                                          ws.numel(), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_gate_topk")
+    return idx, w, logits
+
+
+def bucket_tokens(topk_idx, N: int, ws: Optional[torch.Tensor] = None):
+    """meteora_bucket_tokens: returns (counts[N], offsets[N+1], bucket_tok[T*k], bucket_slot[T*k])."""
+    _chk(topk_idx, "topk_idx", torch.int32)
+    T, k = topk_idx.shape
+    dev = topk_idx.device
+    counts = torch.empty(N, dtype=torch.int32, device=dev)
+    offsets = torch.empty(N + 1, dtype=torch.int32, device=dev)
+    tok = torch.empty(T * k, dtype=torch.int32, device=dev)
+    slot = torch.empty(T * k, dtype=torch.int32, device=dev)
+    ws = _ws(ws, workspace_bytes(T, 8, 8, N, 1, k, torch.float32), dev)
+    st = load_library().meteora_bucket_tokens(_p(topk_idx), T, k, N, _p(counts), _p(offsets), _p(tok), _p(slot),
+                                              _p(ws), ws.numel(), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_bucket_tokens")
+    return counts, offsets, tok, slot
+
+
+def lora_forward(x, A, B, topk_idx, topk_w, scale: float, out: Optional[torch.Tensor] = None,
+                 accumulate: bool = False, ws: Optional[torch.Tensor] = None):
+    """meteora_lora_forward: out (+)= scale * sum_j w_j (x A_j) B_j for the given routing."""
+    T, d_in = x.shape
+    N, _, r = A.shape
+    d_out = B.shape[2]
+    k = topk_idx.shape[1]
+    _chk(x, "x"); _chk(A, "A", x.dtype, (N, d_in, r)); _chk(B, "B", x.dtype, (N, r, d_out))
+    _chk(topk_idx, "topk_idx", torch.int32, (T, k)); _chk(topk_w, "topk_w", torch.float32, (T, k))
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing out")
+        out = torch.empty((T, d_out), dtype=x.dtype, device=x.device)
+    _chk(out, "out", x.dtype, (T, d_out))
+    ws = _ws(ws, workspace_bytes(T, d_in, d_out, N, r, k, x.dtype), x.device)
+    st = load_library().meteora_lora_forward(_p(x), _p(A), _p(B), _p(topk_idx), _p(topk_w), T, d_in, d_out, N,
+                                             r, k, float(scale), _dt(x), _p(out), int(bool(accumulate)), _p(ws),
+                                             ws.numel(), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_lora_forward")
+    return out
+
+
+def linear_forward(x, W, W_gate, gate_bias, A, B, k: int, scale: float, out: Optional[torch.Tensor] = None,
+                   ws: Optional[torch.Tensor] = None, return_routing: bool = False):
+    """meteora_linear_forward: the whole layer (Eq. 2)."""
+    T, d_in = x.shape
+    d_out = W.shape[0]
+    N, _, r = A.shape
+    _chk(x, "x"); _chk(W, "W", x.dtype, (d_out, d_in)); _chk(W_gate, "W_gate", torch.float32, (d_in, N))
+    _chk(gate_bias, "gate_bias", torch.float32, (N,))
+    _chk(A, "A", x.dtype, (N, d_in, r)); _chk(B, "B", x.dtype, (N, r, d_out))
+    if out is None:
+        out = torch.empty((T, d_out), dtype=x.dtype, device=x.device)
+    _chk(out, "out", x.dtype, (T, d_out))
+    idx = w = None
+    if return_routing:
+        idx = torch.empty((T, k), dtype=torch.int32, device=x.device)
+        w = torch.empty((T, k), dtype=torch.float32, device=x.device)
+    ws = _ws(ws, workspace_bytes(T, d_in, d_out, N, r, k, x.dtype), x.device)
+    st = load_library().meteora_linear_forward(_p(x), _p(W), _p(W_gate), _p(gate_bias), _p(A), _p(B), T, d_in,
+                                               d_out, N, r, k, float(scale), _dt(x), _p(out), _p(idx), _p(w),
+                                               _p(ws), ws.numel(), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_linear_forward")
+    return (out, idx, w) if return_routing else out
+
+
+def base_gemm(x, W, out: Optional[torch.Tensor] = None):
+    """meteora_base_gemm: out = x W^T (W stored [d_out, d_in])."""
+    T, d_in = x.shape
+    d_out = W.shape[0]
+    _chk(x, "x"); _chk(W, "W", x.dtype, (d_out, d_in))
+    if out is None:
+        out = torch.empty((T, d_out), dtype=x.dtype, device=x.device)
+    _chk(out, "out", x.dtype, (T, d_out))
+    st = load_library().meteora_base_gemm(_p(x), _p(W), T, d_in, d_out, _dt(x), _p(out), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_base_gemm")
+    return out
+
+
+def stage_timing_enable(on: bool) -> None:
+    """meteora_stage_timing_enable: record hipEvents around each stage of the next calls."""
+    st = load_library().meteora_stage_timing_enable(int(bool(on)))
+    if st != 0:
+        raise MeteoraError(st, "meteora_stage_timing_enable")
+
+
+def stage_timing_read():
+    """meteora_stage_timing_read: {stage: (ms_sum, launches)}, calls."""
+    lib = load_library()
+    n = lib.meteora_stage_count()
+    ms = (ctypes.c_float * n)()
+    launches = (ctypes.c_int * n)()
+    calls = ctypes.c_int(0)
+    st = lib.meteora_stage_timing_read(ms, launches, ctypes.byref(calls))
+    if st != 0:
+        raise MeteoraError(st, "meteora_stage_timing_read")
+    return {lib.meteora_stage_name(s).decode(): (float(ms[s]), int(launches[s])) for s in range(n)}, calls.value

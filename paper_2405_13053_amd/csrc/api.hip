@@ -1,0 +1,304 @@
+// C ABI of the library (declared in include/meteora.h): argument validation, workspace
+// carving and the launch sequence of each entry point.  No device memory is allocated here
+// and nothing synchronises with the host.
+#include <math.h>
+
+#include "../../include/meteora.h"
+#include "common.hpp"
+#include "kernels.hpp"
+
+using namespace meteora;
+
+namespace {
+
+struct WsLayout {
+    size_t wsplit, partials, chunk_counts, counts, offsets, bucket_tok, bucket_slot, topk_idx, topk_w, h32,
+        hdense, total;
+    int ext_stride;   // columns of hdense: N*r rounded up to 32
+};
+
+bool shape_ok(int T, int d_in, int d_out, int N, int r, int k) {
+    return T >= 0 && d_in >= 1 && d_out >= 1 && N >= 1 && r >= 1 && k >= 1 && k <= N;
+}
+
+bool shape_supported(int T, int d_in, int d_out, int N, int r, int k) {
+    return N <= kMaxAdapters && k <= kMaxTopK && r <= kMaxRank && d_in % 8 == 0 && d_out % 8 == 0 &&
+           (int64_t)T * k < (int64_t)INT32_MAX && (int64_t)T * (int64_t)(d_in > d_out ? d_in : d_out) < ((int64_t)1 << 40);
+}
+
+WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
+    (void)d_out;
+    WsLayout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const int NP = padded_adapters(N);
+    const size_t pairs = (size_t)T * k;
+    L.ext_stride = (int)align_up((size_t)N * r, 32);
+    L.wsplit = take(gate_wsplit_bytes(d_in, N, bf16));
+    L.partials = take((size_t)gate_kslices(d_in, bf16) * T * NP * sizeof(float));
+    L.chunk_counts = take((size_t)bucket_chunks((int64_t)pairs) * N * sizeof(int32_t));
+    L.counts = take((size_t)N * sizeof(int32_t));
+    L.offsets = take((size_t)(N + 1) * sizeof(int32_t));
+    L.bucket_tok = take(pairs * sizeof(int32_t));
+    L.bucket_slot = take(pairs * sizeof(int32_t));
+    L.topk_idx = take(pairs * sizeof(int32_t));
+    L.topk_w = take(pairs * sizeof(float));
+    L.h32 = take(pairs * r * sizeof(float));
+    L.hdense = take((size_t)T * L.ext_stride * sizeof(uint16_t));
+    L.total = off;
+    return L;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+template <typename T> T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+#define METEORA_HIP(expr)                              \
+    do {                                               \
+        if ((expr) != hipSuccess) return METEORA_ERR_HIP; \
+    } while (0)
+
+// ---- optional per-stage timing (off by default; hipEvents recorded between the launches) ----
+enum Stage { ST_GATE_LOGITS = 0, ST_GATE_TOPK, ST_BUCKET, ST_SHRINK, ST_GEMM, ST_EXPAND, ST_COUNT };
+constexpr int kTimingRing = 256;
+struct StageTiming {
+    bool on = false;
+    int calls = 0;
+    hipEvent_t ev[kTimingRing][ST_COUNT][2];
+    bool used[kTimingRing][ST_COUNT];
+} g_timing;
+
+struct StageScope {
+    int stage;
+    hipStream_t st;
+    int slot;
+    StageScope(int stage_, hipStream_t st_, int slot_) : stage(stage_), st(st_), slot(slot_) {
+        if (slot >= 0) { (void)hipEventRecord(g_timing.ev[slot][stage][0], st); }
+    }
+    ~StageScope() {
+        if (slot >= 0) { (void)hipEventRecord(g_timing.ev[slot][stage][1], st); g_timing.used[slot][stage] = true; }
+    }
+};
+
+int timing_begin_call() {
+    if (!g_timing.on || g_timing.calls >= kTimingRing) return -1;
+    return g_timing.calls++;
+}
+
+}  // namespace
+
+extern "C" {
+
+int meteora_stage_count(void) { return ST_COUNT; }
+
+const char* meteora_stage_name(int stage) {
+    static const char* names[ST_COUNT] = {"gate_logits", "gate_topk", "bucket", "shrink", "gemm", "expand"};
+    return (stage >= 0 && stage < ST_COUNT) ? names[stage] : "";
+}
+
+meteora_status meteora_stage_timing_enable(int on) {
+    if (on && !g_timing.on) {
+        for (int c = 0; c < kTimingRing; ++c)
+            for (int s = 0; s < ST_COUNT; ++s) {
+                METEORA_HIP(hipEventCreate(&g_timing.ev[c][s][0]));
+                METEORA_HIP(hipEventCreate(&g_timing.ev[c][s][1]));
+                g_timing.used[c][s] = false;
+            }
+        g_timing.calls = 0;
+        g_timing.on = true;
+    } else if (!on && g_timing.on) {
+        for (int c = 0; c < kTimingRing; ++c)
+            for (int s = 0; s < ST_COUNT; ++s) {
+                (void)hipEventDestroy(g_timing.ev[c][s][0]);
+                (void)hipEventDestroy(g_timing.ev[c][s][1]);
+            }
+        g_timing.on = false;
+    }
+    return METEORA_OK;
+}
+
+meteora_status meteora_stage_timing_read(float* ms_sum, int* launches, int* calls) {
+    if (!ms_sum || !launches || !calls) return METEORA_ERR_INVALID_ARG;
+    if (!g_timing.on) return METEORA_ERR_INVALID_ARG;
+    for (int s = 0; s < ST_COUNT; ++s) { ms_sum[s] = 0.f; launches[s] = 0; }
+    for (int c = 0; c < g_timing.calls; ++c)
+        for (int s = 0; s < ST_COUNT; ++s) {
+            if (!g_timing.used[c][s]) continue;
+            METEORA_HIP(hipEventSynchronize(g_timing.ev[c][s][1]));
+            float ms = 0.f;
+            METEORA_HIP(hipEventElapsedTime(&ms, g_timing.ev[c][s][0], g_timing.ev[c][s][1]));
+            ms_sum[s] += ms;
+            launches[s] += 1;
+            g_timing.used[c][s] = false;
+        }
+    *calls = g_timing.calls;
+    g_timing.calls = 0;
+    return METEORA_OK;
+}
+
+int meteora_version(void) { return 100; }
+
+const char* meteora_status_string(meteora_status s) {
+    switch (s) {
+        case METEORA_OK: return "ok";
+        case METEORA_ERR_INVALID_ARG: return "invalid argument";
+        case METEORA_ERR_UNSUPPORTED: return "unsupported shape, dtype or alignment";
+        case METEORA_ERR_WORKSPACE: return "workspace missing or too small";
+        case METEORA_ERR_HIP: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+size_t meteora_workspace_bytes(int T, int d_in, int d_out, int N, int r, int k, meteora_dtype dt) {
+    if (!shape_ok(T, d_in, d_out, N, r, k) || !shape_supported(T, d_in, d_out, N, r, k)) return 0;
+    if (dt != METEORA_F32 && dt != METEORA_BF16) return 0;
+    return ws_layout(T, d_in, d_out, N, r, k, dt == METEORA_BF16).total + 256;
+}
+
+meteora_status meteora_gate_topk(const void* x, const float* W_gate, const float* gate_bias, int T, int d_in,
+                                 int N, int k, meteora_dtype dt, float inv_temperature, int32_t* topk_idx,
+                                 float* topk_w, float* logits, void* ws, size_t ws_bytes,
+                                 meteora_stream stream) {
+    if (!x || !W_gate || !topk_idx || !topk_w) return METEORA_ERR_INVALID_ARG;
+    if (!shape_ok(T, d_in, 8, N, 1, k) || !isfinite(inv_temperature)) return METEORA_ERR_INVALID_ARG;
+    if (dt != METEORA_F32 && dt != METEORA_BF16) return METEORA_ERR_UNSUPPORTED;
+    if (!shape_supported(T, d_in, 8, N, 1, k)) return METEORA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(W_gate) || !aligned16(topk_idx) || !aligned16(topk_w) ||
+        (logits && !aligned16(logits)) || (gate_bias && !aligned4(gate_bias)))
+        return METEORA_ERR_UNSUPPORTED;
+    const bool bf16 = dt == METEORA_BF16;
+    const WsLayout L = ws_layout(T, d_in, 8, N, 1, k, bf16);
+    if (!ws || !aligned256(ws) || ws_bytes < L.chunk_counts) return METEORA_ERR_WORKSPACE;
+    if (T == 0) return METEORA_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* partials = at<float>(ws, L.partials);
+    METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, at<void>(ws, L.wsplit), partials, st));
+    METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, inv_temperature,
+                                 topk_idx, topk_w, logits, st));
+    return METEORA_OK;
+}
+
+meteora_status meteora_bucket_tokens(const int32_t* topk_idx, int T, int k, int N, int32_t* counts,
+                                     int32_t* offsets, int32_t* bucket_tok, int32_t* bucket_slot, void* ws,
+                                     size_t ws_bytes, meteora_stream stream) {
+    if (!topk_idx || !counts || !offsets || !bucket_tok || !bucket_slot) return METEORA_ERR_INVALID_ARG;
+    if (!shape_ok(T, 8, 8, N, 1, k)) return METEORA_ERR_INVALID_ARG;
+    if (!shape_supported(T, 8, 8, N, 1, k)) return METEORA_ERR_UNSUPPORTED;
+    if (!aligned16(topk_idx) || !aligned4(counts) || !aligned4(offsets) || !aligned16(bucket_tok) ||
+        !aligned16(bucket_slot))
+        return METEORA_ERR_UNSUPPORTED;
+    // only the chunk histograms live in the workspace; they sit at offset 0 for this entry point
+    const size_t need = (size_t)bucket_chunks((int64_t)T * k) * N * sizeof(int32_t);
+    if (!ws || !aligned256(ws) || ws_bytes < need) return METEORA_ERR_WORKSPACE;
+    if (T == 0) {
+        // nothing to enqueue; counts/offsets of an empty batch are left to the caller
+        return METEORA_OK;
+    }
+    METEORA_HIP(launch_bucket(topk_idx, T, k, N, static_cast<int32_t*>(ws), counts, offsets, bucket_tok,
+                              bucket_slot, static_cast<hipStream_t>(stream)));
+    return METEORA_OK;
+}
+
+static meteora_status check_lora_args(const void* x, const void* A, const void* B, int T, int d_in, int d_out,
+                                      int N, int r, int k, float scale, meteora_dtype dt, const void* out) {
+    if (!x || !A || !B || !out) return METEORA_ERR_INVALID_ARG;
+    if (!shape_ok(T, d_in, d_out, N, r, k) || !isfinite(scale)) return METEORA_ERR_INVALID_ARG;
+    if (dt != METEORA_F32 && dt != METEORA_BF16) return METEORA_ERR_UNSUPPORTED;
+    if (!shape_supported(T, d_in, d_out, N, r, k)) return METEORA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(A) || !aligned16(B) || !aligned16(out)) return METEORA_ERR_UNSUPPORTED;
+    return METEORA_OK;
+}
+
+// bucketing + shrink + expand on a given routing; shared by lora_forward and linear_forward
+static meteora_status run_lora(const void* x, const void* A, const void* B, const int32_t* topk_idx,
+                               const float* topk_w, int T, int d_in, int d_out, int N, int r, int k, float scale,
+                               bool bf16, void* out, int accumulate, void* ws, const WsLayout& L,
+                               hipStream_t st, int tslot) {
+    int32_t* offsets = at<int32_t>(ws, L.offsets);
+    int32_t* btok = at<int32_t>(ws, L.bucket_tok);
+    int32_t* bslot = at<int32_t>(ws, L.bucket_slot);
+    float* h32 = at<float>(ws, L.h32);
+    {
+        StageScope sc(ST_BUCKET, st, tslot);
+        METEORA_HIP(launch_bucket(topk_idx, T, k, N, at<int32_t>(ws, L.chunk_counts), at<int32_t>(ws, L.counts),
+                                  offsets, btok, bslot, st));
+    }
+    {
+        StageScope sc(ST_SHRINK, st, tslot);
+        METEORA_HIP(launch_shrink(x, A, topk_idx, topk_w, offsets, btok, bslot, T, d_in, N, r, k, scale, bf16,
+                                  h32, nullptr, L.ext_stride, st));
+    }
+    {
+        StageScope sc(ST_EXPAND, st, tslot);
+        METEORA_HIP(launch_expand(h32, B, topk_idx, topk_w, T, d_out, N, r, k, scale, bf16, out, accumulate, st));
+    }
+    return METEORA_OK;
+}
+
+meteora_status meteora_lora_forward(const void* x, const void* A, const void* B, const int32_t* topk_idx,
+                                    const float* topk_w, int T, int d_in, int d_out, int N, int r, int k,
+                                    float scale, meteora_dtype dt, void* out, int accumulate, void* ws,
+                                    size_t ws_bytes, meteora_stream stream) {
+    if (!topk_idx || !topk_w) return METEORA_ERR_INVALID_ARG;
+    if (accumulate != 0 && accumulate != 1) return METEORA_ERR_INVALID_ARG;
+    meteora_status s = check_lora_args(x, A, B, T, d_in, d_out, N, r, k, scale, dt, out);
+    if (s != METEORA_OK) return s;
+    if (!aligned16(topk_idx) || !aligned16(topk_w)) return METEORA_ERR_UNSUPPORTED;
+    const bool bf16 = dt == METEORA_BF16;
+    const WsLayout L = ws_layout(T, d_in, d_out, N, r, k, bf16);
+    if (!ws || !aligned256(ws) || ws_bytes < L.total) return METEORA_ERR_WORKSPACE;
+    if (T == 0) return METEORA_OK;
+    return run_lora(x, A, B, topk_idx, topk_w, T, d_in, d_out, N, r, k, scale, bf16, out, accumulate, ws, L,
+                    static_cast<hipStream_t>(stream), timing_begin_call());
+}
+
+meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, int d_out, meteora_dtype dt,
+                                 void* out, meteora_stream stream) {
+    if (!x || !W || !out) return METEORA_ERR_INVALID_ARG;
+    if (!shape_ok(T, d_in, d_out, 1, 1, 1)) return METEORA_ERR_INVALID_ARG;
+    if (dt != METEORA_F32 && dt != METEORA_BF16) return METEORA_ERR_UNSUPPORTED;
+    if (!shape_supported(T, d_in, d_out, 1, 1, 1)) return METEORA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(W) || !aligned16(out)) return METEORA_ERR_UNSUPPORTED;
+    if (T == 0) return METEORA_OK;
+    METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, dt == METEORA_BF16, nullptr, 0, nullptr, 0, out, 0,
+                            static_cast<hipStream_t>(stream)));
+    return METEORA_OK;
+}
+
+meteora_status meteora_linear_forward(const void* x, const void* W, const float* W_gate, const float* gate_bias,
+                                      const void* A, const void* B, int T, int d_in, int d_out, int N, int r,
+                                      int k, float scale, meteora_dtype dt, void* out, int32_t* topk_idx_out,
+                                      float* topk_w_out, void* ws, size_t ws_bytes, meteora_stream stream) {
+    if (!W || !W_gate) return METEORA_ERR_INVALID_ARG;
+    meteora_status s = check_lora_args(x, A, B, T, d_in, d_out, N, r, k, scale, dt, out);
+    if (s != METEORA_OK) return s;
+    if (!aligned16(W) || !aligned16(W_gate) || (gate_bias && !aligned4(gate_bias)) ||
+        (topk_idx_out && !aligned16(topk_idx_out)) || (topk_w_out && !aligned16(topk_w_out)))
+        return METEORA_ERR_UNSUPPORTED;
+    const bool bf16 = dt == METEORA_BF16;
+    const WsLayout L = ws_layout(T, d_in, d_out, N, r, k, bf16);
+    if (!ws || !aligned256(ws) || ws_bytes < L.total) return METEORA_ERR_WORKSPACE;
+    if (T == 0) return METEORA_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t* idx = topk_idx_out ? topk_idx_out : at<int32_t>(ws, L.topk_idx);
+    float* w = topk_w_out ? topk_w_out : at<float>(ws, L.topk_w);
+    float* partials = at<float>(ws, L.partials);
+    const int tslot = timing_begin_call();
+    {
+        StageScope sc(ST_GATE_LOGITS, st, tslot);
+        METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, at<void>(ws, L.wsplit), partials, st));
+    }
+    {
+        StageScope sc(ST_GATE_TOPK, st, tslot);
+        METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, 1.0f, idx, w,
+                                     nullptr, st));
+    }
+    {
+        StageScope sc(ST_GEMM, st, tslot);
+        METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, bf16, nullptr, 0, nullptr, 0, out, 0, st));
+    }
+    return run_lora(x, A, B, idx, w, T, d_in, d_out, N, r, k, scale, bf16, out, 1, ws, L, st, tslot);
+}
+
+}  // extern "C"

@@ -1,0 +1,126 @@
+// Token-to-adapter bucketing: the per-adapter token sets {x | i in I(x)} of the paper's
+// Sec. 3.3 (the X_i that "loop-original" gathers), kept as index lists instead of copies.
+//
+// The (token, slot) pairs, in flat order p = t*k + slot, are counting-sorted by adapter:
+//   pass 1  per-chunk histograms               chunk_counts[c][j]
+//   pass 2  every chunk derives its own write base from chunk_counts (exclusive scan over
+//           adapters of the totals + counts of the earlier chunks), then scatters its pairs
+//           in order.  The in-chunk rank uses wavefront ballots, so the result is the stable
+//           sort: ascending token, then ascending slot, inside every bucket.
+// Integer work only; the output is unique and bit-comparable.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace meteora {
+
+__global__ __launch_bounds__(256) void bucket_hist_kernel(const int32_t* __restrict__ topk_idx,
+                                                          int64_t pairs, int N,
+                                                          int32_t* __restrict__ chunk_counts) {
+    __shared__ int hist[kMaxAdapters];
+    if (threadIdx.x < kMaxAdapters) hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kBucketChunkPairs;
+    for (int i = threadIdx.x; i < kBucketChunkPairs; i += 256) {
+        const int64_t p = base + i;
+        if (p < pairs) {
+            const int key = topk_idx[p];
+            if (key >= 0 && key < N) atomicAdd(&hist[key], 1);   // out-of-range ids are dropped, never indexed
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < N) chunk_counts[(size_t)blockIdx.x * N + threadIdx.x] = hist[threadIdx.x];
+}
+
+__global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __restrict__ topk_idx,
+                                                             int64_t pairs, int k, int N, int nchunks,
+                                                             const int32_t* __restrict__ chunk_counts,
+                                                             int32_t* __restrict__ counts,
+                                                             int32_t* __restrict__ offsets,
+                                                             int32_t* __restrict__ bucket_tok,
+                                                             int32_t* __restrict__ bucket_slot) {
+    __shared__ int total[kMaxAdapters];      // pairs of adapter j over all chunks
+    __shared__ int before[kMaxAdapters];     // pairs of adapter j in earlier chunks
+    __shared__ int running[kMaxAdapters];    // next write position of adapter j for this chunk
+    __shared__ int wave_hist[4][kMaxAdapters];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = blockIdx.x;
+
+    if (threadIdx.x < kMaxAdapters) {
+        int tot = 0, bef = 0;
+        if (threadIdx.x < N) {
+            for (int cc = 0; cc < nchunks; ++cc) {
+                const int v = chunk_counts[(size_t)cc * N + threadIdx.x];
+                tot += v;
+                if (cc < c) bef += v;
+            }
+        }
+        total[threadIdx.x] = tot;
+        before[threadIdx.x] = bef;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // exclusive scan of total[] over adapters inside one wavefront
+        const int v = total[lane];
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int n = __shfl_up(incl, off);
+            if (lane >= off) incl += n;
+        }
+        const int excl = incl - v;
+        running[lane] = excl + before[lane];
+        if (c == 0) {
+            if (lane < N) { counts[lane] = v; offsets[lane] = excl; }
+            if (lane == N - 1) offsets[N] = incl;
+        }
+    }
+    __syncthreads();
+
+    const int64_t base = (int64_t)c * kBucketChunkPairs;
+    for (int it = 0; it < kBucketChunkPairs / 256; ++it) {
+        const int64_t p = base + it * 256 + threadIdx.x;
+        int key = (p < pairs) ? topk_idx[p] : -1;
+        if (key >= N) key = -1;
+        const bool valid = key >= 0;
+        // lanes of this wavefront that hold the same key
+        unsigned long long peers = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 6; ++bit) {
+            const unsigned long long b = __ballot(valid && ((key >> bit) & 1));
+            peers &= ((key >> bit) & 1) ? b : ~b;
+        }
+        const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        const int rank_in_wave = __popcll(peers & below);
+        const int peers_in_wave = __popcll(peers);
+        wave_hist[wave][lane] = 0;
+        __syncthreads();   // wave_hist cleared (each wave clears its own row; sync orders vs. last round's reads)
+        if (valid && rank_in_wave == 0) wave_hist[wave][key] = peers_in_wave;
+        __syncthreads();
+        if (valid) {
+            int pos = running[key] + rank_in_wave;
+            for (int w = 0; w < wave; ++w) pos += wave_hist[w][key];
+            bucket_tok[pos] = (int32_t)(p / k);
+            bucket_slot[pos] = (int32_t)(p % k);
+        }
+        __syncthreads();
+        if (threadIdx.x < kMaxAdapters)
+            running[threadIdx.x] += wave_hist[0][threadIdx.x] + wave_hist[1][threadIdx.x] +
+                                    wave_hist[2][threadIdx.x] + wave_hist[3][threadIdx.x];
+        __syncthreads();
+    }
+}
+
+hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* chunk_counts,
+                         int32_t* counts, int32_t* offsets, int32_t* bucket_tok, int32_t* bucket_slot,
+                         hipStream_t stream) {
+    const int64_t pairs = (int64_t)T * k;
+    const int nchunks = bucket_chunks(pairs);
+    bucket_hist_kernel<<<nchunks, 256, 0, stream>>>(topk_idx, pairs, N, chunk_counts);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    bucket_scatter_kernel<<<nchunks, 256, 0, stream>>>(topk_idx, pairs, k, N, nchunks, chunk_counts, counts,
+                                                       offsets, bucket_tok, bucket_slot);
+    return hipGetLastError();
+}
+
+}  // namespace meteora

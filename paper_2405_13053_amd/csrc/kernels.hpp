@@ -1,0 +1,50 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher only enqueues work
+// on `stream`; none allocates or synchronises.  Shapes have been validated by
+// the C-ABI layer before a launcher is called.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace meteora {
+
+// ---- gate (Sec. 3.1: G(x), I(x), Eq. 3) ------------------------------------------------
+// Number of K-slices the logit kernel splits d_in into (partials[KS][T][NP]).
+int gate_kslices(int d_in, bool bf16);
+// bytes of the split-bf16 copy of W_gate the MFMA logit kernel reads (0 for fp32 inputs)
+size_t gate_wsplit_bytes(int d_in, int N, bool bf16);
+hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_in, int N, bool bf16,
+                              void* wsplit, float* partials, hipStream_t stream);
+hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, int T, int N, int k,
+                            float inv_temperature, int32_t* topk_idx, float* topk_w, float* logits,
+                            hipStream_t stream);
+
+// ---- bucketing (Sec. 3.3: per-adapter token sets as index lists) --------------------------
+constexpr int kBucketChunkPairs = 1024;  // (token,slot) pairs handled by one workgroup
+inline int bucket_chunks(int64_t pairs) { return (int)((pairs + kBucketChunkPairs - 1) / kBucketChunkPairs); }
+hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* chunk_counts,
+                         int32_t* counts, int32_t* offsets, int32_t* bucket_tok, int32_t* bucket_slot,
+                         hipStream_t stream);
+
+// ---- grouped LoRA shrink: h[t,slot,:] = x[t,:] * A[idx[t,slot]] ---------------------------
+// h32 ([T,k,r] fp32) and/or hdense (bf16 [T, ext_stride], column idx*r+q = scale*w*h, other
+// columns zero) are written; either may be NULL.
+hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, const float* topk_w,
+                         const int32_t* offsets, const int32_t* bucket_tok, const int32_t* bucket_slot,
+                         int T, int d_in, int N, int r, int k, float scale, bool bf16,
+                         float* h32, void* hdense, int ext_stride, hipStream_t stream);
+
+// ---- grouped LoRA expand: out (+)= scale * sum_slot w * h[t,slot,:] * B[idx[t,slot]] ------
+hipError_t launch_expand(const float* h32, const void* B, const int32_t* topk_idx, const float* topk_w,
+                         int T, int d_out, int N, int r, int k, float scale, bool bf16, void* out,
+                         int accumulate, hipStream_t stream);
+
+// ---- base projection out = x * W^T (W stored [d_out, d_in]), optional fused LoRA expand ---
+// If hdense != NULL the contraction is extended by the columns of hdense against B viewed as
+// [N*r, d_out] (out += hdense * B), i.e. the LoRA expand runs in the same accumulators.
+// d_in may be 0 (expand only); accumulate=1 adds the previous contents of out.
+hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out, bool bf16,
+                       const void* hdense, int ext_stride, const void* B, int ext_k,
+                       void* out, int accumulate, hipStream_t stream);
+
+}  // namespace meteora

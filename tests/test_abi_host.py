@@ -1,0 +1,126 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes workspaces, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2405_13053_amd as m
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, INVALID, UNSUPPORTED, WORKSPACE, HIP = range(5)
+F32, BF16 = 0, 1
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return m.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "meteora.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = sorted(set(re.findall(r"\b(meteora_[a-z_0-9]+)\s*\(", hdr)))
+    assert {"meteora_gate_topk", "meteora_bucket_tokens", "meteora_lora_forward", "meteora_linear_forward",
+            "meteora_base_gemm", "meteora_workspace_bytes"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in meteora.h but not exported"
+
+
+def test_version_and_status_strings(lib):
+    assert lib.meteora_version() >= 100
+    texts = {lib.meteora_status_string(s) for s in range(5)}
+    assert len(texts) == 5
+
+
+def test_workspace_bytes(lib):
+    w = m.workspace_bytes(4096, 4096, 4096, 28, 8, 2, "bf16")
+    assert w > 0 and w % 256 == 0
+    assert m.workspace_bytes(8192, 4096, 4096, 28, 8, 2, "bf16") > w
+    assert m.workspace_bytes(0, 4096, 4096, 28, 8, 2, "bf16") > 0            # T = 0 is legal
+    assert m.workspace_bytes(64, 256, 256, 4, 8, 5, "f32") == 0              # k > N
+    assert m.workspace_bytes(64, 250, 256, 4, 8, 2, "f32") == 0              # d_in % 8
+    assert m.workspace_bytes(64, 256, 256, 65, 8, 2, "f32") == 0             # N > 64
+    assert lib.meteora_workspace_bytes(64, 256, 256, 4, 8, 2, 7) == 0        # unknown dtype
+
+
+# Fake, suitably aligned, never-dereferenced addresses: validation must reject before any launch.
+P = ctypes.c_void_p(0x10000)
+ODD = ctypes.c_void_p(0x10004)
+WS = ctypes.c_void_p(0x100000)
+BIG = 1 << 30
+
+
+def gate(lib, x=P, Wg=P, bias=None, T=64, d=256, N=4, k=2, dt=F32, it=1.0, idx=P, w=P, lg=None, ws=WS, wsb=BIG):
+    return lib.meteora_gate_topk(x, Wg, bias, T, d, N, k, dt, it, idx, w, lg, ws, wsb, None)
+
+
+def test_gate_topk_validation(lib):
+    assert gate(lib, x=None) == INVALID
+    assert gate(lib, idx=None) == INVALID
+    assert gate(lib, k=0) == INVALID
+    assert gate(lib, k=5) == INVALID            # k > N
+    assert gate(lib, T=-1) == INVALID
+    assert gate(lib, it=float("nan")) == INVALID
+    assert gate(lib, dt=3) == UNSUPPORTED
+    assert gate(lib, d=250) == UNSUPPORTED
+    assert gate(lib, N=65, k=2) == UNSUPPORTED
+    assert gate(lib, N=16, k=9) == UNSUPPORTED
+    assert gate(lib, x=ODD) == UNSUPPORTED
+    assert gate(lib, ws=None) == WORKSPACE
+    assert gate(lib, wsb=16) == WORKSPACE
+    assert gate(lib, T=0) == OK                 # empty batch: nothing enqueued
+
+
+def test_bucket_validation(lib):
+    f = lambda idx=P, T=64, k=2, N=4, c=P, o=P, bt=P, bs=P, ws=WS, wsb=BIG: \
+        lib.meteora_bucket_tokens(idx, T, k, N, c, o, bt, bs, ws, wsb, None)
+    assert f(idx=None) == INVALID
+    assert f(c=None) == INVALID
+    assert f(k=5) == INVALID
+    assert f(N=100, k=2) == UNSUPPORTED
+    assert f(ws=None) == WORKSPACE
+    assert f(wsb=0) == WORKSPACE
+    assert f(T=0) == OK
+
+
+def test_lora_and_linear_validation(lib):
+    def lora(x=P, A=P, B=P, idx=P, w=P, T=64, di=256, do=256, N=4, r=8, k=2, s=2.0, dt=F32, out=P, acc=0,
+             ws=WS, wsb=BIG):
+        return lib.meteora_lora_forward(x, A, B, idx, w, T, di, do, N, r, k, s, dt, out, acc, ws, wsb, None)
+
+    def lin(x=P, W=P, Wg=P, bias=None, A=P, B=P, T=64, di=256, do=256, N=4, r=8, k=2, s=2.0, dt=BF16, out=P,
+            io=None, wo=None, ws=WS, wsb=BIG):
+        return lib.meteora_linear_forward(x, W, Wg, bias, A, B, T, di, do, N, r, k, s, dt, out, io, wo, ws, wsb,
+                                          None)
+
+    for f in (lora, lin):
+        assert f(x=None) == INVALID
+        assert f(out=None) == INVALID
+        assert f(k=0) == INVALID
+        assert f(k=5) == INVALID
+        assert f(r=0) == INVALID
+        assert f(s=float("inf")) == INVALID
+        assert f(do=100) == UNSUPPORTED
+        assert f(r=65) == UNSUPPORTED
+        assert f(dt=9) == UNSUPPORTED
+        assert f(A=ODD) == UNSUPPORTED
+        assert f(ws=None) == WORKSPACE
+        assert f(wsb=1024) == WORKSPACE
+        assert f(T=0) == OK
+    assert lora(idx=None) == INVALID
+    assert lora(acc=2) == INVALID
+    assert lin(W=None) == INVALID
+    assert lin(Wg=None) == INVALID
+    need = m.workspace_bytes(64, 256, 256, 4, 8, 2, "bf16")
+    assert lin(wsb=need - 512) == WORKSPACE
+
+
+def test_base_gemm_validation(lib):
+    f = lambda x=P, W=P, T=64, di=256, do=256, dt=BF16, out=P: lib.meteora_base_gemm(x, W, T, di, do, dt, out, None)
+    assert f(x=None) == INVALID and f(W=None) == INVALID and f(out=None) == INVALID
+    assert f(T=-2) == INVALID
+    assert f(di=12) == UNSUPPORTED
+    assert f(dt=2) == UNSUPPORTED
+    assert f(T=0) == OK

@@ -1,0 +1,239 @@
+"""GPU parity: the HIP library, called through its C ABI (ctypes binding), against the CPU oracle.
+
+Bars: routing (top-k indices) and bucketing bit-exact; gate weights within 1e-6; outputs within
+max|y - y_ref| / max|y_ref| <= 5e-3 (bf16 storage, fp32 accumulation) or 1e-5 (fp32).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2405_13053_amd as m
+from gen import inputs as gen
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+LS = gen.LayerShape
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+# ------------------------------------------------------------------------------ gate / routing
+GATE_SHAPES = [
+    LS(64, 256, 256, 4, 8, 2, 2.0, "f32", "uniform", "cfg1"),
+    LS(257, 1024, 64, 28, 8, 2, 2.0, "bf16", "uniform", "ragged-T"),
+    LS(1000, 4096, 64, 28, 8, 2, 2.0, "bf16", "zipf", "zipf"),
+    LS(130, 520, 64, 37, 8, 3, 2.0, "bf16", "uniform", "N>32,odd-K"),
+    LS(96, 5120, 64, 64, 8, 8, 2.0, "bf16", "uniform", "N=64,k=8"),
+    LS(33, 264, 64, 5, 8, 1, 2.0, "f32", "zipf", "top1"),
+    LS(1, 4096, 64, 28, 8, 2, 2.0, "bf16", "uniform", "T=1"),
+]
+
+
+@pytest.mark.parametrize("shape", GATE_SHAPES, ids=lambda s: s.name)
+def test_gate_topk_matches_oracle(shape):
+    ops, dev = util.make_case(shape, seed=11)
+    g64, g32, idx_ref, w_ref = util.oracle_routing(ops, shape.k)
+    idx, w, logits = m.gate_topk(dev["x"], dev["W_gate"], dev["bias"], shape.k, want_logits=True)
+    torch.cuda.synchronize()
+    idx, w, logits = _np(idx), _np(w), _np(logits)
+    # (1) logit accuracy: fp32 accumulation noise, scaled by the sum of |terms|
+    mag = np.abs(ops["x"].astype(np.float64)) @ np.abs(ops["W_gate"].astype(np.float64))
+    if ops["bias"] is not None:
+        mag = mag + np.abs(ops["bias"].astype(np.float64))
+    assert np.all(np.abs(logits - g64) <= 8 * 2.0 ** -24 * mag + 1e-30)
+    # (2) selection logic on the GPU's own logits: zero tolerance
+    idx_self, w_self = oracle.topk_softmax(logits, shape.k)
+    assert np.array_equal(idx, idx_self)
+    np.testing.assert_allclose(w, w_self, rtol=0, atol=1e-6)
+    # (3) routing equals the oracle's, bit-exact (inputs are margin-conditioned)
+    assert np.array_equal(idx, idx_ref)
+    # (4) Eq. 3 weights
+    np.testing.assert_allclose(w, w_ref, rtol=0, atol=1e-6)
+    np.testing.assert_allclose(w.sum(axis=1), 1.0, rtol=0, atol=1e-6)
+    assert np.all(w > 0)
+
+
+def test_gate_selection_logic_on_unconditioned_inputs():
+    """Near ties are allowed to resolve either way vs. fp64, but never against the GPU's own logits."""
+    shape = LS(3000, 512, 64, 28, 8, 2, 2.0, "bf16")
+    ops, dev = util.make_case(shape, seed=5, condition=False)
+    idx, w, logits = m.gate_topk(dev["x"], dev["W_gate"], None, 2, want_logits=True)
+    idx_self, _ = oracle.topk_softmax(_np(logits), 2)
+    assert np.array_equal(_np(idx), idx_self)
+
+
+def test_gate_exact_ties_lowest_index_first():
+    shape = LS(200, 512, 64, 12, 8, 4, 2.0, "bf16")
+    ops, dev = util.make_case(shape, seed=6, condition=False)
+    Wg = ops["W_gate"].copy()
+    Wg[:, 7] = Wg[:, 2]          # identical columns -> bit-identical logits in any summation order
+    Wg[:, 9] = Wg[:, 2]
+    idx, w, logits = m.gate_topk(dev["x"], util.to_dev(Wg, torch.float32), None, 4, want_logits=True)
+    logits = _np(logits)
+    assert np.array_equal(logits[:, 2], logits[:, 7]) and np.array_equal(logits[:, 2], logits[:, 9])
+    idx_self, _ = oracle.topk_softmax(logits, 4)
+    assert np.array_equal(_np(idx), idx_self)
+    # all-zero gate with k = N: every logit ties, order is 0..N-1 and w = 1/N
+    z = torch.zeros((512, 12), dtype=torch.float32, device="cuda")
+    idx, w, _ = m.gate_topk(dev["x"], z, None, 8)
+    assert np.array_equal(_np(idx), np.tile(np.arange(8, dtype=np.int32), (200, 1)))
+    np.testing.assert_allclose(_np(w), 1.0 / 8, rtol=0, atol=1e-7)
+
+
+def test_gate_temperature():
+    shape = LS(100, 256, 64, 6, 8, 2, 2.0, "f32")
+    ops, dev = util.make_case(shape, seed=7)
+    idx, w, logits = m.gate_topk(dev["x"], dev["W_gate"], None, 2, inv_temperature=1 / 15.0, want_logits=True)
+    idx_ref, w_ref = oracle.topk_softmax(_np(logits), 2, temperature=15.0)
+    assert np.array_equal(_np(idx), idx_ref)
+    np.testing.assert_allclose(_np(w), w_ref, rtol=0, atol=1e-6)
+
+
+# ------------------------------------------------------------------------------------ bucketing
+@pytest.mark.parametrize("T,k,N,mode", [(64, 2, 4, "uniform"), (4096, 2, 28, "uniform"), (8192, 2, 28, "zipf"),
+                                        (1023, 3, 64, "uniform"), (513, 1, 7, "one-bucket"), (1, 2, 28, "uniform"),
+                                        (16384, 2, 28, "zipf"), (700, 8, 9, "uniform")])
+def test_bucket_tokens_bit_exact(T, k, N, mode):
+    rng = np.random.default_rng(T * 131 + k)
+    if mode == "one-bucket":
+        idx = np.full((T, k), 3, dtype=np.int32)
+    else:
+        # k distinct adapters per token, drawn with probabilities p (Gumbel top-k)
+        p = 1.0 / (np.arange(N) + 1.0) ** 2 if mode == "zipf" else np.ones(N)
+        scores = np.log(p)[None, :] + rng.gumbel(size=(T, N))
+        idx = np.argsort(-scores, axis=1)[:, :k].astype(np.int32)
+    c_ref, o_ref, tok_ref, slot_ref = oracle.bucket(idx, N)
+    c, o, tok, slot = m.bucket_tokens(torch.from_numpy(idx).cuda(), N)
+    assert np.array_equal(_np(c), c_ref)
+    assert np.array_equal(_np(o), o_ref)
+    assert np.array_equal(_np(tok), tok_ref)
+    assert np.array_equal(_np(slot), slot_ref)
+    assert int(_np(c).sum()) == T * k
+
+
+# ------------------------------------------------------------------------------------ LoRA term
+LORA_SHAPES = [
+    LS(64, 256, 256, 4, 8, 2, 2.0, "f32", "uniform", "cfg1"),
+    LS(300, 512, 1032, 28, 8, 2, 2.0, "bf16", "uniform", "bf16-r8"),
+    LS(517, 1024, 520, 28, 16, 2, 2.0, "bf16", "zipf", "bf16-r16-zipf"),
+    LS(70, 264, 136, 6, 5, 3, 0.5, "bf16", "uniform", "odd-r"),
+    LS(40, 128, 64, 3, 64, 1, 1.0, "f32", "uniform", "r64-top1"),
+]
+
+
+@pytest.mark.parametrize("shape", LORA_SHAPES, ids=lambda s: s.name)
+def test_lora_forward_matches_oracle(shape):
+    ops, dev = util.make_case(shape, seed=21)
+    _, _, idx_ref, w_ref = util.oracle_routing(ops, shape.k)
+    delta_ref = oracle.lora_delta(ops["x"], ops["A"], ops["B"], idx_ref, w_ref, shape.scale)
+    idx_d = torch.from_numpy(idx_ref).cuda()
+    w_d = torch.from_numpy(w_ref.astype(np.float32)).cuda()
+    out = m.lora_forward(dev["x"], dev["A"], dev["B"], idx_d, w_d, shape.scale)
+    assert util.rel_max_err(out, delta_ref) <= util.tol(shape)
+    # accumulate=1 on top of the base projection
+    base_ref = oracle.base(ops["x"], ops["W"])
+    out2 = util.to_dev(base_ref.astype(np.float32), util.torch_dtype(shape))
+    base_stored = out2.to(torch.float64).cpu().numpy()
+    m.lora_forward(dev["x"], dev["A"], dev["B"], idx_d, w_d, shape.scale, out=out2, accumulate=True)
+    assert util.rel_max_err(out2, base_stored + delta_ref) <= util.tol(shape)
+
+
+# --------------------------------------------------------------------------------- base GEMM
+@pytest.mark.parametrize("T,d_in,d_out,dtype", [(64, 256, 256, "f32"), (300, 520, 264, "bf16"),
+                                                (1024, 1024, 1024, "bf16"), (17, 4096, 72, "bf16")])
+def test_base_gemm_matches_oracle(T, d_in, d_out, dtype):
+    shape = LS(T, d_in, d_out, 2, 2, 1, 1.0, dtype)
+    ops, dev = util.make_case(shape, seed=31, condition=False)
+    out = m.base_gemm(dev["x"], dev["W"])
+    assert util.rel_max_err(out, oracle.base(ops["x"], ops["W"])) <= util.tol(shape)
+
+
+# --------------------------------------------------------------------------------- whole layer
+LAYER_SHAPES = [
+    LS(64, 256, 256, 4, 8, 2, 2.0, "f32", "uniform", "cfg1"),
+    LS(333, 512, 776, 28, 8, 2, 2.0, "bf16", "uniform", "bf16-ragged"),
+    LS(512, 1024, 512, 28, 16, 2, 2.0, "bf16", "zipf", "bf16-r16-zipf"),
+    LS(50, 264, 136, 7, 5, 3, 1.5, "f32", "uniform", "f32-odd"),
+    LS(100, 512, 256, 28, 8, 1, 2.0, "bf16", "uniform", "top1"),
+]
+
+
+def _check_layer(shape, seed, layer=0, rows="all", n_strided=256):
+    ops, dev = util.make_case(shape, seed, layer)
+    _, _, idx_ref, w_ref = util.oracle_routing(ops, shape.k)
+    out, idx, w = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], dev["bias"], dev["A"], dev["B"], shape.k,
+                                   shape.scale, return_routing=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(_np(idx), idx_ref), "routing differs from the oracle"
+    np.testing.assert_allclose(_np(w), w_ref, rtol=0, atol=1e-6)
+    if rows == "all":
+        sel = None
+        y_gpu = out
+    else:
+        c, o, tok, _ = oracle.bucket(idx_ref, shape.N)
+        sel = util.sample_rows(shape.T, c, o, tok, n_strided=n_strided)
+        y_gpu = out[torch.from_numpy(sel.astype(np.int64)).cuda()]
+    ref = oracle.linear_forward(ops["x"], ops["W"], ops["W_gate"], ops["bias"], ops["A"], ops["B"], shape.k,
+                                shape.scale, rows=sel)
+    err = util.rel_max_err(y_gpu, ref["y"])
+    assert err <= util.tol(shape), f"{shape.name}: rel err {err:.3e}"
+    return out
+
+
+@pytest.mark.parametrize("shape", LAYER_SHAPES, ids=lambda s: s.name)
+def test_linear_forward_matches_oracle(shape):
+    _check_layer(shape, seed=41)
+
+
+def test_linear_forward_zero_B_is_base_and_deterministic():
+    shape = LS(200, 512, 520, 28, 8, 2, 2.0, "bf16")
+    ops, dev = util.make_case(shape, seed=42)
+    zB = torch.zeros_like(dev["B"])
+    y0 = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], None, dev["A"], zB, 2, 2.0)
+    yb = m.base_gemm(dev["x"], dev["W"])
+    assert torch.equal(y0, yb)
+    y1 = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], None, dev["A"], dev["B"], 2, 2.0)
+    y2 = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], None, dev["A"], dev["B"], 2, 2.0)
+    assert torch.equal(y1, y2)
+
+
+def test_linear_forward_single_adapter_is_merged_gemm():
+    """N=1,k=1: the layer is x(W + s*A*B) (Eq. 1)."""
+    shape = LS(100, 256, 264, 1, 8, 1, 2.0, "f32")
+    ops, dev = util.make_case(shape, seed=43, condition=False)
+    y = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], None, dev["A"], dev["B"], 1, 2.0)
+    merged = ops["W"].astype(np.float64).T + 2.0 * ops["A"][0].astype(np.float64) @ ops["B"][0].astype(np.float64)
+    assert util.rel_max_err(y, ops["x"].astype(np.float64) @ merged) <= 1e-5
+
+
+# --------------------------------------------------- the seeded configurations at their full sizes
+def test_config1_tiny_fp32_all_rows():
+    seed, layers = gen.config_layers(1)
+    _check_layer(layers[0], seed)
+
+
+def test_config2_q_proj_prefill_sampled_rows():
+    seed, layers = gen.config_layers(2)
+    _check_layer(layers[0], seed, rows="sample")
+
+
+def test_config4_decode_all_rows():
+    seed, layers = gen.config_layers(4)
+    for li, shape in enumerate(layers):
+        _check_layer(shape, seed, li)
+
+
+@pytest.mark.parametrize("li", [0, 2])
+def test_config3_mlp_zipf_sampled_rows(li):
+    seed, layers = gen.config_layers(3)
+    _check_layer(layers[li], seed, li, rows="sample", n_strided=64)
+
+
+@pytest.mark.parametrize("li", [0, 1, 4, 6])
+def test_config5_block_sampled_rows(li):
+    seed, layers = gen.config_layers(5)
+    _check_layer(layers[li], seed, li, rows="sample", n_strided=48)
