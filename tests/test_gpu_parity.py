@@ -51,8 +51,9 @@ def test_gate_topk_matches_oracle(shape):
     np.testing.assert_allclose(w, w_self, rtol=0, atol=1e-6)
     # (3) routing equals the oracle's, bit-exact (inputs are margin-conditioned)
     assert np.array_equal(idx, idx_ref)
-    # (4) Eq. 3 weights
-    np.testing.assert_allclose(w, w_ref, rtol=0, atol=1e-6)
+    # (4) Eq. 3 weights vs the oracle's: d(softmax)/d(logit) <= 1/4 per logit, so the logit noise of (1)
+    #     moves a weight by at most half the largest logit deviation, on top of the 1e-6 of (2)
+    np.testing.assert_allclose(w, w_ref, rtol=0, atol=1e-6 + 0.5 * float(np.abs(logits - g32).max()))
     np.testing.assert_allclose(w.sum(axis=1), 1.0, rtol=0, atol=1e-6)
     assert np.all(w > 0)
 
@@ -169,7 +170,9 @@ def _check_layer(shape, seed, layer=0, rows="all", n_strided=256):
                                    shape.scale, return_routing=True)
     torch.cuda.synchronize()
     assert np.array_equal(_np(idx), idx_ref), "routing differs from the oracle"
-    np.testing.assert_allclose(_np(w), w_ref, rtol=0, atol=1e-6)
+    # weights: 1e-6 for the softmax arithmetic plus half the fp32 logit noise (see the gate test), which
+    # stays below 1e-5 for logits of O(1) summed over <= 14336 terms
+    np.testing.assert_allclose(_np(w), w_ref, rtol=0, atol=1e-5)
     if rows == "all":
         sel = None
         y_gpu = out
