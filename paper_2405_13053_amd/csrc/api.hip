@@ -210,8 +210,9 @@ static meteora_status check_lora_args(const void* x, const void* A, const void* 
     return METEORA_OK;
 }
 
-// bucketing + shrink + expand on a given routing; shared by lora_forward and linear_forward
-static meteora_status run_lora(const void* x, const void* A, const void* B, const int32_t* topk_idx,
+// bucketing + shrink + (base projection if W != NULL) + expand on a given routing;
+// shared by lora_forward (W == NULL) and linear_forward
+static meteora_status run_lora(const void* x, const void* W, const void* A, const void* B, const int32_t* topk_idx,
                                const float* topk_w, int T, int d_in, int d_out, int N, int r, int k, float scale,
                                bool bf16, void* out, int accumulate, void* ws, const WsLayout& L,
                                hipStream_t st, int tslot) {
@@ -219,6 +220,7 @@ static meteora_status run_lora(const void* x, const void* A, const void* B, cons
     int32_t* btok = at<int32_t>(ws, L.bucket_tok);
     int32_t* bslot = at<int32_t>(ws, L.bucket_slot);
     float* h32 = at<float>(ws, L.h32);
+    const bool fused = gemm_fuses_expand(bf16);
     {
         StageScope sc(ST_BUCKET, st, tslot);
         METEORA_HIP(launch_bucket(topk_idx, T, k, N, at<int32_t>(ws, L.chunk_counts), at<int32_t>(ws, L.counts),
@@ -227,11 +229,22 @@ static meteora_status run_lora(const void* x, const void* A, const void* B, cons
     {
         StageScope sc(ST_SHRINK, st, tslot);
         METEORA_HIP(launch_shrink(x, A, topk_idx, topk_w, offsets, btok, bslot, T, d_in, N, r, k, scale, bf16,
-                                  h32, nullptr, L.ext_stride, st));
+                                  fused ? nullptr : h32, fused ? at<void>(ws, L.hdense) : nullptr, L.ext_stride,
+                                  st));
     }
-    {
+    if (fused) {
+        // base projection (if W is given) and LoRA expand in one MFMA kernel, one rounding of the output
+        StageScope sc(ST_GEMM, st, tslot);
+        METEORA_HIP(launch_gemm(x, W, T, W ? d_in : 0, d_out, bf16, at<void>(ws, L.hdense), L.ext_stride, B,
+                                N * r, out, accumulate, st));
+    } else {
+        if (W) {
+            StageScope sc(ST_GEMM, st, tslot);
+            METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, bf16, nullptr, 0, nullptr, 0, out, accumulate, st));
+        }
         StageScope sc(ST_EXPAND, st, tslot);
-        METEORA_HIP(launch_expand(h32, B, topk_idx, topk_w, T, d_out, N, r, k, scale, bf16, out, accumulate, st));
+        METEORA_HIP(launch_expand(h32, B, topk_idx, topk_w, T, d_out, N, r, k, scale, bf16, out,
+                                  W ? 1 : accumulate, st));
     }
     return METEORA_OK;
 }
@@ -249,7 +262,7 @@ meteora_status meteora_lora_forward(const void* x, const void* A, const void* B,
     const WsLayout L = ws_layout(T, d_in, d_out, N, r, k, bf16);
     if (!ws || !aligned256(ws) || ws_bytes < L.total) return METEORA_ERR_WORKSPACE;
     if (T == 0) return METEORA_OK;
-    return run_lora(x, A, B, topk_idx, topk_w, T, d_in, d_out, N, r, k, scale, bf16, out, accumulate, ws, L,
+    return run_lora(x, nullptr, A, B, topk_idx, topk_w, T, d_in, d_out, N, r, k, scale, bf16, out, accumulate, ws, L,
                     static_cast<hipStream_t>(stream), timing_begin_call());
 }
 
@@ -294,11 +307,7 @@ meteora_status meteora_linear_forward(const void* x, const void* W, const float*
         METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, 1.0f, idx, w,
                                      nullptr, st));
     }
-    {
-        StageScope sc(ST_GEMM, st, tslot);
-        METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, bf16, nullptr, 0, nullptr, 0, out, 0, st));
-    }
-    return run_lora(x, A, B, idx, w, T, d_in, d_out, N, r, k, scale, bf16, out, 1, ws, L, st, tslot);
+    return run_lora(x, W, A, B, idx, w, T, d_in, d_out, N, r, k, scale, bf16, out, 0, ws, L, st, tslot);
 }
 
 }  // extern "C"

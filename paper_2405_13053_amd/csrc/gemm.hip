@@ -1,6 +1,7 @@
 // Base projection of the layer, first term of Eq. 1 / Eq. 2:  out = x * W_base, with W stored
 // [d_out, d_in] so both operands are contiguous along the contraction.
 #include "common.hpp"
+#include "gemm_mfma.hpp"
 #include "kernels.hpp"
 
 namespace meteora {
@@ -56,17 +57,41 @@ __global__ __launch_bounds__(256) void gemm_fma_kernel(const TX* __restrict__ x,
     }
 }
 
+template <int MI, int NI>
+static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
+    constexpr int BM = MI * 64, BN = NI * 64;
+    constexpr int smem = 2 * (BM + BN) * kGemmBK * (int)sizeof(bf16_t);
+    static bool attr_set = false;   // raising the dynamic-LDS limit is a host-side attribute, set once
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<MI, NI>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    a.tiles_m = ceil_div(a.T, BM);
+    a.tiles_n = ceil_div(a.d_out, BN);
+    gemm_mfma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
+    return hipGetLastError();
+}
+
+bool gemm_fuses_expand(bool bf16) { return bf16; }
+
 hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out, bool bf16,
                        const void* hdense, int ext_stride, const void* B, int ext_k,
                        void* out, int accumulate, hipStream_t stream) {
-    (void)hdense; (void)ext_stride; (void)B; (void)ext_k;
+    if (bf16) {
+        GemmArgs a{};
+        a.x = (const bf16_t*)x; a.W = (const bf16_t*)W; a.hd = (const bf16_t*)hdense; a.Bst = (const bf16_t*)B;
+        a.out = (bf16_t*)out; a.T = T; a.d_in = d_in; a.d_out = d_out;
+        a.ext_k = hdense ? ext_k : 0; a.ext_stride = ext_stride; a.accumulate = accumulate;
+        const int64_t big_tiles = (int64_t)ceil_div(T, 256) * ceil_div(d_out, 256);
+        if (T > 128 && big_tiles >= 128) return launch_mfma<4, 4>(a, stream);
+        if (T > 64) return launch_mfma<2, 2>(a, stream);
+        return launch_mfma<1, 1>(a, stream);
+    }
     dim3 grid(ceil_div(d_out, 64), ceil_div(T, 64));
-    if (bf16)
-        gemm_fma_kernel<bf16_t><<<grid, 256, 0, stream>>>((const bf16_t*)x, (const bf16_t*)W, T, d_in, d_out,
-                                                          (bf16_t*)out, accumulate);
-    else
-        gemm_fma_kernel<float><<<grid, 256, 0, stream>>>((const float*)x, (const float*)W, T, d_in, d_out,
-                                                         (float*)out, accumulate);
+    gemm_fma_kernel<float><<<grid, 256, 0, stream>>>((const float*)x, (const float*)W, T, d_in, d_out,
+                                                     (float*)out, accumulate);
     return hipGetLastError();
 }
 

@@ -1,0 +1,216 @@
+// bf16 MFMA kernel for the base projection out = x * W^T (first term of Eq. 1 / Eq. 2), with the
+// LoRA expand optionally fused as an extension of the contraction:
+//
+//     out[t, c] = sum_{i < d_in} x[t,i] * W[c,i]  +  sum_{j < ext_k} hd[t,j] * Bst[j,c]
+//
+// where hd[t, a*r+q] = scale * w * h[t,slot,q] for the adapters a the token selected (zero
+// elsewhere) and Bst is the stacked B[N, r, d_out] viewed as [N*r, d_out].  The second sum is
+// exactly scale * sum_{i in I(x)} w_i (x A_i) B_i of Eq. 2, accumulated in the same fp32
+// registers as the base term, so the output is rounded once.
+//
+// Tiling (gfx950): a workgroup of 4 wavefronts (2x2) owns a BM x BN output tile; each wavefront
+// owns (BM/2) x (BN/2) as MI x NI blocks of v_mfma_f32_32x32x16_bf16.  K advances in steps of
+// 64 through a double-buffered LDS tile; rows are 128 B and their 16-B chunks are XOR-swizzled
+// with the row index so that ds_read_b128 of 8 consecutive rows touches all banks once.
+// The MFMA is issued with W as the first operand, so a lane ends up with 4 consecutive output
+// columns of one token row and stores them as one 8-byte word.
+#pragma once
+#include "common.hpp"
+
+namespace meteora {
+
+constexpr int kGemmBK = 64;          // K elements per LDS tile
+constexpr int kGemmChunks = 8;       // 16-byte chunks per LDS row
+
+struct GemmArgs {
+    const bf16_t* x;      // [T, d_in]
+    const bf16_t* W;      // [d_out, d_in]
+    const bf16_t* hd;     // [T, ext_stride] or nullptr
+    const bf16_t* Bst;    // [ext_k, d_out]  or nullptr
+    bf16_t* out;          // [T, d_out]
+    int T, d_in, d_out;
+    int ext_k;            // N*r (rows of Bst); 0 = no extension
+    int ext_stride;       // row stride of hd (multiple of 8, >= ext_k)
+    int accumulate;       // 1: add previous contents of out
+    int tiles_m, tiles_n;
+};
+
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7); }
+
+// Load a [ROWS x 64] bf16 tile (rows row0.., K columns k0..k0+64 of a row-major matrix with
+// leading dimension ld) into registers: thread tid handles chunk (tid & 7) of rows (tid>>3) + 32*i.
+template <int ROWS>
+__device__ __forceinline__ void load_tile_regs(u32x4 (&regs)[ROWS / 32], const bf16_t* __restrict__ base, int ld,
+                                               int row0, int nrows, int k0, int kmax, int tid) {
+    const int chunk = tid & 7;
+    const int kk = k0 + chunk * 8;
+#pragma unroll
+    for (int i = 0; i < ROWS / 32; ++i) {
+        int row = row0 + (tid >> 3) + 32 * i;
+        row = row < nrows ? row : nrows - 1;   // clamp: rows past the edge are computed but never stored
+        if (kk < kmax)
+            regs[i] = *reinterpret_cast<const u32x4*>(base + (size_t)row * ld + kk);
+        else
+            regs[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
+template <int ROWS>
+__device__ __forceinline__ void store_tile_lds(const u32x4 (&regs)[ROWS / 32], bf16_t* lds_tile, int tid) {
+    const int chunk = tid & 7;
+#pragma unroll
+    for (int i = 0; i < ROWS / 32; ++i) {
+        const int row = (tid >> 3) + 32 * i;
+        *reinterpret_cast<u32x4*>(lds_tile + row * kGemmBK + swz(row, chunk) * 8) = regs[i];
+    }
+}
+
+// Transposing load of the stacked-B tile: LDS wants [n][k] (k contiguous); memory is [k][n].
+// Thread handles column n = n0 + (tid) (+256*i) ... here BN <= 256 so one column per thread and
+// all 8 chunks of it; each chunk gathers 8 k-rows with 2-byte loads that are coalesced across lanes.
+template <int BN>
+__device__ __forceinline__ void load_bst_tile_lds(bf16_t* lds_tile, const bf16_t* __restrict__ Bst, int d_out,
+                                                  int n0, int k0, int ext_k, int tid) {
+    for (int n = tid; n < BN; n += 256) {
+        int col = n0 + n;
+        col = col < d_out ? col : d_out - 1;
+#pragma unroll
+        for (int c = 0; c < kGemmChunks; ++c) {
+            union { uint16_t h[8]; u32x4 v; } p;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int kk = k0 + c * 8 + j;
+                p.h[j] = kk < ext_k ? reinterpret_cast<const uint16_t*>(Bst)[(size_t)kk * d_out + col] : (uint16_t)0;
+            }
+            *reinterpret_cast<u32x4*>(lds_tile + n * kGemmBK + swz(n, c) * 8) = p.v;
+        }
+    }
+}
+
+template <int MI, int NI>
+__device__ __forceinline__ void mma_tile(f32x16 (&acc)[MI][NI], const bf16_t* xs, const bf16_t* wsm, int wm, int wn,
+                                         int lane) {
+    const int lrow = lane & 31, khalf = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < kGemmBK / 16; ++ks) {
+        bf16x8 xf[MI], wf[NI];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int row = wm + mi * 32 + lrow;
+            xf[mi] = *reinterpret_cast<const bf16x8*>(xs + row * kGemmBK + swz(row, ks * 2 + khalf) * 8);
+        }
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int row = wn + ni * 32 + lrow;
+            wf[ni] = *reinterpret_cast<const bf16x8*>(wsm + row * kGemmBK + swz(row, ks * 2 + khalf) * 8);
+        }
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[mi][ni], 0, 0, 0);
+    }
+}
+
+template <int MI, int NI>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmArgs a) {
+    constexpr int BM = MI * 64, BN = NI * 64;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+    // [2 buffers][x tile BM x 64 | w tile BN x 64]
+    constexpr int kBufElems = (BM + BN) * kGemmBK;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
+
+    // XCD-aware tile order: consecutive workgroup ids go to different XCDs (8 of them), so give
+    // each XCD a contiguous run of tiles, walked along n inside a band of tile rows.
+    const int ntiles = a.tiles_m * a.tiles_n;
+    int wg = blockIdx.x;
+    {
+        const int per_xcd = (ntiles + 7) / 8;
+        const int xcd = wg % 8, local = wg / 8;
+        const int remapped = xcd * per_xcd + local;
+        wg = (local < per_xcd && remapped < ntiles && (ntiles % 8 == 0)) ? remapped : wg;
+    }
+    const int tile_m = wg / a.tiles_n, tile_n = wg % a.tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+
+    const int nk_main = ceil_div(a.d_in, kGemmBK);
+    const int nk_ext = a.ext_k > 0 ? ceil_div(a.ext_k, kGemmBK) : 0;
+    const int nk = nk_main + nk_ext;
+
+    u32x4 xr[BM / 32], wr[BN / 32];
+
+    auto fetch = [&](int it) {   // global -> registers (x-like operand and, for the main part, W)
+        if (it < nk_main) {
+            load_tile_regs<BM>(xr, a.x, a.d_in, m0, a.T, it * kGemmBK, a.d_in, tid);
+            load_tile_regs<BN>(wr, a.W, a.d_in, n0, a.d_out, it * kGemmBK, a.d_in, tid);
+        } else {
+            load_tile_regs<BM>(xr, a.hd, a.ext_stride, m0, a.T, (it - nk_main) * kGemmBK, a.ext_k, tid);
+        }
+    };
+    auto commit = [&](int it, int buf) {   // registers -> LDS (and the transposed stacked-B tile)
+        bf16_t* xs = smem + buf * kBufElems;
+        bf16_t* wsm = xs + BM * kGemmBK;
+        store_tile_lds<BM>(xr, xs, tid);
+        if (it < nk_main)
+            store_tile_lds<BN>(wr, wsm, tid);
+        else
+            load_bst_tile_lds<BN>(wsm, a.Bst, a.d_out, n0, (it - nk_main) * kGemmBK, a.ext_k, tid);
+    };
+
+    if (nk > 0) {
+        fetch(0);
+        commit(0, 0);
+    }
+    __syncthreads();
+    for (int it = 0; it < nk; ++it) {
+        const int buf = it & 1;
+        if (it + 1 < nk) fetch(it + 1);
+        const bf16_t* xs = smem + buf * kBufElems;
+        mma_tile<MI, NI>(acc, xs, xs + BM * kGemmBK, wm, wn, lane);
+        if (it + 1 < nk) commit(it + 1, buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: lane holds, per block, 4 groups of 4 consecutive columns of token row (lane & 31)
+    const int lrow = lane & 31, khalf = lane >> 5;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        const int row = m0 + wm + mi * 32 + lrow;
+        if (row >= a.T) continue;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = n0 + wn + ni * 32 + g * 8 + khalf * 4;
+                if (col >= a.d_out) continue;   // d_out % 8 == 0, so a group of 4 is all in or all out
+                uint2* dst = reinterpret_cast<uint2*>(a.out + (size_t)row * a.d_out + col);
+                float v0 = acc[mi][ni][g * 4 + 0], v1 = acc[mi][ni][g * 4 + 1];
+                float v2 = acc[mi][ni][g * 4 + 2], v3 = acc[mi][ni][g * 4 + 3];
+                if (a.accumulate) {
+                    const uint2 old = *dst;
+                    v0 += bf16_bits_to_float(old.x & 0xffffu);
+                    v1 += bf16_bits_to_float(old.x >> 16);
+                    v2 += bf16_bits_to_float(old.y & 0xffffu);
+                    v3 += bf16_bits_to_float(old.y >> 16);
+                }
+                uint2 pk;
+                pk.x = pack_bf16x2(v0, v1);
+                pk.y = pack_bf16x2(v2, v3);
+                *dst = pk;
+            }
+        }
+    }
+}
+
+}  // namespace meteora

@@ -45,6 +45,11 @@ __global__ __launch_bounds__(256) void shrink_fma_kernel(const TX* __restrict__ 
     }
 }
 
+__global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* __restrict__ p, size_t n16) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) p[i] = u32x4{0u, 0u, 0u, 0u};
+}
+
 hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, const float* topk_w,
                          const int32_t* offsets, const int32_t* bucket_tok, const int32_t* bucket_slot,
                          int T, int d_in, int N, int r, int k, float scale, bool bf16,
@@ -53,6 +58,10 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
     int RP = 1;
     while (RP < r) RP <<= 1;
     const int64_t pairs = (int64_t)T * k;
+    if (hdense) {   // columns of adapters a token did not select must read as zero
+        const size_t n16 = (size_t)T * ext_stride * sizeof(bf16_t) / 16;
+        fill_zero_kernel<<<(unsigned)ceil_div64((int64_t)n16, 256), 256, 0, stream>>>((u32x4*)hdense, n16);
+    }
     if (bf16)
         shrink_fma_kernel<bf16_t><<<(unsigned)pairs, 256, 0, stream>>>(
             (const bf16_t*)x, (const bf16_t*)A, topk_idx, topk_w, bucket_tok, bucket_slot, T, d_in, N, r, RP, k,
