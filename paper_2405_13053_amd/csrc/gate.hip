@@ -91,24 +91,202 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(const float* __restrict_
     }
 }
 
-int gate_kslices(int d_in, bool bf16) {
-    (void)d_in; (void)bf16;
-    return 1;
+// ------------------------------------------------------------------------------------------
+// Stage 1, MFMA version for bf16 tokens.
+//
+// The gate is a skinny contraction x[T,d_in] * W_gate[d_in,N] that must keep fp32-level logits
+// (they decide the routing).  x is bf16, W_gate is fp32: W_gate is split once per call into three
+// bf16 terms hi+mid+lo that add up to the fp32 value exactly (8+8+8 significand bits), every
+// bf16 x bf16 product is exact in fp32, and v_mfma_f32_32x32x16_bf16 accumulates in fp32; only
+// the summation order differs from a plain fp32 dot product.
+//
+// Work split: a workgroup takes 128 tokens x one 512-wide K-slice; its 4 wavefronts take a
+// quarter of the slice each (no barrier in the main loop).  A wavefront
+//   - streams its 128 x 128 piece of x from HBM straight into its own 32 KB of LDS with 16-byte
+//     global->LDS loads (16 lanes cover one 256-byte row segment: fully coalesced),
+//     chunks XOR-swizzled by row so the later ds_read_b128 are conflict free,
+//   - reads the split W_gate fragments, pre-arranged in MFMA operand order so that each
+//     fragment is one contiguous 1 KB block, directly from L2 into registers and reuses each
+//     for the 4 row blocks of 32 tokens.
+// The 4 partial tiles are summed through LDS in a fixed order and written as
+// partials[ks][t][NP]; the top-k kernel adds the K-slices in order.
+// ------------------------------------------------------------------------------------------
+constexpr int kGateTM = 128;        // tokens per workgroup
+constexpr int kGateKSL = 512;       // K-slice per workgroup
+constexpr int kGateKW = 128;        // K per wavefront
+constexpr int kGateRegion = 36864;  // LDS bytes per wavefront (x piece 32 KB; reused for the reduction)
+
+// Split W_gate into bf16 hi/mid/lo in MFMA operand order.
+// Block index b = (((ks*4 + wq)*8 + s)*3 + sp)*NCB + cb ; inside a block lane l holds 8 k-values
+// k = ks*512 + wq*128 + s*16 + (l>>5)*8 + j  of column n = cb*32 + (l&31).
+__global__ __launch_bounds__(256) void gate_wsplit_kernel(const float* __restrict__ W_gate, int d_in, int N,
+                                                          int NCB, int KS, u32x4* __restrict__ wsp) {
+    const int frag = blockIdx.x * 4 + (threadIdx.x >> 6);   // (ks, wq, s, cb) without the split index
+    const int lane = threadIdx.x & 63;
+    const int total = KS * 4 * 8 * NCB;
+    if (frag >= total) return;
+    const int cb = frag % NCB;
+    const int s = (frag / NCB) % 8;
+    const int wq = (frag / (NCB * 8)) % 4;
+    const int ks = frag / (NCB * 32);
+    const int n = cb * 32 + (lane & 31);
+    const int k0 = ks * kGateKSL + wq * kGateKW + s * 16 + (lane >> 5) * 8;
+    union { uint16_t h[8]; u32x4 v; } hi, mid, lo;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int k = k0 + j;
+        const float w = (k < d_in && n < N) ? W_gate[(size_t)k * N + n] : 0.f;
+        const bf16_t h = static_cast<bf16_t>(w);
+        const float r1 = w - static_cast<float>(h);
+        const bf16_t m = static_cast<bf16_t>(r1);
+        const float r2 = r1 - static_cast<float>(m);
+        const bf16_t l = static_cast<bf16_t>(r2);
+        hi.h[j] = __builtin_bit_cast(uint16_t, h);
+        mid.h[j] = __builtin_bit_cast(uint16_t, m);
+        lo.h[j] = __builtin_bit_cast(uint16_t, l);
+    }
+    const size_t base = ((size_t)((ks * 4 + wq) * 8 + s) * 3 * NCB + cb) * 64 + lane;
+    wsp[base] = hi.v;
+    wsp[base + (size_t)NCB * 64] = mid.v;
+    wsp[base + (size_t)2 * NCB * 64] = lo.v;
 }
 
+template <int NCB>
+__global__ __launch_bounds__(256) void gate_logits_mfma_kernel(const bf16_t* __restrict__ x,
+                                                               const u32x4* __restrict__ wsp, int T, int d_in,
+                                                               int KS, float* __restrict__ partials) {
+    constexpr int NP = NCB * 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wq = threadIdx.x >> 6;
+    const int ks = blockIdx.x % KS, tile = blockIdx.x / KS;
+    const int t0 = tile * kGateTM;
+    unsigned char* region = smem + wq * kGateRegion;
+    const int kbase = ks * kGateKSL + wq * kGateKW;
+
+    // ---- x piece: 128 rows x 256 B, HBM -> LDS, 4 rows per instruction --------------------
+    {
+        const int rsub = lane >> 4, p = lane & 15;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const int row = 4 * j + rsub;
+            int t = t0 + row;
+            t = t < T ? t : T - 1;
+            int kk = kbase + ((p ^ (row & 15)) << 3);
+            kk = kk <= d_in - 8 ? kk : d_in - 8;   // past-the-end columns meet zero weights; keep the address in range
+            const bf16_t* src = x + (size_t)t * d_in + kk;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(region + j * 1024), 16, 0, 0);
+        }
+    }
+    // ---- W fragments of this wavefront's K quarter: 8 k-steps x 3 terms x NCB ---------------
+    bf16x8 wf[8][3][NCB];
+    {
+        const u32x4* wbase = wsp + (size_t)((ks * 4 + wq) * 8) * 3 * NCB * 64 + lane;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int sp = 0; sp < 3; ++sp)
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) {
+                    const u32x4 v = wbase[(size_t)((s * 3 + sp) * NCB + cb) * 64];
+                    wf[s][sp][cb] = __builtin_bit_cast(bf16x8, v);
+                }
+    }
+    __builtin_amdgcn_s_waitcnt(0);   // everything issued above has landed (vmcnt = lgkmcnt = 0)
+    __builtin_amdgcn_wave_barrier();
+
+    f32x16 acc[4][NCB];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+
+    const int lrow = lane & 31, khalf = lane >> 5;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            const int row = rb * 32 + lrow;
+            const int pos = (s * 2 + khalf) ^ (row & 15);
+            const bf16x8 xf = *reinterpret_cast<const bf16x8*>(region + row * 256 + pos * 16);
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s][0][cb], xf, acc[rb][cb], 0, 0, 0);
+                acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s][1][cb], xf, acc[rb][cb], 0, 0, 0);
+                acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s][2][cb], xf, acc[rb][cb], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- sum the 4 K quarters through LDS (fixed order), write partials[ks][t][:] ------------
+    constexpr int kRowBytes = NP * 4 + 16;   // padded: consecutive tokens start 4 banks apart
+    __builtin_amdgcn_wave_barrier();          // this wavefront's own ds_reads are done before it overwrites
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int m = rb * 32 + lrow, n = cb * 32 + g * 8 + khalf * 4;
+                f32x4 v = {acc[rb][cb][g * 4 + 0], acc[rb][cb][g * 4 + 1], acc[rb][cb][g * 4 + 2],
+                           acc[rb][cb][g * 4 + 3]};
+                *reinterpret_cast<f32x4*>(region + m * kRowBytes + n * 4) = v;
+            }
+    __syncthreads();
+    constexpr int kChunksPerRow = NP / 4;
+    for (int c = threadIdx.x; c < kGateTM * kChunksPerRow; c += 256) {
+        const int m = c / kChunksPerRow, n4 = c % kChunksPerRow;
+        const int t = t0 + m;
+        if (t >= T) continue;
+        const int off = m * kRowBytes + n4 * 16;
+        f32x4 v0 = *reinterpret_cast<const f32x4*>(smem + off);
+        f32x4 v1 = *reinterpret_cast<const f32x4*>(smem + kGateRegion + off);
+        f32x4 v2 = *reinterpret_cast<const f32x4*>(smem + 2 * kGateRegion + off);
+        f32x4 v3 = *reinterpret_cast<const f32x4*>(smem + 3 * kGateRegion + off);
+        f32x4 r = (v0 + v1) + (v2 + v3);
+        *reinterpret_cast<f32x4*>(partials + ((size_t)ks * T + t) * NP + n4 * 4) = r;
+    }
+}
+
+int gate_kslices(int d_in, bool bf16) { return bf16 ? ceil_div(d_in, kGateKSL) : 1; }
+
 size_t gate_wsplit_bytes(int d_in, int N, bool bf16) {
-    (void)d_in; (void)N; (void)bf16;
-    return 0;
+    if (!bf16) return 0;
+    return (size_t)gate_kslices(d_in, true) * kGateKSL * padded_adapters(N) * 3 * sizeof(bf16_t);
 }
 
 hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_in, int N, bool bf16,
                               void* wsplit, float* partials, hipStream_t stream) {
-    (void)wsplit;
     const int NP = padded_adapters(N);
-    if (bf16)
-        gate_logits_fma_kernel<bf16_t><<<T, 256, 0, stream>>>((const bf16_t*)x, W_gate, T, d_in, N, NP, partials);
-    else
+    if (!bf16) {
         gate_logits_fma_kernel<float><<<T, 256, 0, stream>>>((const float*)x, W_gate, T, d_in, N, NP, partials);
+        return hipGetLastError();
+    }
+    const int KS = gate_kslices(d_in, true), NCB = NP / 32;
+    const int frags = KS * 4 * 8 * NCB;
+    gate_wsplit_kernel<<<ceil_div(frags, 4), 256, 0, stream>>>(W_gate, d_in, N, NCB, KS, (u32x4*)wsplit);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    constexpr int smem = 4 * kGateRegion;
+    static bool attr_set = false;
+    if (!attr_set) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_logits_mfma_kernel<1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_logits_mfma_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int grid = ceil_div(T, kGateTM) * KS;
+    if (NCB == 1)
+        gate_logits_mfma_kernel<1><<<grid, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)wsplit, T, d_in, KS,
+                                                                partials);
+    else
+        gate_logits_mfma_kernel<2><<<grid, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)wsplit, T, d_in, KS,
+                                                                partials);
     return hipGetLastError();
 }
 
