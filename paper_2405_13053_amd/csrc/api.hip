@@ -13,7 +13,7 @@ namespace {
 
 struct WsLayout {
     size_t wsplit, partials, chunk_counts, counts, offsets, bucket_tok, bucket_slot, topk_idx, topk_w, h32,
-        hdense, total;
+        hdense, apack, hpart, total;
     int ext_stride;   // columns of hdense: N*r rounded up to 32
 };
 
@@ -45,6 +45,8 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     L.topk_w = take(pairs * sizeof(float));
     L.h32 = take(pairs * r * sizeof(float));
     L.hdense = take((size_t)T * L.ext_stride * sizeof(uint16_t));
+    L.apack = take(shrink_apack_bytes(d_in, N, r, bf16));
+    L.hpart = take(shrink_hpart_bytes(T, d_in, r, k, bf16));
     L.total = off;
     return L;
 }
@@ -229,8 +231,8 @@ static meteora_status run_lora(const void* x, const void* W, const void* A, cons
     {
         StageScope sc(ST_SHRINK, st, tslot);
         METEORA_HIP(launch_shrink(x, A, topk_idx, topk_w, offsets, btok, bslot, T, d_in, N, r, k, scale, bf16,
-                                  fused ? nullptr : h32, fused ? at<void>(ws, L.hdense) : nullptr, L.ext_stride,
-                                  st));
+                                  at<void>(ws, L.apack), at<float>(ws, L.hpart), fused ? nullptr : h32,
+                                  fused ? at<void>(ws, L.hdense) : nullptr, L.ext_stride, st));
     }
     if (fused) {
         // base projection (if W is given) and LoRA expand in one MFMA kernel, one rounding of the output

@@ -29,10 +29,15 @@ hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* 
 // ---- grouped LoRA shrink: h[t,slot,:] = x[t,:] * A[idx[t,slot]] ---------------------------
 // h32 ([T,k,r] fp32) and/or hdense (bf16 [T, ext_stride], column idx*r+q = scale*w*h, other
 // columns zero) are written; either may be NULL.
+// apack / hpart: scratch of shrink_apack_bytes / shrink_hpart_bytes (A in MFMA operand order,
+// per-K-slice partial sums); both sizes are 0 when the plain-FMA kernel is used.
+size_t shrink_apack_bytes(int d_in, int N, int r, bool bf16);
+size_t shrink_hpart_bytes(int T, int d_in, int r, int k, bool bf16);
 hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, const float* topk_w,
                          const int32_t* offsets, const int32_t* bucket_tok, const int32_t* bucket_slot,
                          int T, int d_in, int N, int r, int k, float scale, bool bf16,
-                         float* h32, void* hdense, int ext_stride, hipStream_t stream);
+                         void* apack, float* hpart, float* h32, void* hdense, int ext_stride,
+                         hipStream_t stream);
 
 // ---- grouped LoRA expand: out (+)= scale * sum_slot w * h[t,slot,:] * B[idx[t,slot]] ------
 hipError_t launch_expand(const float* h32, const void* B, const int32_t* topk_idx, const float* topk_w,

@@ -45,19 +45,276 @@ __global__ __launch_bounds__(256) void shrink_fma_kernel(const TX* __restrict__ 
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// MFMA version for bf16.
+//
+// A tile is up to 128 consecutive pairs of one adapter's bucket x one 512-wide K-slice.  As in
+// the gate kernel, each of the 4 wavefronts takes a quarter of the slice: it gathers its
+// 128 x 128 piece of the token rows straight from HBM into its own LDS region (16-byte
+// global->LDS loads, 16 lanes per 256-byte row segment, XOR-swizzled chunks) and multiplies it
+// by A_a fragments that a pack kernel has laid out in MFMA operand order (one contiguous 1 KB
+// block per fragment), reusing every fragment for the 4 row blocks.  The K quarters are summed
+// through LDS in a fixed order; the K-slices are written as partial sums hpart[ks][pair][r] and
+// added, again in a fixed order, by the finalize kernel, which also applies scale * w and
+// writes the dense bf16 operand of the fused expand (zero for adapters a token did not pick).
+// ------------------------------------------------------------------------------------------
+constexpr int kShrTM = 128;
+constexpr int kShrKSL = 512;
+constexpr int kShrKW = 128;
+constexpr int kShrRegion = 36864;
+
+// A[N, d_in, r] -> apk: block ((a*S16 + s16)*RCB + cb), lane l holds A[a][s16*16 + (l>>5)*8 + j][cb*32 + (l&31)].
+__global__ __launch_bounds__(256) void shrink_apack_kernel(const bf16_t* __restrict__ A, int d_in, int N, int r,
+                                                           int RCB, int S16, u32x4* __restrict__ apk) {
+    const int64_t frag = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (frag >= (int64_t)N * S16 * RCB) return;
+    const int cb = (int)(frag % RCB);
+    const int s16 = (int)((frag / RCB) % S16);
+    const int a = (int)(frag / ((int64_t)RCB * S16));
+    const int q = cb * 32 + (lane & 31);
+    const int k0 = s16 * 16 + (lane >> 5) * 8;
+    union { uint16_t h[8]; u32x4 v; } p;
+    const uint16_t* Aa = reinterpret_cast<const uint16_t*>(A) + (size_t)a * d_in * r;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int kk = k0 + j;
+        p.h[j] = (kk < d_in && q < r) ? Aa[(size_t)kk * r + q] : (uint16_t)0;
+    }
+    apk[frag * 64 + lane] = p.v;
+}
+
+template <int RCB>
+__global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restrict__ x, const u32x4* __restrict__ apk,
+                                                          const int32_t* __restrict__ offsets,
+                                                          const int32_t* __restrict__ bucket_tok,
+                                                          const int32_t* __restrict__ bucket_slot, int T, int d_in,
+                                                          int N, int r, int k, int KS, float* __restrict__ hpart) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ int pair_of_row[kShrTM];
+    const int lane = threadIdx.x & 63, wq = threadIdx.x >> 6;
+    const int ks = blockIdx.x % KS, tile_id = blockIdx.x / KS;
+
+    // which (adapter, tile of its bucket) is tile_id?  lane j owns adapter j.
+    int a, row_start, nrows;
+    {
+        const int lo = (lane < N) ? offsets[lane] : 0, hi = (lane < N) ? offsets[lane + 1] : 0;
+        const int tiles = ceil_div(hi - lo, kShrTM);
+        int incl = tiles;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int n = __shfl_up(incl, off);
+            if (lane >= off) incl += n;
+        }
+        const unsigned long long m = __ballot(lane < N && tile_id < incl);
+        if (m == 0ull) return;   // past the last tile: the whole workgroup leaves together
+        a = __ffsll((long long)m) - 1;
+        const int excl = __shfl(incl - tiles, a);
+        const int blo = __shfl(lo, a), bhi = __shfl(hi, a);
+        row_start = blo + (tile_id - excl) * kShrTM;
+        nrows = min(kShrTM, bhi - row_start);
+    }
+    // tokens of the tile: lane l holds rows l and 64+l (clamped to the first row past the end)
+    int tok0, tok1;
+    {
+        const int r0 = lane < nrows ? lane : 0, r1 = 64 + lane < nrows ? 64 + lane : 0;
+        tok0 = bucket_tok[row_start + r0];
+        tok1 = bucket_tok[row_start + r1];
+        tok0 = min(max(tok0, 0), T - 1);
+        tok1 = min(max(tok1, 0), T - 1);
+        if (wq == 0) {
+            const int s0 = bucket_slot[row_start + r0], s1 = bucket_slot[row_start + r1];
+            pair_of_row[lane] = tok0 * k + min(max(s0, 0), k - 1);
+            pair_of_row[64 + lane] = tok1 * k + min(max(s1, 0), k - 1);
+        }
+    }
+    unsigned char* region = smem + wq * kShrRegion;
+    const int kbase = ks * kShrKSL + wq * kShrKW;
+    const int nrb = ceil_div(nrows, 32);   // row blocks that hold at least one pair
+
+    {
+        const int rsub = lane >> 4, p = lane & 15;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            if ((j >> 3) < nrb) {   // uniform
+                const int row = 4 * j + rsub;
+                const int t = __shfl(row < 64 ? tok0 : tok1, row & 63);
+                int kk = kbase + ((p ^ (row & 15)) << 3);
+                kk = kk <= d_in - 8 ? kk : d_in - 8;   // columns past d_in meet zero weights
+                const bf16_t* src = x + (size_t)t * d_in + kk;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (__attribute__((address_space(3))) void*)(region + j * 1024), 16, 0,
+                                                 0);
+            }
+        }
+    }
+    bf16x8 af[8][RCB];
+    {
+        const int S16 = KS * (kShrKSL / 16);
+        const u32x4* abase = apk + ((size_t)a * S16 + (size_t)(ks * 4 + wq) * 8) * RCB * 64 + lane;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int cb = 0; cb < RCB; ++cb) {
+                const u32x4 v = abase[(size_t)(s * RCB + cb) * 64];
+                af[s][cb] = __builtin_bit_cast(bf16x8, v);
+            }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+
+    f32x16 acc[4][RCB];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < RCB; ++cb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+
+    const int lrow = lane & 31, khalf = lane >> 5;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+        if (rb < nrb) {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int row = rb * 32 + lrow;
+                const int pos = (s * 2 + khalf) ^ (row & 15);
+                const bf16x8 xf = *reinterpret_cast<const bf16x8*>(region + row * 256 + pos * 16);
+#pragma unroll
+                for (int cb = 0; cb < RCB; ++cb)
+                    acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][cb], xf, acc[rb][cb], 0, 0, 0);
+            }
+        }
+    }
+
+    constexpr int kRowBytes = RCB * 128 + 16;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < RCB; ++cb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int m = rb * 32 + lrow, n = cb * 32 + g * 8 + khalf * 4;
+                f32x4 v = {acc[rb][cb][g * 4 + 0], acc[rb][cb][g * 4 + 1], acc[rb][cb][g * 4 + 2],
+                           acc[rb][cb][g * 4 + 3]};
+                *reinterpret_cast<f32x4*>(region + m * kRowBytes + n * 4) = v;
+            }
+    __syncthreads();
+    const size_t pairs = (size_t)T * k;
+    for (int e = threadIdx.x; e < nrows * r; e += 256) {
+        const int m = e / r, q = e - m * r;
+        const int off = m * kRowBytes + q * 4;
+        const float v0 = *reinterpret_cast<const float*>(smem + off);
+        const float v1 = *reinterpret_cast<const float*>(smem + kShrRegion + off);
+        const float v2 = *reinterpret_cast<const float*>(smem + 2 * kShrRegion + off);
+        const float v3 = *reinterpret_cast<const float*>(smem + 3 * kShrRegion + off);
+        hpart[((size_t)ks * pairs + pair_of_row[m]) * r + q] = (v0 + v1) + (v2 + v3);
+    }
+}
+
+// Sum the K-slices (fixed order) and emit h32[pair][r] and/or the dense expand operand
+// hdense[t][a*r+q] = bf16(scale * w[t,slot] * h), zero where the token did not select adapter a.
+__global__ __launch_bounds__(256) void shrink_finalize_kernel(const float* __restrict__ hpart, int KS,
+                                                              const int32_t* __restrict__ topk_idx,
+                                                              const float* __restrict__ topk_w, int T, int N, int r,
+                                                              int k, float scale, float* __restrict__ h32,
+                                                              bf16_t* __restrict__ hdense, int ext_stride) {
+    const size_t pairs = (size_t)T * k;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (hdense) {
+        const int cpr = ext_stride / 8;   // 16-byte chunks per row
+        if (gid < (int64_t)T * cpr) {
+            const int t = (int)(gid / cpr), c = (int)(gid % cpr);
+            union { bf16_t h[8]; u32x4 v; } o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int col = c * 8 + e;
+                const int a = col / r, q = col - a * r;
+                float val = 0.f;
+                if (a < N) {
+                    for (int slot = 0; slot < k; ++slot) {
+                        if (topk_idx[(size_t)t * k + slot] == a) {
+                            float s = 0.f;
+                            for (int ks = 0; ks < KS; ++ks) s += hpart[((size_t)ks * pairs + (size_t)t * k + slot) * r + q];
+                            val += scale * topk_w[(size_t)t * k + slot] * s;
+                        }
+                    }
+                }
+                o.h[e] = from_float<bf16_t>(val);
+            }
+            *reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride + c * 8) = o.v;
+        }
+    }
+    if (h32 && gid < (int64_t)pairs * r) {
+        float s = 0.f;
+        for (int ks = 0; ks < KS; ++ks) s += hpart[(size_t)ks * pairs * r + gid];
+        h32[gid] = s;
+    }
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* __restrict__ p, size_t n16) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n16) p[i] = u32x4{0u, 0u, 0u, 0u};
 }
 
+static int shrink_kslices(int d_in) { return ceil_div(d_in, kShrKSL); }
+static bool shrink_uses_mfma(bool bf16, int r) { return bf16 && r <= 64; }
+
+size_t shrink_apack_bytes(int d_in, int N, int r, bool bf16) {
+    if (!shrink_uses_mfma(bf16, r)) return 0;
+    return (size_t)N * shrink_kslices(d_in) * kShrKSL * ceil_div(r, 32) * 32 * sizeof(bf16_t);
+}
+
+size_t shrink_hpart_bytes(int T, int d_in, int r, int k, bool bf16) {
+    if (!shrink_uses_mfma(bf16, r)) return 0;
+    return (size_t)shrink_kslices(d_in) * T * k * r * sizeof(float);
+}
+
 hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, const float* topk_w,
                          const int32_t* offsets, const int32_t* bucket_tok, const int32_t* bucket_slot,
                          int T, int d_in, int N, int r, int k, float scale, bool bf16,
-                         float* h32, void* hdense, int ext_stride, hipStream_t stream) {
-    (void)offsets;
+                         void* apack, float* hpart, float* h32, void* hdense, int ext_stride,
+                         hipStream_t stream) {
+    const int64_t pairs = (int64_t)T * k;
+    if (shrink_uses_mfma(bf16, r)) {
+        const int KS = shrink_kslices(d_in), RCB = ceil_div(r, 32), S16 = KS * (kShrKSL / 16);
+        const int64_t frags = (int64_t)N * S16 * RCB;
+        shrink_apack_kernel<<<(unsigned)ceil_div64(frags, 4), 256, 0, stream>>>((const bf16_t*)A, d_in, N, r, RCB,
+                                                                                 S16, (u32x4*)apack);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        constexpr int smem = 4 * kShrRegion;
+        static bool attr_set = false;
+        if (!attr_set) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shrink_mfma_kernel<1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shrink_mfma_kernel<2>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        // upper bound of the tile count: every bucket rounds up by at most one tile
+        const int max_tiles = (int)ceil_div64(pairs, kShrTM) + N;
+        const unsigned grid = (unsigned)max_tiles * KS;
+        if (RCB == 1)
+            shrink_mfma_kernel<1><<<grid, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)apack, offsets,
+                                                               bucket_tok, bucket_slot, T, d_in, N, r, k, KS, hpart);
+        else
+            shrink_mfma_kernel<2><<<grid, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)apack, offsets,
+                                                               bucket_tok, bucket_slot, T, d_in, N, r, k, KS, hpart);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        int64_t work = 0;
+        if (hdense) work = (int64_t)T * (ext_stride / 8);
+        if (h32 && pairs * r > work) work = pairs * r;
+        shrink_finalize_kernel<<<(unsigned)ceil_div64(work, 256), 256, 0, stream>>>(
+            hpart, KS, topk_idx, topk_w, T, N, r, k, scale, h32, (bf16_t*)hdense, ext_stride);
+        return hipGetLastError();
+    }
     int RP = 1;
     while (RP < r) RP <<= 1;
-    const int64_t pairs = (int64_t)T * k;
     if (hdense) {   // columns of adapters a token did not select must read as zero
         const size_t n16 = (size_t)T * ext_stride * sizeof(bf16_t) / 16;
         fill_zero_kernel<<<(unsigned)ceil_div64((int64_t)n16, 256), 256, 0, stream>>>((u32x4*)hdense, n16);
