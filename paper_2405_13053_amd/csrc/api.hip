@@ -14,7 +14,7 @@ namespace {
 struct WsLayout {
     size_t wsplit, partials, chunk_counts, counts, offsets, bucket_tok, bucket_slot, topk_idx, topk_w, h32,
         hdense, apack, hpart, total;
-    int ext_stride;   // columns of hdense: N*r rounded up to 32
+    int ext_stride;   // columns of hdense: N*r rounded up to 64 (one K tile of the GEMM)
 };
 
 bool shape_ok(int T, int d_in, int d_out, int N, int r, int k) {
@@ -33,7 +33,7 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     const int NP = padded_adapters(N);
     const size_t pairs = (size_t)T * k;
-    L.ext_stride = (int)align_up((size_t)N * r, 32);
+    L.ext_stride = (int)align_up((size_t)N * r, 64);
     L.wsplit = take(gate_wsplit_bytes(d_in, N, bf16));
     L.partials = take((size_t)gate_kslices(d_in, bf16) * T * NP * sizeof(float));
     L.chunk_counts = take((size_t)bucket_chunks((int64_t)pairs) * N * sizeof(int32_t));

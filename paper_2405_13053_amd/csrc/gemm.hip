@@ -66,11 +66,18 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<MI, NI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_dma_kernel<MI, NI>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
         attr_set = true;
     }
     a.tiles_m = ceil_div(a.T, BM);
     a.tiles_n = ceil_div(a.d_out, BN);
-    gemm_mfma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
+    const bool dma_ok = a.d_in % kGemmBK == 0 && (a.ext_k == 0 || a.ext_stride % kGemmBK == 0);
+    if (dma_ok)
+        gemm_mfma_dma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
+    else
+        gemm_mfma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
     return hipGetLastError();
 }
 

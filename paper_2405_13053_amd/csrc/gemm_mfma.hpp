@@ -213,4 +213,172 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmArgs a) {
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Pipelined version for d_in % 64 == 0 (all model shapes): the tiles of x and W go from global
+// memory straight into LDS with 16-byte global->LDS loads (no staging registers), the MFMA
+// operand fragments are double-buffered in registers so the ds_reads of k-step s+1 are in
+// flight while the MFMAs of k-step s run, and there is one barrier per 64-wide K tile, placed
+// before the last k-step: behind it the next tile is visible, the tile after it is requested
+// into the slot that has just been drained, and the first fragments of the next tile are read
+// under the MFMAs of the last k-step.
+// ------------------------------------------------------------------------------------------
+template <int MI, int NI>
+struct Frags {
+    bf16x8 x[MI];
+    bf16x8 w[NI];
+};
+
+template <int MI, int NI>
+__device__ __forceinline__ void load_frags(Frags<MI, NI>& f, const bf16_t* xs, const bf16_t* wsm, int wm, int wn,
+                                           int lrow, int khalf, int ks) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        const int row = wm + mi * 32 + lrow;
+        f.x[mi] = *reinterpret_cast<const bf16x8*>(xs + row * kGemmBK + swz(row, ks * 2 + khalf) * 8);
+    }
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int row = wn + ni * 32 + lrow;
+        f.w[ni] = *reinterpret_cast<const bf16x8*>(wsm + row * kGemmBK + swz(row, ks * 2 + khalf) * 8);
+    }
+}
+
+template <int MI, int NI>
+__device__ __forceinline__ void mma_frags(f32x16 (&acc)[MI][NI], const Frags<MI, NI>& f) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.w[ni], f.x[mi], acc[mi][ni], 0, 0, 0);
+}
+
+// One [ROWS x 64] tile, global -> LDS: an instruction moves 8 rows (8 lanes x 16 B per 128-B row);
+// lane (row, p) fetches global chunk p ^ (row & 7) so the LDS image is the swizzled layout.
+template <int ROWS>
+__device__ __forceinline__ void dma_tile(bf16_t* lds_tile, const bf16_t* __restrict__ base, int ld, int row0,
+                                         int nrows, int k0, int wave, int lane) {
+    const int rsub = lane >> 3, p = lane & 7;
+#pragma unroll
+    for (int j = 0; j < ROWS / 32; ++j) {   // 4 waves x 8 rows per instruction
+        const int row = (j * 4 + wave) * 8 + rsub;
+        int grow = row0 + row;
+        grow = grow < nrows ? grow : nrows - 1;
+        const bf16_t* src = base + (size_t)grow * ld + k0 + ((p ^ (row & 7)) << 3);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(lds_tile + (j * 4 + wave) * 8 * kGemmBK),
+                                         16, 0, 0);
+    }
+}
+
+// Map a workgroup id to an output tile: ids are dealt round-robin to the 8 XCDs, so each XCD
+// gets a contiguous run of the tile order, and the order walks groups of 4 tile rows column by
+// column: the 32 tiles an XCD works on at a time share few rows of x and W in its L2.
+__device__ __forceinline__ void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+    const int ntiles = tiles_m * tiles_n;
+    int id = wg;
+    if (ntiles % 8 == 0) id = (wg % 8) * (ntiles / 8) + wg / 8;
+    constexpr int GM = 4;
+    const int group = id / (GM * tiles_n);
+    const int first_m = group * GM;
+    const int gm = min(GM, tiles_m - first_m);
+    const int in_group = id - group * GM * tiles_n;
+    tile_m = first_m + in_group % gm;
+    tile_n = in_group / gm;
+}
+
+template <int MI, int NI>
+__global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
+    constexpr int BM = MI * 64, BN = NI * 64;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+    constexpr int kBufElems = (BM + BN) * kGemmBK;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
+    const int lrow = lane & 31, khalf = lane >> 5;
+    int tile_m, tile_n;
+    tile_of_workgroup(blockIdx.x, a.tiles_m, a.tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+
+    const int nk_main = a.d_in / kGemmBK;
+    const int nk_ext = a.ext_k > 0 ? ceil_div(a.ext_k, kGemmBK) : 0;
+    const int nk = nk_main + nk_ext;
+
+    auto request = [&](int it, int slot) {   // start moving K tile `it` into LDS slot `slot`
+        bf16_t* xs = smem + slot * kBufElems;
+        bf16_t* wsm = xs + BM * kGemmBK;
+        if (it < nk_main) {
+            dma_tile<BM>(xs, a.x, a.d_in, m0, a.T, it * kGemmBK, wave, lane);
+            dma_tile<BN>(wsm, a.W, a.d_in, n0, a.d_out, it * kGemmBK, wave, lane);
+        } else {
+            dma_tile<BM>(xs, a.hd, a.ext_stride, m0, a.T, (it - nk_main) * kGemmBK, wave, lane);
+            load_bst_tile_lds<BN>(wsm, a.Bst, a.d_out, n0, (it - nk_main) * kGemmBK, a.ext_k, tid);
+        }
+    };
+
+    Frags<MI, NI> f0, f1;
+    if (nk > 0) {
+        request(0, 0);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (nk > 1) request(1, 1);
+        load_frags<MI, NI>(f0, smem, smem + BM * kGemmBK, wm, wn, lrow, khalf, 0);
+    }
+    for (int it = 0; it < nk; ++it) {
+        const bf16_t* xs = smem + (it & 1) * kBufElems;
+        const bf16_t* wsm = xs + BM * kGemmBK;
+        load_frags<MI, NI>(f1, xs, wsm, wm, wn, lrow, khalf, 1);
+        mma_frags<MI, NI>(acc, f0);
+        load_frags<MI, NI>(f0, xs, wsm, wm, wn, lrow, khalf, 2);
+        mma_frags<MI, NI>(acc, f1);
+        load_frags<MI, NI>(f1, xs, wsm, wm, wn, lrow, khalf, 3);
+        mma_frags<MI, NI>(acc, f0);
+        // tile it+1 (requested one tile ago) must have landed; every wavefront has read tile it
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (it + 2 < nk) request(it + 2, it & 1);
+        if (it + 1 < nk) {
+            const bf16_t* xn = smem + ((it + 1) & 1) * kBufElems;
+            load_frags<MI, NI>(f0, xn, xn + BM * kGemmBK, wm, wn, lrow, khalf, 0);
+        }
+        mma_frags<MI, NI>(acc, f1);
+    }
+
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        const int row = m0 + wm + mi * 32 + lrow;
+        if (row >= a.T) continue;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = n0 + wn + ni * 32 + g * 8 + khalf * 4;
+                if (col >= a.d_out) continue;
+                uint2* dst = reinterpret_cast<uint2*>(a.out + (size_t)row * a.d_out + col);
+                float v0 = acc[mi][ni][g * 4 + 0], v1 = acc[mi][ni][g * 4 + 1];
+                float v2 = acc[mi][ni][g * 4 + 2], v3 = acc[mi][ni][g * 4 + 3];
+                if (a.accumulate) {
+                    const uint2 old = *dst;
+                    v0 += bf16_bits_to_float(old.x & 0xffffu);
+                    v1 += bf16_bits_to_float(old.x >> 16);
+                    v2 += bf16_bits_to_float(old.y & 0xffffu);
+                    v3 += bf16_bits_to_float(old.y >> 16);
+                }
+                uint2 pk;
+                pk.x = pack_bf16x2(v0, v1);
+                pk.y = pack_bf16x2(v2, v3);
+                *dst = pk;
+            }
+        }
+    }
+}
+
 }  // namespace meteora
