@@ -73,7 +73,9 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
     }
     a.tiles_m = ceil_div(a.T, BM);
     a.tiles_n = ceil_div(a.d_out, BN);
-    const bool dma_ok = a.d_in % kGemmBK == 0 && (a.ext_k == 0 || a.ext_stride % kGemmBK == 0);
+    // the pipelined kernel needs whole K tiles and byte offsets inside x and W that fit 32 bits
+    const bool dma_ok = a.d_in % kGemmBK == 0 && (a.ext_k == 0 || a.ext_stride % kGemmBK == 0) &&
+                        (uint64_t)a.T * a.d_in * 2 < (1ull << 32) && (uint64_t)a.d_out * a.d_in * 2 < (1ull << 32);
     if (dma_ok)
         gemm_mfma_dma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
     else

@@ -15,6 +15,8 @@
 // The MFMA is issued with W as the first operand, so a lane ends up with 4 consecutive output
 // columns of one token row and stores them as one 8-byte word.
 #pragma once
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace meteora {
@@ -270,6 +272,33 @@ __device__ __forceinline__ void dma_tile(bf16_t* lds_tile, const bf16_t* __restr
     }
 }
 
+// Steady-state form of dma_tile: the per-lane byte offsets are computed once (dma_offsets) and each
+// K tile only adds a uniform base, so the loop carries no per-load address arithmetic.
+template <int ROWS>
+__device__ __forceinline__ void dma_offsets(uint32_t (&voff)[ROWS / 32], int ld, int row0, int nrows, int wave,
+                                            int lane) {
+    const int rsub = lane >> 3, p = lane & 7;
+#pragma unroll
+    for (int j = 0; j < ROWS / 32; ++j) {
+        const int row = (j * 4 + wave) * 8 + rsub;
+        int grow = row0 + row;
+        grow = grow < nrows ? grow : nrows - 1;
+        voff[j] = (uint32_t)grow * (uint32_t)ld * 2u + (uint32_t)((p ^ (row & 7)) << 4);
+    }
+}
+
+template <int ROWS>
+__device__ __forceinline__ void dma_issue(bf16_t* lds_tile, const char* base_k, const uint32_t (&voff)[ROWS / 32],
+                                          int wave) {
+#pragma unroll
+    for (int j = 0; j < ROWS / 32; ++j) {
+        const char* src = base_k + voff[j];
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(lds_tile + (j * 4 + wave) * 8 * kGemmBK),
+                                         16, 0, 0);
+    }
+}
+
 // Map a workgroup id to an output tile: ids are dealt round-robin to the 8 XCDs, so each XCD
 // gets a contiguous run of the tile order, and the order walks groups of 4 tile rows column by
 // column: the 32 tiles an XCD works on at a time share few rows of x and W in its L2.
@@ -293,7 +322,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
     bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
     constexpr int kBufElems = (BM + BN) * kGemmBK;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps LDS bases in SGPRs
     const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
     const int lrow = lane & 31, khalf = lane >> 5;
     int tile_m, tile_n;
@@ -324,6 +354,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
         }
     };
 
+    // steady state: byte offsets of this lane's 16-byte pieces inside a K tile, fixed for the whole loop
+    uint32_t xoff[BM / 32], woff[BN / 32];
+    dma_offsets<BM>(xoff, a.d_in, m0, a.T, wave, lane);
+    dma_offsets<BN>(woff, a.d_in, n0, a.d_out, wave, lane);
+    const char* xb = reinterpret_cast<const char*>(a.x);
+    const char* wb = reinterpret_cast<const char*>(a.W);
+    auto request_main = [&](int it, int slot) {
+        bf16_t* xs = smem + slot * kBufElems;
+        dma_issue<BM>(xs, xb + (size_t)it * (kGemmBK * 2), xoff, wave);
+        dma_issue<BN>(xs + BM * kGemmBK, wb + (size_t)it * (kGemmBK * 2), woff, wave);
+    };
+
     Frags<MI, NI> f0, f1;
     if (nk > 0) {
         request(0, 0);
@@ -332,25 +374,37 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
         if (nk > 1) request(1, 1);
         load_frags<MI, NI>(f0, smem, smem + BM * kGemmBK, wm, wn, lrow, khalf, 0);
     }
-    for (int it = 0; it < nk; ++it) {
+    // One K tile = 4 phases of (16 MFMA + the fragment reads of the next k-step); sched_barrier keeps
+    // each phase's reads from sinking into the next phase, where they would be waited on at once.
+    auto tile_step = [&](int it, auto steady) {
         const bf16_t* xs = smem + (it & 1) * kBufElems;
         const bf16_t* wsm = xs + BM * kGemmBK;
         load_frags<MI, NI>(f1, xs, wsm, wm, wn, lrow, khalf, 1);
         mma_frags<MI, NI>(acc, f0);
+        __builtin_amdgcn_sched_barrier(0);
         load_frags<MI, NI>(f0, xs, wsm, wm, wn, lrow, khalf, 2);
         mma_frags<MI, NI>(acc, f1);
+        __builtin_amdgcn_sched_barrier(0);
         load_frags<MI, NI>(f1, xs, wsm, wm, wn, lrow, khalf, 3);
         mma_frags<MI, NI>(acc, f0);
+        __builtin_amdgcn_sched_barrier(0);
         // tile it+1 (requested one tile ago) must have landed; every wavefront has read tile it
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (it + 2 < nk) request(it + 2, it & 1);
-        if (it + 1 < nk) {
-            const bf16_t* xn = smem + ((it + 1) & 1) * kBufElems;
+        const bf16_t* xn = smem + ((it + 1) & 1) * kBufElems;
+        if constexpr (decltype(steady)::value) {
+            request_main(it + 2, it & 1);
             load_frags<MI, NI>(f0, xn, xn + BM * kGemmBK, wm, wn, lrow, khalf, 0);
+        } else {
+            if (it + 2 < nk) request(it + 2, it & 1);
+            if (it + 1 < nk) load_frags<MI, NI>(f0, xn, xn + BM * kGemmBK, wm, wn, lrow, khalf, 0);
         }
         mma_frags<MI, NI>(acc, f1);
-    }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int it = 0;
+    for (; it + 2 < nk_main; ++it) tile_step(it, std::true_type{});   // branch-free body
+    for (; it < nk; ++it) tile_step(it, std::false_type{});            // last tiles and the expand extension
 
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
