@@ -18,6 +18,11 @@ if ROOT not in sys.path:
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this same command (each counter scaled by what it reads for a plain 1 GiB copy kernel: 2.0 and 1.0);
+# the summary is profiles/linear_forward_config2_hbm_traffic.md.  Only the profiled workload has a value.
+MEASURED_GEMM_TRAFFIC_BYTES = {(2, 0): 104459.3 * 2.0 * 1024 + 37376.0 * 1024}
+
 
 def algorithmic(shape):
     """Algorithmic flops and bytes of each stage of one layer call (e = bytes per element)."""
@@ -111,7 +116,9 @@ def main():
     achieved = gemm_flops / (gemm_us * 1e-6) / 1e12
     roofline = {"kernel": "base GEMM (bf16 MFMA)" if shape.dtype == "bf16" else "base GEMM (fp32)",
                 "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_MFMA_BF16_TFLOPS, "traffic": None}
+                "frac": achieved / PEAK_MFMA_BF16_TFLOPS,
+                "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get((args.config, args.layer)),
+                "algorithmic_bytes": alg["gemm"]["bytes"], "us": gemm_us}
     per_stage = {}
     for n, us in stage_us.items():
         key = {"gate_logits": "gate", "gate_topk": None, "bucket": None}.get(n, n)
