@@ -36,7 +36,7 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     L.ext_stride = (int)align_up((size_t)N * r, 64);
     L.wsplit = take(gate_wsplit_bytes(d_in, N, bf16));
     L.partials = take((size_t)gate_kslices(d_in, bf16) * T * NP * sizeof(float));
-    L.chunk_counts = take((size_t)bucket_chunks((int64_t)pairs) * N * sizeof(int32_t));
+    L.chunk_counts = take((size_t)bucket_chunks(T) * N * sizeof(int32_t));
     L.counts = take((size_t)N * sizeof(int32_t));
     L.offsets = take((size_t)(N + 1) * sizeof(int32_t));
     L.bucket_tok = take(pairs * sizeof(int32_t));
@@ -177,7 +177,7 @@ meteora_status meteora_gate_topk(const void* x, const float* W_gate, const float
     float* partials = at<float>(ws, L.partials);
     METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, at<void>(ws, L.wsplit), partials, st));
     METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, inv_temperature,
-                                 topk_idx, topk_w, logits, st));
+                                 topk_idx, topk_w, logits, nullptr, st));
     return METEORA_OK;
 }
 
@@ -191,13 +191,13 @@ meteora_status meteora_bucket_tokens(const int32_t* topk_idx, int T, int k, int 
         !aligned16(bucket_slot))
         return METEORA_ERR_UNSUPPORTED;
     // only the chunk histograms live in the workspace; they sit at offset 0 for this entry point
-    const size_t need = (size_t)bucket_chunks((int64_t)T * k) * N * sizeof(int32_t);
+    const size_t need = (size_t)bucket_chunks(T) * N * sizeof(int32_t);
     if (!ws || !aligned256(ws) || ws_bytes < need) return METEORA_ERR_WORKSPACE;
     if (T == 0) {
         // nothing to enqueue; counts/offsets of an empty batch are left to the caller
         return METEORA_OK;
     }
-    METEORA_HIP(launch_bucket(topk_idx, T, k, N, static_cast<int32_t*>(ws), counts, offsets, bucket_tok,
+    METEORA_HIP(launch_bucket(topk_idx, T, k, N, static_cast<int32_t*>(ws), false, counts, offsets, bucket_tok,
                               bucket_slot, static_cast<hipStream_t>(stream)));
     return METEORA_OK;
 }
@@ -217,7 +217,7 @@ static meteora_status check_lora_args(const void* x, const void* A, const void* 
 static meteora_status run_lora(const void* x, const void* W, const void* A, const void* B, const int32_t* topk_idx,
                                const float* topk_w, int T, int d_in, int d_out, int N, int r, int k, float scale,
                                bool bf16, void* out, int accumulate, void* ws, const WsLayout& L,
-                               hipStream_t st, int tslot) {
+                               hipStream_t st, int tslot, bool have_hist) {
     int32_t* offsets = at<int32_t>(ws, L.offsets);
     int32_t* btok = at<int32_t>(ws, L.bucket_tok);
     int32_t* bslot = at<int32_t>(ws, L.bucket_slot);
@@ -225,8 +225,8 @@ static meteora_status run_lora(const void* x, const void* W, const void* A, cons
     const bool fused = gemm_fuses_expand(bf16);
     {
         StageScope sc(ST_BUCKET, st, tslot);
-        METEORA_HIP(launch_bucket(topk_idx, T, k, N, at<int32_t>(ws, L.chunk_counts), at<int32_t>(ws, L.counts),
-                                  offsets, btok, bslot, st));
+        METEORA_HIP(launch_bucket(topk_idx, T, k, N, at<int32_t>(ws, L.chunk_counts), have_hist,
+                                  at<int32_t>(ws, L.counts), offsets, btok, bslot, st));
     }
     {
         StageScope sc(ST_SHRINK, st, tslot);
@@ -265,7 +265,7 @@ meteora_status meteora_lora_forward(const void* x, const void* A, const void* B,
     if (!ws || !aligned256(ws) || ws_bytes < L.total) return METEORA_ERR_WORKSPACE;
     if (T == 0) return METEORA_OK;
     return run_lora(x, nullptr, A, B, topk_idx, topk_w, T, d_in, d_out, N, r, k, scale, bf16, out, accumulate, ws, L,
-                    static_cast<hipStream_t>(stream), timing_begin_call());
+                    static_cast<hipStream_t>(stream), timing_begin_call(), false);
 }
 
 meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, int d_out, meteora_dtype dt,
@@ -307,9 +307,9 @@ meteora_status meteora_linear_forward(const void* x, const void* W, const float*
     {
         StageScope sc(ST_GATE_TOPK, st, tslot);
         METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, 1.0f, idx, w,
-                                     nullptr, st));
+                                     nullptr, at<int32_t>(ws, L.chunk_counts), st));
     }
-    return run_lora(x, W, A, B, idx, w, T, d_in, d_out, N, r, k, scale, bf16, out, 0, ws, L, st, tslot);
+    return run_lora(x, W, A, B, idx, w, T, d_in, d_out, N, r, k, scale, bf16, out, 0, ws, L, st, tslot, true);
 }
 
 }  // extern "C"

@@ -2,7 +2,8 @@
 // Sec. 3.3 (the X_i that "loop-original" gathers), kept as index lists instead of copies.
 //
 // The (token, slot) pairs, in flat order p = t*k + slot, are counting-sorted by adapter:
-//   pass 1  per-chunk histograms               chunk_counts[c][j]
+//   pass 1  per-chunk histograms               chunk_counts[c][j]   (a chunk = 64 tokens; the gate's
+//           top-k kernel writes them itself when the routing comes from the gate)
 //   pass 2  every chunk derives its own write base from chunk_counts (exclusive scan over
 //           adapters of the totals + counts of the earlier chunks), then scatters its pairs
 //           in order.  The in-chunk rank uses wavefront ballots, so the result is the stable
@@ -14,13 +15,14 @@
 namespace meteora {
 
 __global__ __launch_bounds__(256) void bucket_hist_kernel(const int32_t* __restrict__ topk_idx,
-                                                          int64_t pairs, int N,
+                                                          int64_t pairs, int k, int N,
                                                           int32_t* __restrict__ chunk_counts) {
     __shared__ int hist[kMaxAdapters];
     if (threadIdx.x < kMaxAdapters) hist[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kBucketChunkPairs;
-    for (int i = threadIdx.x; i < kBucketChunkPairs; i += 256) {
+    const int chunk_pairs = kBucketChunkTokens * k;
+    const int64_t base = (int64_t)blockIdx.x * chunk_pairs;
+    for (int i = threadIdx.x; i < chunk_pairs; i += 256) {
         const int64_t p = base + i;
         if (p < pairs) {
             const int key = topk_idx[p];
@@ -38,29 +40,29 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
                                                              int32_t* __restrict__ offsets,
                                                              int32_t* __restrict__ bucket_tok,
                                                              int32_t* __restrict__ bucket_slot) {
-    __shared__ int total[kMaxAdapters];      // pairs of adapter j over all chunks
-    __shared__ int before[kMaxAdapters];     // pairs of adapter j in earlier chunks
+    __shared__ int part_total[4][kMaxAdapters], part_before[4][kMaxAdapters];
     __shared__ int running[kMaxAdapters];    // next write position of adapter j for this chunk
     __shared__ int wave_hist[4][kMaxAdapters];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = blockIdx.x;
 
-    if (threadIdx.x < kMaxAdapters) {
+    {   // totals over all chunks and over the chunks before this one; wave w takes chunks w, w+4, ...
         int tot = 0, bef = 0;
-        if (threadIdx.x < N) {
-            for (int cc = 0; cc < nchunks; ++cc) {
-                const int v = chunk_counts[(size_t)cc * N + threadIdx.x];
+        if (lane < N) {
+            for (int cc = wave; cc < nchunks; cc += 4) {
+                const int v = chunk_counts[(size_t)cc * N + lane];
                 tot += v;
                 if (cc < c) bef += v;
             }
         }
-        total[threadIdx.x] = tot;
-        before[threadIdx.x] = bef;
+        part_total[wave][lane] = tot;
+        part_before[wave][lane] = bef;
     }
     __syncthreads();
     if (wave == 0) {
-        // exclusive scan of total[] over adapters inside one wavefront
-        const int v = total[lane];
+        // exclusive scan of the totals over adapters inside one wavefront
+        const int v = part_total[0][lane] + part_total[1][lane] + part_total[2][lane] + part_total[3][lane];
+        const int bef = part_before[0][lane] + part_before[1][lane] + part_before[2][lane] + part_before[3][lane];
         int incl = v;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
             if (lane >= off) incl += n;
         }
         const int excl = incl - v;
-        running[lane] = excl + before[lane];
+        running[lane] = excl + bef;
         if (c == 0) {
             if (lane < N) { counts[lane] = v; offsets[lane] = excl; }
             if (lane == N - 1) offsets[N] = incl;
@@ -76,10 +78,12 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
     }
     __syncthreads();
 
-    const int64_t base = (int64_t)c * kBucketChunkPairs;
-    for (int it = 0; it < kBucketChunkPairs / 256; ++it) {
-        const int64_t p = base + it * 256 + threadIdx.x;
-        int key = (p < pairs) ? topk_idx[p] : -1;
+    const int chunk_pairs = kBucketChunkTokens * k;
+    const int64_t base = (int64_t)c * chunk_pairs;
+    for (int it = 0; it * 256 < chunk_pairs; ++it) {
+        const int i = it * 256 + threadIdx.x;
+        const int64_t p = base + i;
+        int key = (i < chunk_pairs && p < pairs) ? topk_idx[p] : -1;
         if (key >= N) key = -1;
         const bool valid = key >= 0;
         // lanes of this wavefront that hold the same key
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
         const int rank_in_wave = __popcll(peers & below);
         const int peers_in_wave = __popcll(peers);
         wave_hist[wave][lane] = 0;
-        __syncthreads();   // wave_hist cleared (each wave clears its own row; sync orders vs. last round's reads)
+        __syncthreads();   // rows cleared (each wave clears its own); also orders against last round's reads
         if (valid && rank_in_wave == 0) wave_hist[wave][key] = peers_in_wave;
         __syncthreads();
         if (valid) {
@@ -110,14 +114,16 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
     }
 }
 
-hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* chunk_counts,
+hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* chunk_counts, bool have_hist,
                          int32_t* counts, int32_t* offsets, int32_t* bucket_tok, int32_t* bucket_slot,
                          hipStream_t stream) {
     const int64_t pairs = (int64_t)T * k;
-    const int nchunks = bucket_chunks(pairs);
-    bucket_hist_kernel<<<nchunks, 256, 0, stream>>>(topk_idx, pairs, N, chunk_counts);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const int nchunks = bucket_chunks(T);
+    if (!have_hist) {
+        bucket_hist_kernel<<<nchunks, 256, 0, stream>>>(topk_idx, pairs, k, N, chunk_counts);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     bucket_scatter_kernel<<<nchunks, 256, 0, stream>>>(topk_idx, pairs, k, N, nchunks, chunk_counts, counts,
                                                        offsets, bucket_tok, bucket_slot);
     return hipGetLastError();

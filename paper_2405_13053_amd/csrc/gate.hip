@@ -48,47 +48,66 @@ __device__ __forceinline__ void argmax_step(float& v, int& i, int offset) {
     if (take) { v = v2; i = i2; }
 }
 
+// A workgroup of 16 wavefronts owns one bucketing chunk of 64 tokens (4 per wavefront, their
+// partial-sum loads batched) and also leaves the chunk's adapter histogram for the scatter pass.
 constexpr int kTopkTokensPerWave = 4;
+constexpr int kTopkWaves = kBucketChunkTokens / kTopkTokensPerWave;
+static_assert(kTopkWaves * 64 <= 1024, "one workgroup per bucketing chunk");
 
-__global__ __launch_bounds__(256) void gate_topk_kernel(const float* __restrict__ partials, int KS,
-                                                        const float* __restrict__ bias, int T, int N,
-                                                        int NP, int k, float inv_temperature,
-                                                        int32_t* __restrict__ topk_idx,
-                                                        float* __restrict__ topk_w,
-                                                        float* __restrict__ logits) {
+__global__ __launch_bounds__(kTopkWaves * 64) void gate_topk_kernel(
+    const float* __restrict__ partials, int KS, const float* __restrict__ bias, int T, int N, int NP, int k,
+    float inv_temperature, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, float* __restrict__ logits,
+    int32_t* __restrict__ chunk_counts) {
+    __shared__ int hist[kMaxAdapters];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int t0 = (blockIdx.x * 4 + wave) * kTopkTokensPerWave;
-    const float b = (bias != nullptr && lane < N) ? bias[lane] : 0.f;
+    if (threadIdx.x < kMaxAdapters) hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int t0 = blockIdx.x * kBucketChunkTokens + wave * kTopkTokensPerWave;
+    float g[kTopkTokensPerWave];
+#pragma unroll
+    for (int i = 0; i < kTopkTokensPerWave; ++i) g[i] = 0.f;
+    if (lane < N) {
+        for (int s = 0; s < KS; ++s) {   // fixed order over K-slices; the 4 tokens' loads are independent
+#pragma unroll
+            for (int i = 0; i < kTopkTokensPerWave; ++i) {
+                const int t = min(t0 + i, T - 1);
+                g[i] += partials[((size_t)s * T + t) * NP + lane];
+            }
+        }
+        const float b = bias != nullptr ? bias[lane] : 0.f;
+#pragma unroll
+        for (int i = 0; i < kTopkTokensPerWave; ++i) g[i] += b;
+    }
+#pragma unroll
     for (int tt = 0; tt < kTopkTokensPerWave; ++tt) {
         const int t = t0 + tt;
-        if (t >= T) return;   // uniform per wave
-        float g = 0.f;
-        if (lane < N) {
-            for (int s = 0; s < KS; ++s) g += partials[((size_t)s * T + t) * NP + lane];
-            g += b;
-            if (logits) logits[(size_t)t * N + lane] = g;
-        }
-        bool live = lane < N;
-        float sel_g = 0.f;   // lane s < k keeps the s-th selected logit
-        int sel_i = 0;
-        for (int s = 0; s < k; ++s) {
-            float v = g;
-            int i = live ? lane : 0x7fffffff;
+        if (t < T) {   // uniform per wavefront
+            if (logits && lane < N) logits[(size_t)t * N + lane] = g[tt];
+            bool live = lane < N;
+            float sel_g = 0.f;   // lane s < k keeps the s-th selected logit
+            int sel_i = 0;
+            for (int s = 0; s < k; ++s) {
+                float v = g[tt];
+                int i = live ? lane : 0x7fffffff;
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) argmax_step(v, i, off);
-            if (lane == i) live = false;
-            if (lane == s) { sel_g = v; sel_i = i; }
-        }
-        const float gmax = __shfl(sel_g, 0);
-        float e = (lane < k) ? expf((sel_g - gmax) * inv_temperature) : 0.f;
-        float sum = e;
+                for (int off = 32; off >= 1; off >>= 1) argmax_step(v, i, off);
+                if (lane == i) live = false;
+                if (lane == s) { sel_g = v; sel_i = i; }
+            }
+            const float gmax = __shfl(sel_g, 0);
+            float e = (lane < k) ? expf((sel_g - gmax) * inv_temperature) : 0.f;
+            float sum = e;
 #pragma unroll
-        for (int off = 1; off < kMaxTopK; off <<= 1) sum += __shfl_xor(sum, off);
-        if (lane < k) {
-            topk_idx[(size_t)t * k + lane] = sel_i;
-            topk_w[(size_t)t * k + lane] = e / sum;
+            for (int off = 1; off < kMaxTopK; off <<= 1) sum += __shfl_xor(sum, off);
+            if (lane < k) {
+                topk_idx[(size_t)t * k + lane] = sel_i;
+                topk_w[(size_t)t * k + lane] = e / sum;
+                atomicAdd(&hist[sel_i], 1);
+            }
         }
     }
+    __syncthreads();
+    if (chunk_counts && threadIdx.x < N) chunk_counts[(size_t)blockIdx.x * N + threadIdx.x] = hist[threadIdx.x];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -292,12 +311,11 @@ hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_i
 
 hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, int T, int N, int k,
                             float inv_temperature, int32_t* topk_idx, float* topk_w, float* logits,
-                            hipStream_t stream) {
+                            int32_t* chunk_counts, hipStream_t stream) {
     const int NP = padded_adapters(N);
-    const int tokens_per_block = 4 * kTopkTokensPerWave;
-    gate_topk_kernel<<<ceil_div(T, tokens_per_block), 256, 0, stream>>>(partials, KS, bias, T, N, NP, k,
-                                                                        inv_temperature, topk_idx, topk_w,
-                                                                        logits);
+    gate_topk_kernel<<<bucket_chunks(T), kTopkWaves * 64, 0, stream>>>(partials, KS, bias, T, N, NP, k,
+                                                                     inv_temperature, topk_idx, topk_w, logits,
+                                                                     chunk_counts);
     return hipGetLastError();
 }
 

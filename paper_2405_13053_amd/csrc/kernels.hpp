@@ -15,14 +15,16 @@ int gate_kslices(int d_in, bool bf16);
 size_t gate_wsplit_bytes(int d_in, int N, bool bf16);
 hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_in, int N, bool bf16,
                               void* wsplit, float* partials, hipStream_t stream);
+// chunk_counts (optional): per-chunk adapter histograms [bucket_chunks(T)][N] for launch_bucket_scatter
 hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, int T, int N, int k,
                             float inv_temperature, int32_t* topk_idx, float* topk_w, float* logits,
-                            hipStream_t stream);
+                            int32_t* chunk_counts, hipStream_t stream);
 
 // ---- bucketing (Sec. 3.3: per-adapter token sets as index lists) --------------------------
-constexpr int kBucketChunkPairs = 1024;  // (token,slot) pairs handled by one workgroup
-inline int bucket_chunks(int64_t pairs) { return (int)((pairs + kBucketChunkPairs - 1) / kBucketChunkPairs); }
-hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* chunk_counts,
+constexpr int kBucketChunkTokens = 64;   // tokens (k pairs each) whose pairs one workgroup histograms and scatters
+inline int bucket_chunks(int T) { return (T + kBucketChunkTokens - 1) / kBucketChunkTokens; }
+// have_hist: chunk_counts already holds the histograms (written by launch_gate_topk)
+hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* chunk_counts, bool have_hist,
                          int32_t* counts, int32_t* offsets, int32_t* bucket_tok, int32_t* bucket_slot,
                          hipStream_t stream);
 

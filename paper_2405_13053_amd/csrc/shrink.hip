@@ -215,6 +215,9 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restri
 
 // Sum the K-slices (fixed order) and emit h32[pair][r] and/or the dense expand operand
 // hdense[t][a*r+q] = bf16(scale * w[t,slot] * h), zero where the token did not select adapter a.
+// One thread per 16-byte chunk (8 columns) of hdense.  R8 = (r % 8 == 0): the chunk lies inside one
+// adapter, so the thread decides once whether it is a zero chunk (most are) before touching hpart.
+template <bool R8>
 __global__ __launch_bounds__(256) void shrink_finalize_kernel(const float* __restrict__ hpart, int KS,
                                                               const int32_t* __restrict__ topk_idx,
                                                               const float* __restrict__ topk_w, int T, int N, int r,
@@ -227,21 +230,47 @@ __global__ __launch_bounds__(256) void shrink_finalize_kernel(const float* __res
         if (gid < (int64_t)T * cpr) {
             const int t = (int)(gid / cpr), c = (int)(gid % cpr);
             union { bf16_t h[8]; u32x4 v; } o;
+            if (R8) {
+                const int a = (c * 8) / r, q0 = c * 8 - a * r;
+                int slot = -1;
+                if (a < N)
+                    for (int s = 0; s < k; ++s)
+                        if (topk_idx[(size_t)t * k + s] == a) slot = s;
+                if (slot < 0) {
+                    o.v = u32x4{0u, 0u, 0u, 0u};
+                } else {
+                    const size_t pair = (size_t)t * k + slot;
+                    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+                    for (int ks = 0; ks < KS; ++ks) {
+                        const float* src = hpart + ((size_t)ks * pairs + pair) * r + q0;
+                        lo += *reinterpret_cast<const f32x4*>(src);
+                        hi += *reinterpret_cast<const f32x4*>(src + 4);
+                    }
+                    const float sw = scale * topk_w[pair];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int col = c * 8 + e;
-                const int a = col / r, q = col - a * r;
-                float val = 0.f;
-                if (a < N) {
-                    for (int slot = 0; slot < k; ++slot) {
-                        if (topk_idx[(size_t)t * k + slot] == a) {
-                            float s = 0.f;
-                            for (int ks = 0; ks < KS; ++ks) s += hpart[((size_t)ks * pairs + (size_t)t * k + slot) * r + q];
-                            val += scale * topk_w[(size_t)t * k + slot] * s;
-                        }
+                    for (int e = 0; e < 4; ++e) {
+                        o.h[e] = from_float<bf16_t>(sw * lo[e]);
+                        o.h[4 + e] = from_float<bf16_t>(sw * hi[e]);
                     }
                 }
-                o.h[e] = from_float<bf16_t>(val);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int col = c * 8 + e;
+                    const int a = col / r, q = col - a * r;
+                    float val = 0.f;
+                    if (a < N) {
+                        for (int slot = 0; slot < k; ++slot) {
+                            if (topk_idx[(size_t)t * k + slot] == a) {
+                                float s = 0.f;
+                                for (int ks = 0; ks < KS; ++ks)
+                                    s += hpart[((size_t)ks * pairs + (size_t)t * k + slot) * r + q];
+                                val = scale * topk_w[(size_t)t * k + slot] * s;
+                            }
+                        }
+                    }
+                    o.h[e] = from_float<bf16_t>(val);
+                }
             }
             *reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride + c * 8) = o.v;
         }
@@ -309,8 +338,12 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
         int64_t work = 0;
         if (hdense) work = (int64_t)T * (ext_stride / 8);
         if (h32 && pairs * r > work) work = pairs * r;
-        shrink_finalize_kernel<<<(unsigned)ceil_div64(work, 256), 256, 0, stream>>>(
-            hpart, KS, topk_idx, topk_w, T, N, r, k, scale, h32, (bf16_t*)hdense, ext_stride);
+        if (r % 8 == 0)
+            shrink_finalize_kernel<true><<<(unsigned)ceil_div64(work, 256), 256, 0, stream>>>(
+                hpart, KS, topk_idx, topk_w, T, N, r, k, scale, h32, (bf16_t*)hdense, ext_stride);
+        else
+            shrink_finalize_kernel<false><<<(unsigned)ceil_div64(work, 256), 256, 0, stream>>>(
+                hpart, KS, topk_idx, topk_w, T, N, r, k, scale, h32, (bf16_t*)hdense, ext_stride);
         return hipGetLastError();
     }
     int RP = 1;
