@@ -142,8 +142,8 @@ meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, 
 /*
  * Optional per-stage timing, for benchmarks.  Host only; off by default.
  * While enabled, meteora_lora_forward and meteora_linear_forward record
- * hipEvents on `stream` around each stage (gate_logits, gate_topk, bucket,
- * shrink, gemm, expand) for up to 256 calls.  meteora_stage_timing_read waits
+ * hipEvents on `stream` around each stage (prep, gate_logits, gate_topk,
+ * bucket, shrink, gemm, expand) for up to 256 calls.  meteora_stage_timing_read waits
  * for those events, returns per stage the summed milliseconds and the number
  * of timed launches (arrays of meteora_stage_count() entries, host memory)
  * and the number of calls covered, and starts a new window.  Not thread-safe;

@@ -62,7 +62,7 @@ template <typename T> T* at(void* ws, size_t off) { return reinterpret_cast<T*>(
     } while (0)
 
 // ---- optional per-stage timing (off by default; hipEvents recorded between the launches) ----
-enum Stage { ST_GATE_LOGITS = 0, ST_GATE_TOPK, ST_BUCKET, ST_SHRINK, ST_GEMM, ST_EXPAND, ST_COUNT };
+enum Stage { ST_PREP = 0, ST_GATE_LOGITS, ST_GATE_TOPK, ST_BUCKET, ST_SHRINK, ST_GEMM, ST_EXPAND, ST_COUNT };
 constexpr int kTimingRing = 256;
 struct StageTiming {
     bool on = false;
@@ -95,7 +95,7 @@ extern "C" {
 int meteora_stage_count(void) { return ST_COUNT; }
 
 const char* meteora_stage_name(int stage) {
-    static const char* names[ST_COUNT] = {"gate_logits", "gate_topk", "bucket", "shrink", "gemm", "expand"};
+    static const char* names[ST_COUNT] = {"prep", "gate_logits", "gate_topk", "bucket", "shrink", "gemm", "expand"};
     return (stage >= 0 && stage < ST_COUNT) ? names[stage] : "";
 }
 
@@ -175,6 +175,8 @@ meteora_status meteora_gate_topk(const void* x, const float* W_gate, const float
     if (T == 0) return METEORA_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* partials = at<float>(ws, L.partials);
+    if (gate_wsplit_bytes(d_in, N, bf16) > 0)
+        METEORA_HIP(launch_prep(W_gate, at<void>(ws, L.wsplit), nullptr, nullptr, d_in, N, 1, st));
     METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, at<void>(ws, L.wsplit), partials, st));
     METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, inv_temperature,
                                  topk_idx, topk_w, logits, nullptr, st));
@@ -264,6 +266,9 @@ meteora_status meteora_lora_forward(const void* x, const void* A, const void* B,
     const WsLayout L = ws_layout(T, d_in, d_out, N, r, k, bf16);
     if (!ws || !aligned256(ws) || ws_bytes < L.total) return METEORA_ERR_WORKSPACE;
     if (T == 0) return METEORA_OK;
+    if (shrink_apack_bytes(d_in, N, r, bf16) > 0)
+        METEORA_HIP(launch_prep(nullptr, nullptr, A, at<void>(ws, L.apack), d_in, N, r,
+                                static_cast<hipStream_t>(stream)));
     return run_lora(x, nullptr, A, B, topk_idx, topk_w, T, d_in, d_out, N, r, k, scale, bf16, out, accumulate, ws, L,
                     static_cast<hipStream_t>(stream), timing_begin_call(), false);
 }
@@ -300,6 +305,12 @@ meteora_status meteora_linear_forward(const void* x, const void* W, const float*
     float* w = topk_w_out ? topk_w_out : at<float>(ws, L.topk_w);
     float* partials = at<float>(ws, L.partials);
     const int tslot = timing_begin_call();
+    {
+        StageScope sc(ST_PREP, st, tslot);
+        const bool pw = gate_wsplit_bytes(d_in, N, bf16) > 0, pa = shrink_apack_bytes(d_in, N, r, bf16) > 0;
+        METEORA_HIP(launch_prep(pw ? W_gate : nullptr, pw ? at<void>(ws, L.wsplit) : nullptr, pa ? A : nullptr,
+                                pa ? at<void>(ws, L.apack) : nullptr, d_in, N, r, st));
+    }
     {
         StageScope sc(ST_GATE_LOGITS, st, tslot);
         METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, at<void>(ws, L.wsplit), partials, st));

@@ -7,6 +7,7 @@
 //      top-k with a wavefront-wide arg-max (ties -> lowest adapter index), softmax over the k.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "prep.hpp"
 
 namespace meteora {
 
@@ -38,72 +39,100 @@ __global__ __launch_bounds__(256) void gate_logits_fma_kernel(const TX* __restri
 }
 
 // ------------------------------------------------------------------------------------------
-// Stage 2: one wavefront per token.
+// Stage 2: wavefront-level top-k.
+//
+// A token's NP (32 or 64) logit columns sit in NP adjacent lanes, so a wavefront ranks 64/NP tokens
+// at a time.  A logit and its adapter index are packed into one 64-bit key, (order-preserving bits
+// of the fp32 value) << 32 | (0xffffffff - index), so the wavefront-wide maximum of the keys is the
+// largest logit with the LOWEST index among equal logits: exactly the tie-break of the layer.  Lanes
+// that are padding or already selected carry key 0 and can never win.  Selecting k adapters is k
+// butterfly maxima (log2(NP) shuffles each); the groups a wavefront owns are interleaved so their
+// shuffle latencies overlap.
+//
+// A workgroup of 16 wavefronts owns one bucketing chunk of 64 tokens (4 per wavefront) and also
+// leaves the chunk's adapter histogram for the scatter pass.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ void argmax_step(float& v, int& i, int offset) {
-    const float v2 = __shfl_xor(v, offset);
-    const int i2 = __shfl_xor(i, offset);
-    // candidates that are out of play carry i = INT_MAX and lose every comparison
-    const bool take = (i2 != 0x7fffffff) && (i == 0x7fffffff || v2 > v || (v2 == v && i2 < i));
-    if (take) { v = v2; i = i2; }
-}
-
-// A workgroup of 16 wavefronts owns one bucketing chunk of 64 tokens (4 per wavefront, their
-// partial-sum loads batched) and also leaves the chunk's adapter histogram for the scatter pass.
 constexpr int kTopkTokensPerWave = 4;
 constexpr int kTopkWaves = kBucketChunkTokens / kTopkTokensPerWave;
 static_assert(kTopkWaves * 64 <= 1024, "one workgroup per bucketing chunk");
 
+__device__ __forceinline__ uint64_t logit_key(float g, int index) {
+    uint32_t u = __float_as_uint(g);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // monotonic map of finite floats to unsigned; -0 < +0 never ties with an index swap
+    return ((uint64_t)u << 32) | (uint64_t)(0xffffffffu - (uint32_t)index);
+}
+__device__ __forceinline__ float key_logit(uint64_t key) {
+    uint32_t u = (uint32_t)(key >> 32);
+    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+    return __uint_as_float(u);
+}
+
+template <int NP>
 __global__ __launch_bounds__(kTopkWaves * 64) void gate_topk_kernel(
-    const float* __restrict__ partials, int KS, const float* __restrict__ bias, int T, int N, int NP, int k,
+    const float* __restrict__ partials, int KS, const float* __restrict__ bias, int T, int N, int k,
     float inv_temperature, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, float* __restrict__ logits,
     int32_t* __restrict__ chunk_counts) {
+    constexpr int TPP = 64 / NP;                     // tokens ranked per pass
+    constexpr int G = kTopkTokensPerWave / TPP;      // passes (groups) per wavefront
     __shared__ int hist[kMaxAdapters];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & (NP - 1), sub = lane / NP;
     if (threadIdx.x < kMaxAdapters) hist[threadIdx.x] = 0;
     __syncthreads();
     const int t0 = blockIdx.x * kBucketChunkTokens + wave * kTopkTokensPerWave;
-    float g[kTopkTokensPerWave];
+
+    float g[G];
+    int tok[G];
 #pragma unroll
-    for (int i = 0; i < kTopkTokensPerWave; ++i) g[i] = 0.f;
-    if (lane < N) {
-        for (int s = 0; s < KS; ++s) {   // fixed order over K-slices; the 4 tokens' loads are independent
+    for (int i = 0; i < G; ++i) { g[i] = 0.f; tok[i] = t0 + i * TPP + sub; }
+    if (col < N) {
+        for (int s = 0; s < KS; ++s) {   // fixed order over K-slices; the groups' loads are independent
 #pragma unroll
-            for (int i = 0; i < kTopkTokensPerWave; ++i) {
-                const int t = min(t0 + i, T - 1);
-                g[i] += partials[((size_t)s * T + t) * NP + lane];
+            for (int i = 0; i < G; ++i) g[i] += partials[((size_t)s * T + min(tok[i], T - 1)) * NP + col];
+        }
+        const float b = bias != nullptr ? bias[col] : 0.f;
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            g[i] += b;
+            if (g[i] == 0.f) g[i] = 0.f;   // -0 -> +0 so equal logits have equal keys
+            if (logits && tok[i] < T) logits[(size_t)tok[i] * N + col] = g[i];
+        }
+    }
+    uint64_t key[G];
+    float sel_g[G];   // lane col = s < k of each token keeps its s-th selected logit and index
+    int sel_i[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) { key[i] = col < N ? logit_key(g[i], col) : 0ull; sel_g[i] = 0.f; sel_i[i] = 0; }
+    for (int s = 0; s < k; ++s) {
+        uint64_t best[G];
+#pragma unroll
+        for (int i = 0; i < G; ++i) best[i] = key[i];
+#pragma unroll
+        for (int off = NP / 2; off >= 1; off >>= 1) {
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                const uint64_t o = __shfl_xor((unsigned long long)best[i], off);
+                best[i] = o > best[i] ? o : best[i];
             }
         }
-        const float b = bias != nullptr ? bias[lane] : 0.f;
 #pragma unroll
-        for (int i = 0; i < kTopkTokensPerWave; ++i) g[i] += b;
+        for (int i = 0; i < G; ++i) {
+            const int win = (int)(0xffffffffu - (uint32_t)best[i]);
+            if (col == win) key[i] = 0ull;
+            if (col == s) { sel_g[i] = key_logit(best[i]); sel_i[i] = win; }
+        }
     }
 #pragma unroll
-    for (int tt = 0; tt < kTopkTokensPerWave; ++tt) {
-        const int t = t0 + tt;
-        if (t < T) {   // uniform per wavefront
-            if (logits && lane < N) logits[(size_t)t * N + lane] = g[tt];
-            bool live = lane < N;
-            float sel_g = 0.f;   // lane s < k keeps the s-th selected logit
-            int sel_i = 0;
-            for (int s = 0; s < k; ++s) {
-                float v = g[tt];
-                int i = live ? lane : 0x7fffffff;
+    for (int i = 0; i < G; ++i) {
+        const float gmax = __shfl(sel_g[i], lane & ~(NP - 1));
+        const float e = (col < k) ? expf((sel_g[i] - gmax) * inv_temperature) : 0.f;
+        float sum = e;
 #pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) argmax_step(v, i, off);
-                if (lane == i) live = false;
-                if (lane == s) { sel_g = v; sel_i = i; }
-            }
-            const float gmax = __shfl(sel_g, 0);
-            float e = (lane < k) ? expf((sel_g - gmax) * inv_temperature) : 0.f;
-            float sum = e;
-#pragma unroll
-            for (int off = 1; off < kMaxTopK; off <<= 1) sum += __shfl_xor(sum, off);
-            if (lane < k) {
-                topk_idx[(size_t)t * k + lane] = sel_i;
-                topk_w[(size_t)t * k + lane] = e / sum;
-                atomicAdd(&hist[sel_i], 1);
-            }
+        for (int off = 1; off < kMaxTopK; off <<= 1) sum += __shfl_xor(sum, off);
+        if (col < k && tok[i] < T) {
+            topk_idx[(size_t)tok[i] * k + col] = sel_i[i];
+            topk_w[(size_t)tok[i] * k + col] = e / sum;
+            atomicAdd(&hist[sel_i[i]], 1);
         }
     }
     __syncthreads();
@@ -131,44 +160,9 @@ __global__ __launch_bounds__(kTopkWaves * 64) void gate_topk_kernel(
 // partials[ks][t][NP]; the top-k kernel adds the K-slices in order.
 // ------------------------------------------------------------------------------------------
 constexpr int kGateTM = 128;        // tokens per workgroup
-constexpr int kGateKSL = 512;       // K-slice per workgroup
-constexpr int kGateKW = 128;        // K per wavefront
+constexpr int kGateKSL = kSkinnyKSL; // K-slice per workgroup
+constexpr int kGateKW = kSkinnyKW;   // K per wavefront
 constexpr int kGateRegion = 36864;  // LDS bytes per wavefront (x piece 32 KB; reused for the reduction)
-
-// Split W_gate into bf16 hi/mid/lo in MFMA operand order.
-// Block index b = (((ks*4 + wq)*8 + s)*3 + sp)*NCB + cb ; inside a block lane l holds 8 k-values
-// k = ks*512 + wq*128 + s*16 + (l>>5)*8 + j  of column n = cb*32 + (l&31).
-__global__ __launch_bounds__(256) void gate_wsplit_kernel(const float* __restrict__ W_gate, int d_in, int N,
-                                                          int NCB, int KS, u32x4* __restrict__ wsp) {
-    const int frag = blockIdx.x * 4 + (threadIdx.x >> 6);   // (ks, wq, s, cb) without the split index
-    const int lane = threadIdx.x & 63;
-    const int total = KS * 4 * 8 * NCB;
-    if (frag >= total) return;
-    const int cb = frag % NCB;
-    const int s = (frag / NCB) % 8;
-    const int wq = (frag / (NCB * 8)) % 4;
-    const int ks = frag / (NCB * 32);
-    const int n = cb * 32 + (lane & 31);
-    const int k0 = ks * kGateKSL + wq * kGateKW + s * 16 + (lane >> 5) * 8;
-    union { uint16_t h[8]; u32x4 v; } hi, mid, lo;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int k = k0 + j;
-        const float w = (k < d_in && n < N) ? W_gate[(size_t)k * N + n] : 0.f;
-        const bf16_t h = static_cast<bf16_t>(w);
-        const float r1 = w - static_cast<float>(h);
-        const bf16_t m = static_cast<bf16_t>(r1);
-        const float r2 = r1 - static_cast<float>(m);
-        const bf16_t l = static_cast<bf16_t>(r2);
-        hi.h[j] = __builtin_bit_cast(uint16_t, h);
-        mid.h[j] = __builtin_bit_cast(uint16_t, m);
-        lo.h[j] = __builtin_bit_cast(uint16_t, l);
-    }
-    const size_t base = ((size_t)((ks * 4 + wq) * 8 + s) * 3 * NCB + cb) * 64 + lane;
-    wsp[base] = hi.v;
-    wsp[base + (size_t)NCB * 64] = mid.v;
-    wsp[base + (size_t)2 * NCB * 64] = lo.v;
-}
 
 template <int NCB>
 __global__ __launch_bounds__(256) void gate_logits_mfma_kernel(const bf16_t* __restrict__ x,
@@ -284,10 +278,7 @@ hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_i
         return hipGetLastError();
     }
     const int KS = gate_kslices(d_in, true), NCB = NP / 32;
-    const int frags = KS * 4 * 8 * NCB;
-    gate_wsplit_kernel<<<ceil_div(frags, 4), 256, 0, stream>>>(W_gate, d_in, N, NCB, KS, (u32x4*)wsplit);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    hipError_t e;   // wsplit has been filled by launch_prep
     constexpr int smem = 4 * kGateRegion;
     static bool attr_set = false;
     if (!attr_set) {
@@ -312,10 +303,12 @@ hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_i
 hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, int T, int N, int k,
                             float inv_temperature, int32_t* topk_idx, float* topk_w, float* logits,
                             int32_t* chunk_counts, hipStream_t stream) {
-    const int NP = padded_adapters(N);
-    gate_topk_kernel<<<bucket_chunks(T), kTopkWaves * 64, 0, stream>>>(partials, KS, bias, T, N, NP, k,
-                                                                     inv_temperature, topk_idx, topk_w, logits,
-                                                                     chunk_counts);
+    if (padded_adapters(N) == 32)
+        gate_topk_kernel<32><<<bucket_chunks(T), kTopkWaves * 64, 0, stream>>>(
+            partials, KS, bias, T, N, k, inv_temperature, topk_idx, topk_w, logits, chunk_counts);
+    else
+        gate_topk_kernel<64><<<bucket_chunks(T), kTopkWaves * 64, 0, stream>>>(
+            partials, KS, bias, T, N, k, inv_temperature, topk_idx, topk_w, logits, chunk_counts);
     return hipGetLastError();
 }
 

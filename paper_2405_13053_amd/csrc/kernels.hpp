@@ -8,6 +8,12 @@
 
 namespace meteora {
 
+// ---- weight repacking, one launch: W_gate -> split bf16 fragments (bf16 gate), A -> MFMA fragments -----
+// Either pair (W_gate, wsplit) / (A, apack) may be NULL to skip it; sizes are gate_wsplit_bytes and
+// shrink_apack_bytes (0 = that operand is not packed for this dtype/rank: pass NULL).
+hipError_t launch_prep(const float* W_gate, void* wsplit, const void* A, void* apack, int d_in, int N, int r,
+                       hipStream_t stream);
+
 // ---- gate (Sec. 3.1: G(x), I(x), Eq. 3) ------------------------------------------------
 // Number of K-slices the logit kernel splits d_in into (partials[KS][T][NP]).
 int gate_kslices(int d_in, bool bf16);

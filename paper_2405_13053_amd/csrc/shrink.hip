@@ -4,6 +4,7 @@
 // adapter, so A_a is fetched once per tile and the gathered token rows stream past it.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "prep.hpp"
 
 namespace meteora {
 
@@ -59,30 +60,9 @@ __global__ __launch_bounds__(256) void shrink_fma_kernel(const TX* __restrict__ 
 // writes the dense bf16 operand of the fused expand (zero for adapters a token did not pick).
 // ------------------------------------------------------------------------------------------
 constexpr int kShrTM = 128;
-constexpr int kShrKSL = 512;
-constexpr int kShrKW = 128;
+constexpr int kShrKSL = kSkinnyKSL;
+constexpr int kShrKW = kSkinnyKW;
 constexpr int kShrRegion = 36864;
-
-// A[N, d_in, r] -> apk: block ((a*S16 + s16)*RCB + cb), lane l holds A[a][s16*16 + (l>>5)*8 + j][cb*32 + (l&31)].
-__global__ __launch_bounds__(256) void shrink_apack_kernel(const bf16_t* __restrict__ A, int d_in, int N, int r,
-                                                           int RCB, int S16, u32x4* __restrict__ apk) {
-    const int64_t frag = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (frag >= (int64_t)N * S16 * RCB) return;
-    const int cb = (int)(frag % RCB);
-    const int s16 = (int)((frag / RCB) % S16);
-    const int a = (int)(frag / ((int64_t)RCB * S16));
-    const int q = cb * 32 + (lane & 31);
-    const int k0 = s16 * 16 + (lane >> 5) * 8;
-    union { uint16_t h[8]; u32x4 v; } p;
-    const uint16_t* Aa = reinterpret_cast<const uint16_t*>(A) + (size_t)a * d_in * r;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int kk = k0 + j;
-        p.h[j] = (kk < d_in && q < r) ? Aa[(size_t)kk * r + q] : (uint16_t)0;
-    }
-    apk[frag * 64 + lane] = p.v;
-}
 
 template <int RCB>
 __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restrict__ x, const u32x4* __restrict__ apk,
@@ -308,11 +288,7 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
     const int64_t pairs = (int64_t)T * k;
     if (shrink_uses_mfma(bf16, r)) {
         const int KS = shrink_kslices(d_in), RCB = ceil_div(r, 32), S16 = KS * (kShrKSL / 16);
-        const int64_t frags = (int64_t)N * S16 * RCB;
-        shrink_apack_kernel<<<(unsigned)ceil_div64(frags, 4), 256, 0, stream>>>((const bf16_t*)A, d_in, N, r, RCB,
-                                                                                 S16, (u32x4*)apack);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+        hipError_t e;   // apack has been filled by launch_prep
         constexpr int smem = 4 * kShrRegion;
         static bool attr_set = false;
         if (!attr_set) {
