@@ -159,28 +159,33 @@ __global__ __launch_bounds__(kTopkWaves * 64) void gate_topk_kernel(
 // The 4 partial tiles are summed through LDS in a fixed order and written as
 // partials[ks][t][NP]; the top-k kernel adds the K-slices in order.
 // ------------------------------------------------------------------------------------------
-constexpr int kGateTM = 128;        // tokens per workgroup
 constexpr int kGateKSL = kSkinnyKSL; // K-slice per workgroup
 constexpr int kGateKW = kSkinnyKW;   // K per wavefront
-constexpr int kGateRegion = 36864;  // LDS bytes per wavefront (x piece 32 KB; reused for the reduction)
+// LDS bytes per wavefront: its RB*32 x 256 B piece of x, reused for the padded fp32 reduction tile
+__host__ __device__ constexpr int gate_region_bytes(int NCB, int RB) {
+    const int xbytes = RB * 32 * 256, red = RB * 32 * (NCB * 128 + 16);
+    return (int)align_up((size_t)(xbytes > red ? xbytes : red), 1024);
+}
 
-template <int NCB>
+template <int NCB, int RB>
 __global__ __launch_bounds__(256) void gate_logits_mfma_kernel(const bf16_t* __restrict__ x,
                                                                const u32x4* __restrict__ wsp, int T, int d_in,
                                                                int KS, float* __restrict__ partials) {
     constexpr int NP = NCB * 32;
+    constexpr int TM = RB * 32;                                   // tokens per workgroup
+    constexpr int kRegion = gate_region_bytes(NCB, RB);           // LDS bytes per wavefront
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int lane = threadIdx.x & 63, wq = threadIdx.x >> 6;
     const int ks = blockIdx.x % KS, tile = blockIdx.x / KS;
-    const int t0 = tile * kGateTM;
-    unsigned char* region = smem + wq * kGateRegion;
+    const int t0 = tile * TM;
+    unsigned char* region = smem + wq * kRegion;
     const int kbase = ks * kGateKSL + wq * kGateKW;
 
     // ---- x piece: 128 rows x 256 B, HBM -> LDS, 4 rows per instruction --------------------
     {
         const int rsub = lane >> 4, p = lane & 15;
 #pragma unroll
-        for (int j = 0; j < 32; ++j) {
+        for (int j = 0; j < RB * 8; ++j) {
             const int row = 4 * j + rsub;
             int t = t0 + row;
             t = t < T ? t : T - 1;
@@ -208,9 +213,9 @@ __global__ __launch_bounds__(256) void gate_logits_mfma_kernel(const bf16_t* __r
     __builtin_amdgcn_s_waitcnt(0);   // everything issued above has landed (vmcnt = lgkmcnt = 0)
     __builtin_amdgcn_wave_barrier();
 
-    f32x16 acc[4][NCB];
+    f32x16 acc[RB][NCB];
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
@@ -220,7 +225,7 @@ __global__ __launch_bounds__(256) void gate_logits_mfma_kernel(const bf16_t* __r
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
+        for (int rb = 0; rb < RB; ++rb) {
             const int row = rb * 32 + lrow;
             const int pos = (s * 2 + khalf) ^ (row & 15);
             const bf16x8 xf = *reinterpret_cast<const bf16x8*>(region + row * 256 + pos * 16);
@@ -237,7 +242,7 @@ __global__ __launch_bounds__(256) void gate_logits_mfma_kernel(const bf16_t* __r
     constexpr int kRowBytes = NP * 4 + 16;   // padded: consecutive tokens start 4 banks apart
     __builtin_amdgcn_wave_barrier();          // this wavefront's own ds_reads are done before it overwrites
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
@@ -249,15 +254,15 @@ __global__ __launch_bounds__(256) void gate_logits_mfma_kernel(const bf16_t* __r
             }
     __syncthreads();
     constexpr int kChunksPerRow = NP / 4;
-    for (int c = threadIdx.x; c < kGateTM * kChunksPerRow; c += 256) {
+    for (int c = threadIdx.x; c < TM * kChunksPerRow; c += 256) {
         const int m = c / kChunksPerRow, n4 = c % kChunksPerRow;
         const int t = t0 + m;
         if (t >= T) continue;
         const int off = m * kRowBytes + n4 * 16;
         f32x4 v0 = *reinterpret_cast<const f32x4*>(smem + off);
-        f32x4 v1 = *reinterpret_cast<const f32x4*>(smem + kGateRegion + off);
-        f32x4 v2 = *reinterpret_cast<const f32x4*>(smem + 2 * kGateRegion + off);
-        f32x4 v3 = *reinterpret_cast<const f32x4*>(smem + 3 * kGateRegion + off);
+        f32x4 v1 = *reinterpret_cast<const f32x4*>(smem + kRegion + off);
+        f32x4 v2 = *reinterpret_cast<const f32x4*>(smem + 2 * kRegion + off);
+        f32x4 v3 = *reinterpret_cast<const f32x4*>(smem + 3 * kRegion + off);
         f32x4 r = (v0 + v1) + (v2 + v3);
         *reinterpret_cast<f32x4*>(partials + ((size_t)ks * T + t) * NP + n4 * 4) = r;
     }
@@ -278,26 +283,21 @@ hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_i
         return hipGetLastError();
     }
     const int KS = gate_kslices(d_in, true), NCB = NP / 32;
-    hipError_t e;   // wsplit has been filled by launch_prep
-    constexpr int smem = 4 * kGateRegion;
-    static bool attr_set = false;
-    if (!attr_set) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_logits_mfma_kernel<1>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_logits_mfma_kernel<2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    const int grid = ceil_div(T, kGateTM) * KS;
-    if (NCB == 1)
-        gate_logits_mfma_kernel<1><<<grid, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)wsplit, T, d_in, KS,
-                                                                partials);
-    else
-        gate_logits_mfma_kernel<2><<<grid, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)wsplit, T, d_in, KS,
-                                                                partials);
-    return hipGetLastError();
+    // wsplit has been filled by launch_prep
+    // 64 tokens per workgroup (two workgroups share a CU and overlap load with compute) unless the batch
+    // is large enough that 128-token workgroups, which reuse each W fragment twice as often, still fill the chip
+    const bool big = (int64_t)ceil_div(T, 128) * KS >= 1024;
+    auto launch = [&](auto kern, int rb) -> hipError_t {
+        const int smem = 4 * gate_region_bytes(NCB, rb);
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (err != hipSuccess) return err;
+        kern<<<ceil_div(T, rb * 32) * KS, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)wsplit, T, d_in, KS,
+                                                              partials);
+        return hipGetLastError();
+    };
+    if (NCB == 1) return big ? launch(gate_logits_mfma_kernel<1, 4>, 4) : launch(gate_logits_mfma_kernel<1, 2>, 2);
+    return big ? launch(gate_logits_mfma_kernel<2, 4>, 4) : launch(gate_logits_mfma_kernel<2, 2>, 2);
 }
 
 hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, int T, int N, int k,

@@ -59,19 +59,23 @@ __global__ __launch_bounds__(256) void shrink_fma_kernel(const TX* __restrict__ 
 // added, again in a fixed order, by the finalize kernel, which also applies scale * w and
 // writes the dense bf16 operand of the fused expand (zero for adapters a token did not pick).
 // ------------------------------------------------------------------------------------------
-constexpr int kShrTM = 128;
 constexpr int kShrKSL = kSkinnyKSL;
 constexpr int kShrKW = kSkinnyKW;
-constexpr int kShrRegion = 36864;
+__host__ __device__ constexpr int shrink_region_bytes(int RCB, int RB) {
+    const int xbytes = RB * 32 * 256, red = RB * 32 * (RCB * 128 + 16);
+    return (int)align_up((size_t)(xbytes > red ? xbytes : red), 1024);
+}
 
-template <int RCB>
+template <int RCB, int RB>
 __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restrict__ x, const u32x4* __restrict__ apk,
                                                           const int32_t* __restrict__ offsets,
                                                           const int32_t* __restrict__ bucket_tok,
                                                           const int32_t* __restrict__ bucket_slot, int T, int d_in,
                                                           int N, int r, int k, int KS, float* __restrict__ hpart) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    __shared__ int pair_of_row[kShrTM];
+    constexpr int TM = RB * 32;                              // pairs per tile
+    constexpr int kRegion = shrink_region_bytes(RCB, RB);    // LDS bytes per wavefront
+    __shared__ int pair_of_row[TM];
     const int lane = threadIdx.x & 63, wq = threadIdx.x >> 6;
     const int ks = blockIdx.x % KS, tile_id = blockIdx.x / KS;
 
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restri
     int a, row_start, nrows;
     {
         const int lo = (lane < N) ? offsets[lane] : 0, hi = (lane < N) ? offsets[lane + 1] : 0;
-        const int tiles = ceil_div(hi - lo, kShrTM);
+        const int tiles = ceil_div(hi - lo, TM);
         int incl = tiles;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -91,13 +95,13 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restri
         a = __ffsll((long long)m) - 1;
         const int excl = __shfl(incl - tiles, a);
         const int blo = __shfl(lo, a), bhi = __shfl(hi, a);
-        row_start = blo + (tile_id - excl) * kShrTM;
-        nrows = min(kShrTM, bhi - row_start);
+        row_start = blo + (tile_id - excl) * TM;
+        nrows = min(TM, bhi - row_start);
     }
     // tokens of the tile: lane l holds rows l and 64+l (clamped to the first row past the end)
     int tok0, tok1;
     {
-        const int r0 = lane < nrows ? lane : 0, r1 = 64 + lane < nrows ? 64 + lane : 0;
+        const int r0 = lane < nrows ? lane : 0, r1 = (TM > 64 && 64 + lane < nrows) ? 64 + lane : 0;
         tok0 = bucket_tok[row_start + r0];
         tok1 = bucket_tok[row_start + r1];
         tok0 = min(max(tok0, 0), T - 1);
@@ -105,17 +109,17 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restri
         if (wq == 0) {
             const int s0 = bucket_slot[row_start + r0], s1 = bucket_slot[row_start + r1];
             pair_of_row[lane] = tok0 * k + min(max(s0, 0), k - 1);
-            pair_of_row[64 + lane] = tok1 * k + min(max(s1, 0), k - 1);
+            if (TM > 64) pair_of_row[64 + lane] = tok1 * k + min(max(s1, 0), k - 1);
         }
     }
-    unsigned char* region = smem + wq * kShrRegion;
+    unsigned char* region = smem + wq * kRegion;
     const int kbase = ks * kShrKSL + wq * kShrKW;
     const int nrb = ceil_div(nrows, 32);   // row blocks that hold at least one pair
 
     {
         const int rsub = lane >> 4, p = lane & 15;
 #pragma unroll
-        for (int j = 0; j < 32; ++j) {
+        for (int j = 0; j < RB * 8; ++j) {
             if ((j >> 3) < nrb) {   // uniform
                 const int row = 4 * j + rsub;
                 const int t = __shfl(row < 64 ? tok0 : tok1, row & 63);
@@ -143,9 +147,9 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restri
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_wave_barrier();
 
-    f32x16 acc[4][RCB];
+    f32x16 acc[RB][RCB];
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < RCB; ++cb)
 #pragma unroll
@@ -153,7 +157,7 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restri
 
     const int lrow = lane & 31, khalf = lane >> 5;
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
+    for (int rb = 0; rb < RB; ++rb) {
         if (rb < nrb) {
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
@@ -170,7 +174,7 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restri
     constexpr int kRowBytes = RCB * 128 + 16;
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < RCB; ++cb)
 #pragma unroll
@@ -186,9 +190,9 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restri
         const int m = e / r, q = e - m * r;
         const int off = m * kRowBytes + q * 4;
         const float v0 = *reinterpret_cast<const float*>(smem + off);
-        const float v1 = *reinterpret_cast<const float*>(smem + kShrRegion + off);
-        const float v2 = *reinterpret_cast<const float*>(smem + 2 * kShrRegion + off);
-        const float v3 = *reinterpret_cast<const float*>(smem + 3 * kShrRegion + off);
+        const float v1 = *reinterpret_cast<const float*>(smem + kRegion + off);
+        const float v2 = *reinterpret_cast<const float*>(smem + 2 * kRegion + off);
+        const float v3 = *reinterpret_cast<const float*>(smem + 3 * kRegion + off);
         hpart[((size_t)ks * pairs + pair_of_row[m]) * r + q] = (v0 + v1) + (v2 + v3);
     }
 }
@@ -288,28 +292,24 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
     const int64_t pairs = (int64_t)T * k;
     if (shrink_uses_mfma(bf16, r)) {
         const int KS = shrink_kslices(d_in), RCB = ceil_div(r, 32), S16 = KS * (kShrKSL / 16);
-        hipError_t e;   // apack has been filled by launch_prep
-        constexpr int smem = 4 * kShrRegion;
-        static bool attr_set = false;
-        if (!attr_set) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shrink_mfma_kernel<1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-            if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&shrink_mfma_kernel<2>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        // upper bound of the tile count: every bucket rounds up by at most one tile
-        const int max_tiles = (int)ceil_div64(pairs, kShrTM) + N;
-        const unsigned grid = (unsigned)max_tiles * KS;
-        if (RCB == 1)
-            shrink_mfma_kernel<1><<<grid, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)apack, offsets,
-                                                               bucket_tok, bucket_slot, T, d_in, N, r, k, KS, hpart);
-        else
-            shrink_mfma_kernel<2><<<grid, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)apack, offsets,
-                                                               bucket_tok, bucket_slot, T, d_in, N, r, k, KS, hpart);
-        e = hipGetLastError();
+        // apack has been filled by launch_prep
+        // 64-pair tiles: less padding in small buckets and two workgroups per CU; 128-pair tiles reuse
+        // each A fragment twice as often and are kept for batches that fill the chip anyway
+        const bool big = ceil_div64(pairs, 128) * KS >= 2048;
+        auto launch = [&](auto kern, int rb) -> hipError_t {
+            const int smem = 4 * shrink_region_bytes(RCB, rb);
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (err != hipSuccess) return err;
+            // upper bound of the tile count: every bucket rounds up by at most one tile
+            const int64_t max_tiles = ceil_div64(pairs, rb * 32) + N;
+            kern<<<(unsigned)(max_tiles * KS), 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)apack, offsets,
+                                                                  bucket_tok, bucket_slot, T, d_in, N, r, k, KS, hpart);
+            return hipGetLastError();
+        };
+        hipError_t e;
+        if (RCB == 1) e = big ? launch(shrink_mfma_kernel<1, 4>, 4) : launch(shrink_mfma_kernel<1, 2>, 2);
+        else e = big ? launch(shrink_mfma_kernel<2, 4>, 4) : launch(shrink_mfma_kernel<2, 2>, 2);
         if (e != hipSuccess) return e;
         int64_t work = 0;
         if (hdense) work = (int64_t)T * (ext_stride / 8);
