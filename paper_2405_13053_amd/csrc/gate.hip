@@ -284,9 +284,8 @@ hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_i
     }
     const int KS = gate_kslices(d_in, true), NCB = NP / 32;
     // wsplit has been filled by launch_prep
-    // 64 tokens per workgroup (two workgroups share a CU and overlap load with compute) unless the batch
-    // is large enough that 128-token workgroups, which reuse each W fragment twice as often, still fill the chip
-    const bool big = (int64_t)ceil_div(T, 128) * KS >= 1024;
+    // 64 tokens per workgroup: two workgroups share a CU, so one loads while the other computes
+    // (measured faster than 32 or 128 tokens on every configuration, 4096 to 16384 tokens)
     auto launch = [&](auto kern, int rb) -> hipError_t {
         const int smem = 4 * gate_region_bytes(NCB, rb);
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -296,8 +295,8 @@ hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_i
                                                               partials);
         return hipGetLastError();
     };
-    if (NCB == 1) return big ? launch(gate_logits_mfma_kernel<1, 4>, 4) : launch(gate_logits_mfma_kernel<1, 2>, 2);
-    return big ? launch(gate_logits_mfma_kernel<2, 4>, 4) : launch(gate_logits_mfma_kernel<2, 2>, 2);
+    if (NCB == 1) return launch(gate_logits_mfma_kernel<1, 2>, 2);
+    return launch(gate_logits_mfma_kernel<2, 2>, 2);
 }
 
 hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, int T, int N, int k,

@@ -293,9 +293,8 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
     if (shrink_uses_mfma(bf16, r)) {
         const int KS = shrink_kslices(d_in), RCB = ceil_div(r, 32), S16 = KS * (kShrKSL / 16);
         // apack has been filled by launch_prep
-        // 64-pair tiles: less padding in small buckets and two workgroups per CU; 128-pair tiles reuse
-        // each A fragment twice as often and are kept for batches that fill the chip anyway
-        const bool big = ceil_div64(pairs, 128) * KS >= 2048;
+        // 64-pair tiles: little padding in small buckets and two workgroups per CU (one loads while the
+        // other computes); measured faster than 32- or 128-pair tiles on every configuration
         auto launch = [&](auto kern, int rb) -> hipError_t {
             const int smem = 4 * shrink_region_bytes(RCB, rb);
             hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -308,8 +307,8 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
             return hipGetLastError();
         };
         hipError_t e;
-        if (RCB == 1) e = big ? launch(shrink_mfma_kernel<1, 4>, 4) : launch(shrink_mfma_kernel<1, 2>, 2);
-        else e = big ? launch(shrink_mfma_kernel<2, 4>, 4) : launch(shrink_mfma_kernel<2, 2>, 2);
+        if (RCB == 1) e = launch(shrink_mfma_kernel<1, 2>, 2);
+        else e = launch(shrink_mfma_kernel<2, 2>, 2);
         if (e != hipSuccess) return e;
         int64_t work = 0;
         if (hdense) work = (int64_t)T * (ext_stride / 8);
