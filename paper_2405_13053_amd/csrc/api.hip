@@ -13,7 +13,7 @@ namespace {
 
 struct WsLayout {
     size_t wsplit, partials, chunk_counts, counts, offsets, bucket_tok, bucket_slot, topk_idx, topk_w, h32,
-        hdense, apack, hpart, total;
+        hdense, apack, hpart, splitk, total;
     int ext_stride;   // columns of hdense: N*r rounded up to 64 (one K tile of the GEMM)
 };
 
@@ -27,7 +27,6 @@ bool shape_supported(int T, int d_in, int d_out, int N, int r, int k) {
 }
 
 WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
-    (void)d_out;
     WsLayout L{};
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -47,6 +46,7 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     L.hdense = take((size_t)T * L.ext_stride * sizeof(uint16_t));
     L.apack = take(shrink_apack_bytes(d_in, N, r, bf16));
     L.hpart = take(shrink_hpart_bytes(T, d_in, r, k, bf16));
+    L.splitk = take(gemm_splitk_bytes(T, d_in, d_out, bf16));
     L.total = off;
     return L;
 }
@@ -240,11 +240,12 @@ static meteora_status run_lora(const void* x, const void* W, const void* A, cons
         // base projection (if W is given) and LoRA expand in one MFMA kernel, one rounding of the output
         StageScope sc(ST_GEMM, st, tslot);
         METEORA_HIP(launch_gemm(x, W, T, W ? d_in : 0, d_out, bf16, at<void>(ws, L.hdense), L.ext_stride, B,
-                                N * r, out, accumulate, st));
+                                N * r, out, accumulate,
+                                gemm_splitk_bytes(T, d_in, d_out, bf16) > 0 ? at<float>(ws, L.splitk) : nullptr, st));
     } else {
         if (W) {
             StageScope sc(ST_GEMM, st, tslot);
-            METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, bf16, nullptr, 0, nullptr, 0, out, accumulate, st));
+            METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, bf16, nullptr, 0, nullptr, 0, out, accumulate, nullptr, st));
         }
         StageScope sc(ST_EXPAND, st, tslot);
         METEORA_HIP(launch_expand(h32, B, topk_idx, topk_w, T, d_out, N, r, k, scale, bf16, out,
@@ -281,7 +282,7 @@ meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, 
     if (!shape_supported(T, d_in, d_out, 1, 1, 1)) return METEORA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(W) || !aligned16(out)) return METEORA_ERR_UNSUPPORTED;
     if (T == 0) return METEORA_OK;
-    METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, dt == METEORA_BF16, nullptr, 0, nullptr, 0, out, 0,
+    METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, dt == METEORA_BF16, nullptr, 0, nullptr, 0, out, 0, nullptr,
                             static_cast<hipStream_t>(stream)));
     return METEORA_OK;
 }

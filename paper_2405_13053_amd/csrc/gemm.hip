@@ -57,6 +57,52 @@ __global__ __launch_bounds__(256) void gemm_fma_kernel(const TX* __restrict__ x,
     }
 }
 
+// Sum the fp32 split-K tiles in a fixed order (deterministic), add the old output if asked, round once.
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __restrict__ partial, int nsplit,
+                                                                 int T, int d_out, bf16_t* __restrict__ out,
+                                                                 int accumulate) {
+    const size_t n8 = (size_t)T * d_out / 8;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < nsplit; ++s) {
+        const float* src = partial + (size_t)s * T * d_out + i * 8;
+        lo += *reinterpret_cast<const f32x4*>(src);
+        hi += *reinterpret_cast<const f32x4*>(src + 4);
+    }
+    u32x4* dst = reinterpret_cast<u32x4*>(out) + i;
+    if (accumulate) {
+        const u32x4 old = *dst;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            lo[2 * e] += bf16_bits_to_float(old[e] & 0xffffu);
+            lo[2 * e + 1] += bf16_bits_to_float(old[e] >> 16);
+            hi[2 * e] += bf16_bits_to_float(old[2 + e] & 0xffffu);
+            hi[2 * e + 1] += bf16_bits_to_float(old[2 + e] >> 16);
+        }
+    }
+    u32x4 pk;
+    pk[0] = pack_bf16x2(lo[0], lo[1]); pk[1] = pack_bf16x2(lo[2], lo[3]);
+    pk[2] = pack_bf16x2(hi[0], hi[1]); pk[3] = pack_bf16x2(hi[2], hi[3]);
+    *dst = pk;
+}
+
+// Skinny batches (decode): one 64-row tile per 64 output columns leaves most CUs idle while W streams
+// from HBM, so K is split over workgroups.  Returns the number of main-K splits (0 = do not split).
+int gemm_splitk_splits(int T, int d_in, int d_out, bool bf16) {
+    if (!bf16 || T > 64 || d_in % kGemmBK != 0) return 0;
+    const int tiles = ceil_div(T, 64) * ceil_div(d_out, 64), nk = d_in / kGemmBK;
+    if (tiles >= 512 || nk < 8) return 0;
+    int S = ceil_div(768, tiles);
+    if (S > nk / 4) S = nk / 4;
+    return S >= 2 ? S : 0;
+}
+
+size_t gemm_splitk_bytes(int T, int d_in, int d_out, bool bf16) {
+    const int S = gemm_splitk_splits(T, d_in, d_out, bf16);
+    return S == 0 ? 0 : (size_t)(S + 1) * T * d_out * sizeof(float);   // +1: the expand extension
+}
+
 template <int MI, int NI>
 static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
     constexpr int BM = MI * 64, BN = NI * 64;
@@ -76,7 +122,15 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
     // the pipelined kernel needs whole K tiles and byte offsets inside x and W that fit 32 bits
     const bool dma_ok = a.d_in % kGemmBK == 0 && (a.ext_k == 0 || a.ext_stride % kGemmBK == 0) &&
                         (uint64_t)a.T * a.d_in * 2 < (1ull << 32) && (uint64_t)a.d_out * a.d_in * 2 < (1ull << 32);
-    if (dma_ok)
+    if (dma_ok && a.partial != nullptr) {
+        const int nsplit = a.splits + (a.ext_k > 0 ? 1 : 0);
+        gemm_mfma_dma_kernel<MI, NI><<<dim3(a.tiles_m * a.tiles_n, nsplit), 256, smem, stream>>>(a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const size_t n8 = (size_t)a.T * a.d_out / 8;
+        gemm_splitk_reduce_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, stream>>>(a.partial, nsplit, a.T, a.d_out,
+                                                                                   a.out, a.accumulate);
+    } else if (dma_ok)
         gemm_mfma_dma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
     else
         gemm_mfma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
@@ -87,12 +141,19 @@ bool gemm_fuses_expand(bool bf16) { return bf16; }
 
 hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out, bool bf16,
                        const void* hdense, int ext_stride, const void* B, int ext_k,
-                       void* out, int accumulate, hipStream_t stream) {
+                       void* out, int accumulate, float* splitk_ws, hipStream_t stream) {
     if (bf16) {
         GemmArgs a{};
         a.x = (const bf16_t*)x; a.W = (const bf16_t*)W; a.hd = (const bf16_t*)hdense; a.Bst = (const bf16_t*)B;
         a.out = (bf16_t*)out; a.T = T; a.d_in = d_in; a.d_out = d_out;
         a.ext_k = hdense ? ext_k : 0; a.ext_stride = ext_stride; a.accumulate = accumulate;
+        const int S = splitk_ws ? gemm_splitk_splits(T, d_in, d_out, true) : 0;
+        if (S > 0 && d_in > 0) {
+            a.partial = splitk_ws;
+            a.splits = S;
+            a.tiles_per_split = ceil_div(d_in / kGemmBK, S);
+            return launch_mfma<1, 1>(a, stream);
+        }
         const int64_t big_tiles = (int64_t)ceil_div(T, 256) * ceil_div(d_out, 256);
         if (T > 128 && big_tiles >= 128) return launch_mfma<4, 4>(a, stream);
         if (T > 64) return launch_mfma<2, 2>(a, stream);

@@ -35,6 +35,10 @@ struct GemmArgs {
     int ext_stride;       // row stride of hd (multiple of 8, >= ext_k)
     int accumulate;       // 1: add previous contents of out
     int tiles_m, tiles_n;
+    // split-K (skinny batches): blockIdx.y = split; split s < splits takes K tiles [s*tiles_per_split, ...),
+    // split == splits (only if ext_k > 0) takes the expand extension; fp32 tiles go to partial[split][T][d_out]
+    float* partial;       // nullptr: no split, the kernel writes `out` itself
+    int splits, tiles_per_split;
 };
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7); }
@@ -338,16 +342,27 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 
-    const int nk_main = a.d_in / kGemmBK;
-    const int nk_ext = a.ext_k > 0 ? ceil_div(a.ext_k, kGemmBK) : 0;
+    // this workgroup's share of the contraction: main K tiles [kt0, kt0 + nk_main) and/or the extension
+    int kt0 = 0, nk_main = a.d_in / kGemmBK;
+    int nk_ext = a.ext_k > 0 ? ceil_div(a.ext_k, kGemmBK) : 0;
+    if (a.partial != nullptr) {
+        const int split = blockIdx.y;
+        if (split < a.splits) {
+            kt0 = split * a.tiles_per_split;
+            nk_main = max(0, min(a.tiles_per_split, nk_main - kt0));
+            nk_ext = 0;
+        } else {
+            nk_main = 0;
+        }
+    }
     const int nk = nk_main + nk_ext;
 
-    auto request = [&](int it, int slot) {   // start moving K tile `it` into LDS slot `slot`
+    auto request = [&](int it, int slot) {   // start moving local K tile `it` into LDS slot `slot`
         bf16_t* xs = smem + slot * kBufElems;
         bf16_t* wsm = xs + BM * kGemmBK;
         if (it < nk_main) {
-            dma_tile<BM>(xs, a.x, a.d_in, m0, a.T, it * kGemmBK, wave, lane);
-            dma_tile<BN>(wsm, a.W, a.d_in, n0, a.d_out, it * kGemmBK, wave, lane);
+            dma_tile<BM>(xs, a.x, a.d_in, m0, a.T, (kt0 + it) * kGemmBK, wave, lane);
+            dma_tile<BN>(wsm, a.W, a.d_in, n0, a.d_out, (kt0 + it) * kGemmBK, wave, lane);
         } else {
             dma_tile<BM>(xs, a.hd, a.ext_stride, m0, a.T, (it - nk_main) * kGemmBK, wave, lane);
             load_bst_tile_lds<BN>(wsm, a.Bst, a.d_out, n0, (it - nk_main) * kGemmBK, a.ext_k, tid);
@@ -358,8 +373,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
     uint32_t xoff[BM / 32], woff[BN / 32];
     dma_offsets<BM>(xoff, a.d_in, m0, a.T, wave, lane);
     dma_offsets<BN>(woff, a.d_in, n0, a.d_out, wave, lane);
-    const char* xb = reinterpret_cast<const char*>(a.x);
-    const char* wb = reinterpret_cast<const char*>(a.W);
+    const char* xb = reinterpret_cast<const char*>(a.x) + (size_t)kt0 * (kGemmBK * 2);
+    const char* wb = reinterpret_cast<const char*>(a.W) + (size_t)kt0 * (kGemmBK * 2);
     auto request_main = [&](int it, int slot) {
         bf16_t* xs = smem + slot * kBufElems;
         dma_issue<BM>(xs, xb + (size_t)it * (kGemmBK * 2), xoff, wave);
@@ -416,9 +431,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
             for (int g = 0; g < 4; ++g) {
                 const int col = n0 + wn + ni * 32 + g * 8 + khalf * 4;
                 if (col >= a.d_out) continue;
-                uint2* dst = reinterpret_cast<uint2*>(a.out + (size_t)row * a.d_out + col);
                 float v0 = acc[mi][ni][g * 4 + 0], v1 = acc[mi][ni][g * 4 + 1];
                 float v2 = acc[mi][ni][g * 4 + 2], v3 = acc[mi][ni][g * 4 + 3];
+                if (a.partial != nullptr) {
+                    const f32x4 v = {v0, v1, v2, v3};
+                    *reinterpret_cast<f32x4*>(a.partial + ((size_t)blockIdx.y * a.T + row) * a.d_out + col) = v;
+                    continue;
+                }
+                uint2* dst = reinterpret_cast<uint2*>(a.out + (size_t)row * a.d_out + col);
                 if (a.accumulate) {
                     const uint2 old = *dst;
                     v0 += bf16_bits_to_float(old.x & 0xffffu);

@@ -58,8 +58,10 @@ hipError_t launch_expand(const float* h32, const void* B, const int32_t* topk_id
 // d_in may be 0 (expand only); accumulate=1 adds the previous contents of out.
 // true if launch_gemm applies the hdense/B extension for this dtype (else run launch_expand after it)
 bool gemm_fuses_expand(bool bf16);
+// splitk_ws: scratch of gemm_splitk_bytes (0 = this shape is not split) or NULL to forbid splitting.
+size_t gemm_splitk_bytes(int T, int d_in, int d_out, bool bf16);
 hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out, bool bf16,
                        const void* hdense, int ext_stride, const void* B, int ext_k,
-                       void* out, int accumulate, hipStream_t stream);
+                       void* out, int accumulate, float* splitk_ws, hipStream_t stream);
 
 }  // namespace meteora
