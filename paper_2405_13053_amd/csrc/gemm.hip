@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __
 // Skinny batches (decode): one 64-row tile per 64 output columns leaves most CUs idle while W streams
 // from HBM, so K is split over workgroups.  Returns the number of main-K splits (0 = do not split).
 int gemm_splitk_splits(int T, int d_in, int d_out, bool bf16) {
-    if (!bf16 || T > 64 || d_in % kGemmBK != 0) return 0;
+    if (!bf16 || T < 1 || T > 64 || d_in % kGemmBK != 0) return 0;
     const int tiles = ceil_div(T, 64) * ceil_div(d_out, 64), nk = d_in / kGemmBK;
     if (tiles >= 512 || nk < 8) return 0;
     int S = ceil_div(768, tiles);
