@@ -13,7 +13,7 @@ namespace {
 
 struct WsLayout {
     size_t wsplit, partials, chunk_counts, counts, offsets, bucket_tok, bucket_slot, topk_idx, topk_w, h32,
-        hdense, apack, hpart, splitk, total;
+        hdense, apack, hpart, splitk, btrans, total;
     int ext_stride;   // columns of hdense: N*r rounded up to 64 (one K tile of the GEMM)
 };
 
@@ -47,6 +47,7 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     L.apack = take(shrink_apack_bytes(d_in, N, r, bf16));
     L.hpart = take(shrink_hpart_bytes(T, d_in, r, k, bf16));
     L.splitk = take(gemm_splitk_bytes(T, d_in, d_out, bf16));
+    L.btrans = take(prep_btrans_bytes(d_out, N, r, bf16));
     L.total = off;
     return L;
 }
@@ -176,7 +177,7 @@ meteora_status meteora_gate_topk(const void* x, const float* W_gate, const float
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* partials = at<float>(ws, L.partials);
     if (gate_wsplit_bytes(d_in, N, bf16) > 0)
-        METEORA_HIP(launch_prep(W_gate, at<void>(ws, L.wsplit), nullptr, nullptr, d_in, N, 1, st));
+        METEORA_HIP(launch_prep(W_gate, at<void>(ws, L.wsplit), nullptr, nullptr, nullptr, nullptr, d_in, 8, N, 1, st));
     METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, at<void>(ws, L.wsplit), partials, st));
     METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, inv_temperature,
                                  topk_idx, topk_w, logits, nullptr, st));
@@ -239,8 +240,8 @@ static meteora_status run_lora(const void* x, const void* W, const void* A, cons
     if (fused) {
         // base projection (if W is given) and LoRA expand in one MFMA kernel, one rounding of the output
         StageScope sc(ST_GEMM, st, tslot);
-        METEORA_HIP(launch_gemm(x, W, T, W ? d_in : 0, d_out, bf16, at<void>(ws, L.hdense), L.ext_stride, B,
-                                N * r, out, accumulate,
+        METEORA_HIP(launch_gemm(x, W, T, W ? d_in : 0, d_out, bf16, at<void>(ws, L.hdense), L.ext_stride,
+                                at<void>(ws, L.btrans), N * r, out, accumulate,
                                 gemm_splitk_bytes(T, d_in, d_out, bf16) > 0 ? at<float>(ws, L.splitk) : nullptr, st));
     } else {
         if (W) {
@@ -267,9 +268,12 @@ meteora_status meteora_lora_forward(const void* x, const void* A, const void* B,
     const WsLayout L = ws_layout(T, d_in, d_out, N, r, k, bf16);
     if (!ws || !aligned256(ws) || ws_bytes < L.total) return METEORA_ERR_WORKSPACE;
     if (T == 0) return METEORA_OK;
-    if (shrink_apack_bytes(d_in, N, r, bf16) > 0)
-        METEORA_HIP(launch_prep(nullptr, nullptr, A, at<void>(ws, L.apack), d_in, N, r,
+    {
+        const bool pa = shrink_apack_bytes(d_in, N, r, bf16) > 0, pb = prep_btrans_bytes(d_out, N, r, bf16) > 0;
+        METEORA_HIP(launch_prep(nullptr, nullptr, pa ? A : nullptr, pa ? at<void>(ws, L.apack) : nullptr,
+                                pb ? B : nullptr, pb ? at<void>(ws, L.btrans) : nullptr, d_in, d_out, N, r,
                                 static_cast<hipStream_t>(stream)));
+    }
     return run_lora(x, nullptr, A, B, topk_idx, topk_w, T, d_in, d_out, N, r, k, scale, bf16, out, accumulate, ws, L,
                     static_cast<hipStream_t>(stream), timing_begin_call(), false);
 }
@@ -309,8 +313,10 @@ meteora_status meteora_linear_forward(const void* x, const void* W, const float*
     {
         StageScope sc(ST_PREP, st, tslot);
         const bool pw = gate_wsplit_bytes(d_in, N, bf16) > 0, pa = shrink_apack_bytes(d_in, N, r, bf16) > 0;
+        const bool pb = prep_btrans_bytes(d_out, N, r, bf16) > 0;
         METEORA_HIP(launch_prep(pw ? W_gate : nullptr, pw ? at<void>(ws, L.wsplit) : nullptr, pa ? A : nullptr,
-                                pa ? at<void>(ws, L.apack) : nullptr, d_in, N, r, st));
+                                pa ? at<void>(ws, L.apack) : nullptr, pb ? B : nullptr,
+                                pb ? at<void>(ws, L.btrans) : nullptr, d_in, d_out, N, r, st));
     }
     {
         StageScope sc(ST_GATE_LOGITS, st, tslot);

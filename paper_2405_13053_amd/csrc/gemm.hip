@@ -120,8 +120,9 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
     a.tiles_m = ceil_div(a.T, BM);
     a.tiles_n = ceil_div(a.d_out, BN);
     // the pipelined kernel needs whole K tiles and byte offsets inside x and W that fit 32 bits
-    const bool dma_ok = a.d_in % kGemmBK == 0 && (a.ext_k == 0 || a.ext_stride % kGemmBK == 0) &&
-                        (uint64_t)a.T * a.d_in * 2 < (1ull << 32) && (uint64_t)a.d_out * a.d_in * 2 < (1ull << 32);
+    const uint64_t widest = (uint64_t)(a.d_in > a.ext_stride ? a.d_in : a.ext_stride) * 2;
+    const bool dma_ok = a.d_in % kGemmBK == 0 && ((uint64_t)a.T + BM) * widest < (1ull << 32) &&
+                        ((uint64_t)a.d_out + BN) * widest < (1ull << 32);
     if (dma_ok && a.partial != nullptr) {
         const int nsplit = a.splits + (a.ext_k > 0 ? 1 : 0);
         gemm_mfma_dma_kernel<MI, NI><<<dim3(a.tiles_m * a.tiles_n, nsplit), 256, smem, stream>>>(a);
@@ -140,11 +141,12 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
 bool gemm_fuses_expand(bool bf16) { return bf16; }
 
 hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out, bool bf16,
-                       const void* hdense, int ext_stride, const void* B, int ext_k,
+                       const void* hdense, int ext_stride, const void* Bt, int ext_k,
                        void* out, int accumulate, float* splitk_ws, hipStream_t stream) {
     if (bf16) {
+        if (hdense && (ext_stride % kGemmBK != 0 || ext_stride < ext_k || !Bt)) return hipErrorInvalidValue;
         GemmArgs a{};
-        a.x = (const bf16_t*)x; a.W = (const bf16_t*)W; a.hd = (const bf16_t*)hdense; a.Bst = (const bf16_t*)B;
+        a.x = (const bf16_t*)x; a.W = (const bf16_t*)W; a.hd = (const bf16_t*)hdense; a.Bt = (const bf16_t*)Bt;
         a.out = (bf16_t*)out; a.T = T; a.d_in = d_in; a.d_out = d_out;
         a.ext_k = hdense ? ext_k : 0; a.ext_stride = ext_stride; a.accumulate = accumulate;
         const int S = splitk_ws ? gemm_splitk_splits(T, d_in, d_out, true) : 0;

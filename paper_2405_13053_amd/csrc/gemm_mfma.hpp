@@ -4,7 +4,9 @@
 //     out[t, c] = sum_{i < d_in} x[t,i] * W[c,i]  +  sum_{j < ext_k} hd[t,j] * Bst[j,c]
 //
 // where hd[t, a*r+q] = scale * w * h[t,slot,q] for the adapters a the token selected (zero
-// elsewhere) and Bst is the stacked B[N, r, d_out] viewed as [N*r, d_out].  The second sum is
+// elsewhere) and Bst is the stacked B[N, r, d_out] viewed as [N*r, d_out]; the kernels read it
+// transposed (Bt[c, j], rows of ext_stride elements, columns j >= ext_k zero), which makes the
+// extension one more stretch of K tiles with the same operand layout as x and W.  The second sum is
 // exactly scale * sum_{i in I(x)} w_i (x A_i) B_i of Eq. 2, accumulated in the same fp32
 // registers as the base term, so the output is rounded once.
 //
@@ -28,11 +30,11 @@ struct GemmArgs {
     const bf16_t* x;      // [T, d_in]
     const bf16_t* W;      // [d_out, d_in]
     const bf16_t* hd;     // [T, ext_stride] or nullptr
-    const bf16_t* Bst;    // [ext_k, d_out]  or nullptr
+    const bf16_t* Bt;     // [d_out, ext_stride] (stacked B transposed, zero-padded columns) or nullptr
     bf16_t* out;          // [T, d_out]
     int T, d_in, d_out;
-    int ext_k;            // N*r (rows of Bst); 0 = no extension
-    int ext_stride;       // row stride of hd (multiple of 8, >= ext_k)
+    int ext_k;            // N*r; 0 = no extension
+    int ext_stride;       // row stride of hd and Bt: ext_k rounded up to a multiple of 64
     int accumulate;       // 1: add previous contents of out
     int tiles_m, tiles_n;
     // split-K (skinny batches): blockIdx.y = split; split s < splits takes K tiles [s*tiles_per_split, ...),
@@ -68,28 +70,6 @@ __device__ __forceinline__ void store_tile_lds(const u32x4 (&regs)[ROWS / 32], b
     for (int i = 0; i < ROWS / 32; ++i) {
         const int row = (tid >> 3) + 32 * i;
         *reinterpret_cast<u32x4*>(lds_tile + row * kGemmBK + swz(row, chunk) * 8) = regs[i];
-    }
-}
-
-// Transposing load of the stacked-B tile: LDS wants [n][k] (k contiguous); memory is [k][n].
-// Thread handles column n = n0 + (tid) (+256*i) ... here BN <= 256 so one column per thread and
-// all 8 chunks of it; each chunk gathers 8 k-rows with 2-byte loads that are coalesced across lanes.
-template <int BN>
-__device__ __forceinline__ void load_bst_tile_lds(bf16_t* lds_tile, const bf16_t* __restrict__ Bst, int d_out,
-                                                  int n0, int k0, int ext_k, int tid) {
-    for (int n = tid; n < BN; n += 256) {
-        int col = n0 + n;
-        col = col < d_out ? col : d_out - 1;
-#pragma unroll
-        for (int c = 0; c < kGemmChunks; ++c) {
-            union { uint16_t h[8]; u32x4 v; } p;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int kk = k0 + c * 8 + j;
-                p.h[j] = kk < ext_k ? reinterpret_cast<const uint16_t*>(Bst)[(size_t)kk * d_out + col] : (uint16_t)0;
-            }
-            *reinterpret_cast<u32x4*>(lds_tile + n * kGemmBK + swz(n, c) * 8) = p.v;
-        }
     }
 }
 
@@ -151,27 +131,24 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmArgs a) {
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 
     const int nk_main = ceil_div(a.d_in, kGemmBK);
-    const int nk_ext = a.ext_k > 0 ? ceil_div(a.ext_k, kGemmBK) : 0;
+    const int nk_ext = a.ext_k > 0 ? a.ext_stride / kGemmBK : 0;
     const int nk = nk_main + nk_ext;
 
     u32x4 xr[BM / 32], wr[BN / 32];
 
-    auto fetch = [&](int it) {   // global -> registers (x-like operand and, for the main part, W)
+    auto fetch = [&](int it) {   // global -> registers
         if (it < nk_main) {
             load_tile_regs<BM>(xr, a.x, a.d_in, m0, a.T, it * kGemmBK, a.d_in, tid);
             load_tile_regs<BN>(wr, a.W, a.d_in, n0, a.d_out, it * kGemmBK, a.d_in, tid);
         } else {
-            load_tile_regs<BM>(xr, a.hd, a.ext_stride, m0, a.T, (it - nk_main) * kGemmBK, a.ext_k, tid);
+            load_tile_regs<BM>(xr, a.hd, a.ext_stride, m0, a.T, (it - nk_main) * kGemmBK, a.ext_stride, tid);
+            load_tile_regs<BN>(wr, a.Bt, a.ext_stride, n0, a.d_out, (it - nk_main) * kGemmBK, a.ext_stride, tid);
         }
     };
-    auto commit = [&](int it, int buf) {   // registers -> LDS (and the transposed stacked-B tile)
+    auto commit = [&](int, int buf) {   // registers -> LDS
         bf16_t* xs = smem + buf * kBufElems;
-        bf16_t* wsm = xs + BM * kGemmBK;
         store_tile_lds<BM>(xr, xs, tid);
-        if (it < nk_main)
-            store_tile_lds<BN>(wr, wsm, tid);
-        else
-            load_bst_tile_lds<BN>(wsm, a.Bst, a.d_out, n0, (it - nk_main) * kGemmBK, a.ext_k, tid);
+        store_tile_lds<BN>(wr, xs + BM * kGemmBK, tid);
     };
 
     if (nk > 0) {
@@ -220,13 +197,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Pipelined version for d_in % 64 == 0 (all model shapes): the tiles of x and W go from global
-// memory straight into LDS with 16-byte global->LDS loads (no staging registers), the MFMA
-// operand fragments are double-buffered in registers so the ds_reads of k-step s+1 are in
+// Pipelined version for d_in % 64 == 0 (all model shapes): the tiles of both operands go from
+// global memory straight into LDS with 16-byte buffer_load ... lds (no staging registers), the
+// MFMA operand fragments are double-buffered in registers so the ds_reads of k-step s+1 are in
 // flight while the MFMAs of k-step s run, and there is one barrier per 64-wide K tile, placed
 // before the last k-step: behind it the next tile is visible, the tile after it is requested
 // into the slot that has just been drained, and the first fragments of the next tile are read
-// under the MFMAs of the last k-step.
+// under the MFMAs of the last k-step.  The K tiles of the extension (hd x Bt) follow the main
+// ones through the same pipeline; only the buffer resources and row strides change.
 // ------------------------------------------------------------------------------------------
 template <int MI, int NI>
 struct Frags {
@@ -249,6 +227,19 @@ __device__ __forceinline__ void load_frags(Frags<MI, NI>& f, const bf16_t* xs, c
     }
 }
 
+// One MFMA operand fragment of k-step ks of an LDS tile pair: i < MI -> x block i, else W block i - MI.
+template <int MI, int NI>
+__device__ __forceinline__ void load_frag1(Frags<MI, NI>& f, const bf16_t* xs, const bf16_t* wsm, int wm, int wn,
+                                           int lrow, int khalf, int ks, int i) {
+    if (i < MI) {
+        const int row = wm + i * 32 + lrow;
+        f.x[i] = *reinterpret_cast<const bf16x8*>(xs + row * kGemmBK + swz(row, ks * 2 + khalf) * 8);
+    } else {
+        const int row = wn + (i - MI) * 32 + lrow;
+        f.w[i - MI] = *reinterpret_cast<const bf16x8*>(wsm + row * kGemmBK + swz(row, ks * 2 + khalf) * 8);
+    }
+}
+
 template <int MI, int NI>
 __device__ __forceinline__ void mma_frags(f32x16 (&acc)[MI][NI], const Frags<MI, NI>& f) {
 #pragma unroll
@@ -258,50 +249,39 @@ __device__ __forceinline__ void mma_frags(f32x16 (&acc)[MI][NI], const Frags<MI,
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.w[ni], f.x[mi], acc[mi][ni], 0, 0, 0);
 }
 
-// One [ROWS x 64] tile, global -> LDS: an instruction moves 8 rows (8 lanes x 16 B per 128-B row);
-// lane (row, p) fetches global chunk p ^ (row & 7) so the LDS image is the swizzled layout.
-template <int ROWS>
-__device__ __forceinline__ void dma_tile(bf16_t* lds_tile, const bf16_t* __restrict__ base, int ld, int row0,
-                                         int nrows, int k0, int wave, int lane) {
+// A [rows x 64-element-tiles] operand as the global->LDS loads see it.  An instruction moves 8 rows
+// (8 lanes x 16 B per 128-byte tile row); lane (rsub, p) fetches chunk p ^ rsub of its row so the
+// LDS image is the swizzled layout.  Wavefront `wave` moves rows (j*4 + wave)*8 .. +8 of the tile
+// as piece j.  The address is rsrc base + voff (per lane: first row of piece 0, swizzled chunk)
+// + a uniform offset (piece and K tile).  The resource covers exactly the matrix, so rows past
+// its last one (ragged edge tiles) are out of range for the hardware and load zeros; they only
+// feed output rows or columns that are never stored.
+struct DmaOperand {
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t voff;        // per lane
+    uint32_t piece_step;  // bytes between pieces: 32 rows
+};
+
+__device__ __forceinline__ DmaOperand dma_operand(const bf16_t* base, int nrows, int ld, int row0, int wave, int lane) {
+    DmaOperand o;
+    o.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (uint32_t)nrows * (uint32_t)ld * 2u,
+                                               0x00020000);
     const int rsub = lane >> 3, p = lane & 7;
-#pragma unroll
-    for (int j = 0; j < ROWS / 32; ++j) {   // 4 waves x 8 rows per instruction
-        const int row = (j * 4 + wave) * 8 + rsub;
-        int grow = row0 + row;
-        grow = grow < nrows ? grow : nrows - 1;
-        const bf16_t* src = base + (size_t)grow * ld + k0 + ((p ^ (row & 7)) << 3);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)(lds_tile + (j * 4 + wave) * 8 * kGemmBK),
-                                         16, 0, 0);
-    }
+    o.voff = (uint32_t)(row0 + wave * 8 + rsub) * (uint32_t)ld * 2u + (uint32_t)((p ^ rsub) << 4);
+    o.piece_step = 32u * (uint32_t)ld * 2u;
+    return o;
 }
 
-// Steady-state form of dma_tile: the per-lane byte offsets are computed once (dma_offsets) and each
-// K tile only adds a uniform base, so the loop carries no per-load address arithmetic.
-template <int ROWS>
-__device__ __forceinline__ void dma_offsets(uint32_t (&voff)[ROWS / 32], int ld, int row0, int nrows, int wave,
-                                            int lane) {
-    const int rsub = lane >> 3, p = lane & 7;
-#pragma unroll
-    for (int j = 0; j < ROWS / 32; ++j) {
-        const int row = (j * 4 + wave) * 8 + rsub;
-        int grow = row0 + row;
-        grow = grow < nrows ? grow : nrows - 1;
-        voff[j] = (uint32_t)grow * (uint32_t)ld * 2u + (uint32_t)((p ^ (row & 7)) << 4);
-    }
+__device__ __forceinline__ void dma_piece(bf16_t* lds_tile, const DmaOperand& o, int ktile, int j, int wave) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        o.rsrc, (__attribute__((address_space(3))) void*)(lds_tile + (j * 4 + wave) * 8 * kGemmBK), 16, o.voff,
+        (int)(o.piece_step * (uint32_t)j + (uint32_t)ktile * (kGemmBK * 2)), 0, 0);
 }
 
-template <int ROWS>
-__device__ __forceinline__ void dma_issue(bf16_t* lds_tile, const char* base_k, const uint32_t (&voff)[ROWS / 32],
-                                          int wave) {
-#pragma unroll
-    for (int j = 0; j < ROWS / 32; ++j) {
-        const char* src = base_k + voff[j];
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)(lds_tile + (j * 4 + wave) * 8 * kGemmBK),
-                                         16, 0, 0);
-    }
-}
+// Instruction-order hints for one phase (the code between two sched_barrier(0)): the compiler's own
+// order bunches the LDS reads and the global->LDS loads and exposes their issue time and latency;
+// these groups alternate them with the MFMAs instead.  Masks: 0x008 MFMA, 0x100 LDS read, 0x020 VMEM read.
+#define METEORA_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
 // Map a workgroup id to an output tile: ids are dealt round-robin to the 8 XCDs, so each XCD
 // gets a contiguous run of the tile order, and the order walks groups of 4 tile rows column by
@@ -322,6 +302,7 @@ __device__ __forceinline__ void tile_of_workgroup(int wg, int tiles_m, int tiles
 template <int MI, int NI>
 __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
     constexpr int BM = MI * 64, BN = NI * 64;
+    constexpr int PX = BM / 32, PW = BN / 32;   // pieces per wavefront per tile
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
     constexpr int kBufElems = (BM + BN) * kGemmBK;
@@ -344,7 +325,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
 
     // this workgroup's share of the contraction: main K tiles [kt0, kt0 + nk_main) and/or the extension
     int kt0 = 0, nk_main = a.d_in / kGemmBK;
-    int nk_ext = a.ext_k > 0 ? ceil_div(a.ext_k, kGemmBK) : 0;
+    int nk_ext = a.ext_k > 0 ? a.ext_stride / kGemmBK : 0;
     if (a.partial != nullptr) {
         const int split = blockIdx.y;
         if (split < a.splits) {
@@ -357,69 +338,99 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
     }
     const int nk = nk_main + nk_ext;
 
-    auto request = [&](int it, int slot) {   // start moving local K tile `it` into LDS slot `slot`
+    // (x, W) feed local tiles [0, nk_main), (hd, Bt) the tiles after them
+    const DmaOperand ox = dma_operand(a.x, a.T, a.d_in, m0, wave, lane);
+    const DmaOperand ow = dma_operand(a.W, a.d_out, a.d_in, n0, wave, lane);
+    const DmaOperand oh = dma_operand(a.hd, nk_ext > 0 ? a.T : 0, a.ext_stride, m0, wave, lane);
+    const DmaOperand ob = dma_operand(a.Bt, nk_ext > 0 ? a.d_out : 0, a.ext_stride, n0, wave, lane);
+
+    // piece i of local tile `it` (x-like pieces first) into LDS slot `slot`
+    auto request_piece = [&](int it, int slot, int i, auto is_ext) {
         bf16_t* xs = smem + slot * kBufElems;
-        bf16_t* wsm = xs + BM * kGemmBK;
-        if (it < nk_main) {
-            dma_tile<BM>(xs, a.x, a.d_in, m0, a.T, (kt0 + it) * kGemmBK, wave, lane);
-            dma_tile<BN>(wsm, a.W, a.d_in, n0, a.d_out, (kt0 + it) * kGemmBK, wave, lane);
+        if constexpr (decltype(is_ext)::value) {
+            if (i < PX) dma_piece(xs, oh, it - nk_main, i, wave);
+            else dma_piece(xs + BM * kGemmBK, ob, it - nk_main, i - PX, wave);
         } else {
-            dma_tile<BM>(xs, a.hd, a.ext_stride, m0, a.T, (it - nk_main) * kGemmBK, wave, lane);
-            load_bst_tile_lds<BN>(wsm, a.Bst, a.d_out, n0, (it - nk_main) * kGemmBK, a.ext_k, tid);
+            if (i < PX) dma_piece(xs, ox, kt0 + it, i, wave);
+            else dma_piece(xs + BM * kGemmBK, ow, kt0 + it, i - PX, wave);
         }
     };
-
-    // steady state: byte offsets of this lane's 16-byte pieces inside a K tile, fixed for the whole loop
-    uint32_t xoff[BM / 32], woff[BN / 32];
-    dma_offsets<BM>(xoff, a.d_in, m0, a.T, wave, lane);
-    dma_offsets<BN>(woff, a.d_in, n0, a.d_out, wave, lane);
-    const char* xb = reinterpret_cast<const char*>(a.x) + (size_t)kt0 * (kGemmBK * 2);
-    const char* wb = reinterpret_cast<const char*>(a.W) + (size_t)kt0 * (kGemmBK * 2);
-    auto request_main = [&](int it, int slot) {
-        bf16_t* xs = smem + slot * kBufElems;
-        dma_issue<BM>(xs, xb + (size_t)it * (kGemmBK * 2), xoff, wave);
-        dma_issue<BN>(xs + BM * kGemmBK, wb + (size_t)it * (kGemmBK * 2), woff, wave);
+    auto request_tile = [&](int it, int slot) {
+#pragma unroll
+        for (int i = 0; i < PX + PW; ++i) {
+            if (it < nk_main) request_piece(it, slot, i, std::false_type{});
+            else request_piece(it, slot, i, std::true_type{});
+        }
     };
 
     Frags<MI, NI> f0, f1;
     if (nk > 0) {
-        request(0, 0);
+        request_tile(0, 0);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (nk > 1) request(1, 1);
+        if (nk > 1) request_tile(1, 1);
         load_frags<MI, NI>(f0, smem, smem + BM * kGemmBK, wm, wn, lrow, khalf, 0);
     }
-    // One K tile = 4 phases of (16 MFMA + the fragment reads of the next k-step); sched_barrier keeps
+    // One K tile = 4 phases of (MI*NI MFMA + the fragment reads of the next k-step); sched_barrier keeps
     // each phase's reads from sinking into the next phase, where they would be waited on at once.
-    auto tile_step = [&](int it, auto steady) {
+    // In the 256x256 kernel the reads are issued one per MFMA in the first half of the phase, so each
+    // has at least half a phase of MFMAs to land under.
+    constexpr bool kPaced = (MI == 4 && NI == 4);
+    auto phase = [&](Frags<MI, NI>& fnext, const Frags<MI, NI>& fcur, const bf16_t* xs, int ks) {
+        load_frags<MI, NI>(fnext, xs, xs + BM * kGemmBK, wm, wn, lrow, khalf, ks);
+        mma_frags<MI, NI>(acc, fcur);
+        if constexpr (kPaced) {
+#pragma unroll
+            for (int i = 0; i < MI + NI; ++i) { METEORA_SGB(0x008, 1); METEORA_SGB(0x100, 1); }
+            METEORA_SGB(0x008, MI * NI - (MI + NI));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // REQ: 0 = tile it+2 is a main tile, 1 = it is an extension tile, 2 = there is none (last two tiles)
+    auto tile_step = [&](int it, auto req) {
+        constexpr int REQ = decltype(req)::value;
         const bf16_t* xs = smem + (it & 1) * kBufElems;
-        const bf16_t* wsm = xs + BM * kGemmBK;
-        load_frags<MI, NI>(f1, xs, wsm, wm, wn, lrow, khalf, 1);
-        mma_frags<MI, NI>(acc, f0);
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags<MI, NI>(f0, xs, wsm, wm, wn, lrow, khalf, 2);
-        mma_frags<MI, NI>(acc, f1);
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags<MI, NI>(f1, xs, wsm, wm, wn, lrow, khalf, 3);
-        mma_frags<MI, NI>(acc, f0);
-        __builtin_amdgcn_sched_barrier(0);
+        phase(f1, f0, xs, 1);
+        phase(f0, f1, xs, 2);
+        phase(f1, f0, xs, 3);
         // tile it+1 (requested one tile ago) must have landed; every wavefront has read tile it
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         const bf16_t* xn = smem + ((it + 1) & 1) * kBufElems;
-        if constexpr (decltype(steady)::value) {
-            request_main(it + 2, it & 1);
-            load_frags<MI, NI>(f0, xn, xn + BM * kGemmBK, wm, wn, lrow, khalf, 0);
+        if constexpr (REQ < 2) {
+            // Program order = the order the LDS accesses must keep (the compiler does not move an LDS
+            // read across a global->LDS load): the first fragments of tile it+1 with pieces of tile
+            // it+2 between them, then the remaining pieces; tile it+2 goes into the slot just drained.
+            constexpr int NR = MI + NI, NPC = PX + PW;
+#pragma unroll
+            for (int i = 0; i < NR; ++i) {
+                load_frag1<MI, NI>(f0, xn, xn + BM * kGemmBK, wm, wn, lrow, khalf, 0, i);
+                request_piece(it + 2, it & 1, i, std::integral_constant<bool, REQ == 1>{});
+            }
+#pragma unroll
+            for (int i = NR; i < NPC; ++i) request_piece(it + 2, it & 1, i, std::integral_constant<bool, REQ == 1>{});
+            mma_frags<MI, NI>(acc, f1);
+            if constexpr (kPaced) {
+#pragma unroll
+                for (int i = 0; i < NR; ++i) { METEORA_SGB(0x008, 1); METEORA_SGB(0x100, 1); METEORA_SGB(0x020, 1); }
+#pragma unroll
+                for (int i = NR; i < NPC; ++i) { METEORA_SGB(0x008, 1); METEORA_SGB(0x020, 1); }
+            }
         } else {
-            if (it + 2 < nk) request(it + 2, it & 1);
             if (it + 1 < nk) load_frags<MI, NI>(f0, xn, xn + BM * kGemmBK, wm, wn, lrow, khalf, 0);
+            mma_frags<MI, NI>(acc, f1);
+            if constexpr (kPaced) {
+#pragma unroll
+                for (int i = 0; i < MI + NI; ++i) { METEORA_SGB(0x008, 1); METEORA_SGB(0x100, 1); }
+                METEORA_SGB(0x008, MI * NI - (MI + NI));
+            }
         }
-        mma_frags<MI, NI>(acc, f1);
         __builtin_amdgcn_sched_barrier(0);
     };
     int it = 0;
-    for (; it + 2 < nk_main; ++it) tile_step(it, std::true_type{});   // branch-free body
-    for (; it < nk; ++it) tile_step(it, std::false_type{});            // last tiles and the expand extension
+    for (; it + 2 < nk_main; ++it) tile_step(it, std::integral_constant<int, 0>{});
+    for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{});
+    for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{});
 
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {

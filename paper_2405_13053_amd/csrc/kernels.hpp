@@ -8,11 +8,13 @@
 
 namespace meteora {
 
-// ---- weight repacking, one launch: W_gate -> split bf16 fragments (bf16 gate), A -> MFMA fragments -----
-// Either pair (W_gate, wsplit) / (A, apack) may be NULL to skip it; sizes are gate_wsplit_bytes and
-// shrink_apack_bytes (0 = that operand is not packed for this dtype/rank: pass NULL).
-hipError_t launch_prep(const float* W_gate, void* wsplit, const void* A, void* apack, int d_in, int N, int r,
-                       hipStream_t stream);
+// ---- weight repacking, one launch: W_gate -> split bf16 fragments (bf16 gate), A -> MFMA fragments,
+// stacked B -> its transpose Bt[d_out, N*r rounded up to 64] (zero-padded) for the GEMM's K-extension.
+// Any pair (W_gate, wsplit) / (A, apack) / (B, btrans) may be NULL to skip it; sizes are gate_wsplit_bytes,
+// shrink_apack_bytes and prep_btrans_bytes (0 = that operand is not packed for this dtype/rank: pass NULL).
+size_t prep_btrans_bytes(int d_out, int N, int r, bool bf16);
+hipError_t launch_prep(const float* W_gate, void* wsplit, const void* A, void* apack, const void* B, void* btrans,
+                       int d_in, int d_out, int N, int r, hipStream_t stream);
 
 // ---- gate (Sec. 3.1: G(x), I(x), Eq. 3) ------------------------------------------------
 // Number of K-slices the logit kernel splits d_in into (partials[KS][T][NP]).
@@ -53,15 +55,17 @@ hipError_t launch_expand(const float* h32, const void* B, const int32_t* topk_id
                          int accumulate, hipStream_t stream);
 
 // ---- base projection out = x * W^T (W stored [d_out, d_in]), optional fused LoRA expand ---
-// If hdense != NULL the contraction is extended by the columns of hdense against B viewed as
-// [N*r, d_out] (out += hdense * B), i.e. the LoRA expand runs in the same accumulators.
+// If hdense != NULL the contraction is extended by the columns of hdense against the stacked B
+// (out += hdense * B viewed as [N*r, d_out]), i.e. the LoRA expand runs in the same accumulators;
+// the kernel takes B transposed and zero-padded, Bt[d_out, ext_stride] as launch_prep writes it,
+// and ext_stride must be a multiple of 64.
 // d_in may be 0 (expand only); accumulate=1 adds the previous contents of out.
 // true if launch_gemm applies the hdense/B extension for this dtype (else run launch_expand after it)
 bool gemm_fuses_expand(bool bf16);
 // splitk_ws: scratch of gemm_splitk_bytes (0 = this shape is not split) or NULL to forbid splitting.
 size_t gemm_splitk_bytes(int T, int d_in, int d_out, bool bf16);
 hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out, bool bf16,
-                       const void* hdense, int ext_stride, const void* B, int ext_k,
+                       const void* hdense, int ext_stride, const void* Bt, int ext_k,
                        void* out, int accumulate, float* splitk_ws, hipStream_t stream);
 
 }  // namespace meteora

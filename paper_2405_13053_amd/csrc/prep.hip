@@ -1,8 +1,11 @@
 // Per-call repacking of the small weight operands into MFMA fragment order (see prep.hpp):
 //   - W_gate (fp32) -> three bf16 terms hi + mid + lo that add up to the fp32 value exactly
 //     (8 + 8 + 8 significand bits), so that bf16 MFMAs reproduce fp32-level gate logits;
-//   - stacked LoRA A[N, d_in, r] (Sec. 3.3) -> fragments with the rank padded to 32 columns.
-// Both run in ONE launch (disjoint workgroup ranges); a wavefront writes one fragment.
+//   - stacked LoRA A[N, d_in, r] (Sec. 3.3) -> fragments with the rank padded to 32 columns;
+//   - stacked LoRA B[N, r, d_out] viewed as [N*r, d_out] -> its transpose Bt[d_out, ext_stride]
+//     (columns >= N*r zero), the layout the GEMM's K-extension streams like W.
+// All run in ONE launch (disjoint workgroup ranges); a wavefront writes one fragment, a workgroup
+// one 64x64 tile of the transpose.
 #include "common.hpp"
 #include "kernels.hpp"
 #include "prep.hpp"
@@ -57,29 +60,66 @@ __device__ __forceinline__ void apack_fragment(const bf16_t* __restrict__ A, int
     apk[frag * 64 + lane] = p.v;
 }
 
+// tile (tj, tc): Bt[tc*64 + c][tj*64 + j] = B[tj*64 + j][tc*64 + c], zero where j >= ext_k
+__device__ __forceinline__ void btrans_tile(const uint16_t* __restrict__ B, int d_out, int ext_k, int ext_stride,
+                                            int tile, int tid, uint16_t* __restrict__ Bt) {
+    __shared__ uint16_t t[64][66];
+    const int tiles_j = ext_stride / 64;
+    const int j0 = (tile % tiles_j) * 64, c0 = (tile / tiles_j) * 64;
+#pragma unroll 4
+    for (int i = 0; i < 16; ++i) {
+        const int j = i * 4 + (tid >> 6), c = tid & 63;
+        t[j][c] = (j0 + j < ext_k && c0 + c < d_out) ? B[(size_t)(j0 + j) * d_out + c0 + c] : (uint16_t)0;
+    }
+    __syncthreads();
+    const int c = tid >> 2, jq = (tid & 3) * 16;
+    if (c0 + c < d_out) {
+        union { uint16_t h[16]; u32x4 v[2]; } p;
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) p.h[jj] = t[jq + jj][c];
+        u32x4* dst = reinterpret_cast<u32x4*>(Bt + (size_t)(c0 + c) * ext_stride + j0 + jq);
+        dst[0] = p.v[0];
+        dst[1] = p.v[1];
+    }
+}
+
 __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ W_gate, const bf16_t* __restrict__ A,
                                                    int d_in, int N, int r, int wblocks, int wfrags, int64_t afrags,
-                                                   u32x4* __restrict__ wsp, u32x4* __restrict__ apk) {
+                                                   u32x4* __restrict__ wsp, u32x4* __restrict__ apk,
+                                                   const uint16_t* __restrict__ B, uint16_t* __restrict__ Bt,
+                                                   int d_out, int ext_stride, int bblocks) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if ((int)blockIdx.x < wblocks) {
-        const int frag = blockIdx.x * 4 + wave;
+    if ((int)blockIdx.x < bblocks) {   // uniform per workgroup
+        btrans_tile(B, d_out, N * r, ext_stride, blockIdx.x, threadIdx.x, Bt);
+        return;
+    }
+    const int blk = blockIdx.x - bblocks;
+    if (blk < wblocks) {
+        const int frag = blk * 4 + wave;
         if (frag < wfrags) wsplit_fragment(W_gate, d_in, N, padded_adapters(N) / 32, frag, lane, wsp);
     } else {
-        const int64_t frag = (int64_t)(blockIdx.x - wblocks) * 4 + wave;
+        const int64_t frag = (int64_t)(blk - wblocks) * 4 + wave;
         if (frag < afrags)
             apack_fragment(A, d_in, r, ceil_div(r, 32), skinny_kslices(d_in) * (kSkinnyKSL / 16), frag, lane, apk);
     }
 }
 
-hipError_t launch_prep(const float* W_gate, void* wsplit, const void* A, void* apack, int d_in, int N, int r,
-                       hipStream_t stream) {
+size_t prep_btrans_bytes(int d_out, int N, int r, bool bf16) {
+    return bf16 ? (size_t)d_out * align_up((size_t)N * r, 64) * sizeof(uint16_t) : 0;
+}
+
+hipError_t launch_prep(const float* W_gate, void* wsplit, const void* A, void* apack, const void* B, void* btrans,
+                       int d_in, int d_out, int N, int r, hipStream_t stream) {
     const int wfrags = (W_gate && wsplit) ? wsplit_fragments(d_in, N) : 0;
     const int64_t afrags = (A && apack) ? apack_fragments(d_in, N, r) : 0;
+    const int ext_stride = (int)align_up((size_t)N * r, 64);
+    const int bblocks = (B && btrans) ? (ext_stride / 64) * ceil_div(d_out, 64) : 0;
     const int wblocks = ceil_div(wfrags, 4);
-    const int64_t blocks = wblocks + ceil_div64(afrags, 4);
+    const int64_t blocks = (int64_t)bblocks + wblocks + ceil_div64(afrags, 4);
     if (blocks == 0) return hipSuccess;
     prep_kernel<<<(unsigned)blocks, 256, 0, stream>>>(W_gate, (const bf16_t*)A, d_in, N, r, wblocks, wfrags, afrags,
-                                                      (u32x4*)wsplit, (u32x4*)apack);
+                                                      (u32x4*)wsplit, (u32x4*)apack, (const uint16_t*)B,
+                                                      (uint16_t*)btrans, d_out, ext_stride, bblocks);
     return hipGetLastError();
 }
 
