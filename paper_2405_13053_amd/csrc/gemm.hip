@@ -106,7 +106,7 @@ size_t gemm_splitk_bytes(int T, int d_in, int d_out, bool bf16) {
 template <int MI, int NI>
 static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
     constexpr int BM = MI * 64, BN = NI * 64;
-    constexpr int smem = 2 * (BM + BN) * kGemmBK * (int)sizeof(bf16_t);
+    constexpr int smem = gemm_lds_bytes<MI, NI>();
     static bool attr_set = false;   // raising the dynamic-LDS limit is a host-side attribute, set once
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<MI, NI>),

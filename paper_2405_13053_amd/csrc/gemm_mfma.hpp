@@ -26,6 +26,17 @@ namespace meteora {
 constexpr int kGemmBK = 64;          // K elements per LDS tile
 constexpr int kGemmChunks = 8;       // 16-byte chunks per LDS row
 
+// LDS staging of the output tile in the pipelined kernel: a wavefront's (MI*32) x (NI*32) bf16 block,
+// rows padded by 16 bytes; the dynamic LDS size is the larger of the operand ring and this stage.
+template <int NI>
+__host__ __device__ constexpr int gemm_epilogue_stride() { return NI * 64 + 16; }
+template <int MI, int NI>
+__host__ __device__ constexpr int gemm_lds_bytes() {
+    constexpr int ring = 2 * (MI * 64 + NI * 64) * kGemmBK * 2;
+    constexpr int stage = 4 * (MI * 32) * gemm_epilogue_stride<NI>();
+    return ring > stage ? ring : stage;
+}
+
 struct GemmArgs {
     const bf16_t* x;      // [T, d_in]
     const bf16_t* W;      // [d_out, d_in]
@@ -431,6 +442,39 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
     for (; it + 2 < nk_main; ++it) tile_step(it, std::integral_constant<int, 0>{});
     for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{});
     for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{});
+
+    // Epilogue.  A lane holds 4 consecutive columns per block row, so direct stores are 8-byte pieces
+    // of 32 different rows per instruction; when the output is simply written (no split-K partials,
+    // no accumulate) the bf16 tile is staged in this wavefront's own LDS region and stored as
+    // 16-byte pieces that cover whole 128-byte lines.
+    if (a.partial == nullptr && !a.accumulate) {
+        constexpr int EST = gemm_epilogue_stride<NI>();   // bytes per staged row
+        __syncthreads();                                   // every wavefront is done with the operand tiles
+        unsigned char* ep = smem_raw + wave * (MI * 32) * EST;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint2 pk;
+                    pk.x = pack_bf16x2(acc[mi][ni][g * 4 + 0], acc[mi][ni][g * 4 + 1]);
+                    pk.y = pack_bf16x2(acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]);
+                    *reinterpret_cast<uint2*>(ep + (mi * 32 + lrow) * EST + (ni * 32 + g * 8 + khalf * 4) * 2) = pk;
+                }
+        __syncthreads();
+        constexpr int LPR = NI * 4, RPI = 64 / LPR;        // lanes per staged row, rows per store instruction
+        const int r_in = lane / LPR, c = (lane % LPR) * 8;
+        const int col = n0 + wn + c;
+#pragma unroll
+        for (int i = 0; i < MI * 32 / RPI; ++i) {
+            const int r = i * RPI + r_in;
+            const int row = m0 + wm + r;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(ep + r * EST + c * 2);
+            if (row < a.T && col < a.d_out) *reinterpret_cast<u32x4*>(a.out + (size_t)row * a.d_out + col) = v;
+        }
+        return;
+    }
 
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {

@@ -60,23 +60,28 @@ __device__ __forceinline__ void apack_fragment(const bf16_t* __restrict__ A, int
     apk[frag * 64 + lane] = p.v;
 }
 
-// tile (tj, tc): Bt[tc*64 + c][tj*64 + j] = B[tj*64 + j][tc*64 + c], zero where j >= ext_k
+// tile (tj, tc): Bt[tc*64 + c][tj*64 + j] = B[tj*64 + j][tc*64 + c], zero where j >= ext_k.
+// 16-byte loads along c, a padded LDS tile, 2 x 16-byte stores along j (d_out % 8 == 0, so a
+// chunk of 8 columns is all inside or all outside the matrix).
 __device__ __forceinline__ void btrans_tile(const uint16_t* __restrict__ B, int d_out, int ext_k, int ext_stride,
                                             int tile, int tid, uint16_t* __restrict__ Bt) {
-    __shared__ uint16_t t[64][66];
+    constexpr int LD = 72;   // 144-byte rows: 16-byte aligned, odd multiple of 16 B across banks
+    __shared__ __attribute__((aligned(16))) uint16_t t[64 * LD];
     const int tiles_j = ext_stride / 64;
     const int j0 = (tile % tiles_j) * 64, c0 = (tile / tiles_j) * 64;
-#pragma unroll 4
-    for (int i = 0; i < 16; ++i) {
-        const int j = i * 4 + (tid >> 6), c = tid & 63;
-        t[j][c] = (j0 + j < ext_k && c0 + c < d_out) ? B[(size_t)(j0 + j) * d_out + c0 + c] : (uint16_t)0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int j = i * 32 + (tid >> 3), c = (tid & 7) * 8;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (j0 + j < ext_k && c0 + c < d_out) v = *reinterpret_cast<const u32x4*>(B + (size_t)(j0 + j) * d_out + c0 + c);
+        *reinterpret_cast<u32x4*>(&t[j * LD + c]) = v;
     }
     __syncthreads();
     const int c = tid >> 2, jq = (tid & 3) * 16;
     if (c0 + c < d_out) {
         union { uint16_t h[16]; u32x4 v[2]; } p;
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj) p.h[jj] = t[jq + jj][c];
+        for (int jj = 0; jj < 16; ++jj) p.h[jj] = t[(jq + jj) * LD + c];
         u32x4* dst = reinterpret_cast<u32x4*>(Bt + (size_t)(c0 + c) * ext_stride + j0 + jq);
         dst[0] = p.v[0];
         dst[1] = p.v[1];
