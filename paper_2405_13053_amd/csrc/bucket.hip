@@ -47,12 +47,21 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
     const int c = blockIdx.x;
 
     {   // totals over all chunks and over the chunks before this one; wave w takes chunks w, w+4, ...
+        // (8 independent loads per step: the loop is bound by load latency, not by bandwidth)
         int tot = 0, bef = 0;
         if (lane < N) {
-            for (int cc = wave; cc < nchunks; cc += 4) {
-                const int v = chunk_counts[(size_t)cc * N + lane];
-                tot += v;
-                if (cc < c) bef += v;
+            for (int cc0 = wave; cc0 < nchunks; cc0 += 32) {
+                int v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int cc = cc0 + 4 * u;
+                    v[u] = cc < nchunks ? chunk_counts[(size_t)cc * N + lane] : 0;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    tot += v[u];
+                    if (cc0 + 4 * u < c) bef += v[u];
+                }
             }
         }
         part_total[wave][lane] = tot;

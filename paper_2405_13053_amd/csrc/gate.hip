@@ -86,9 +86,19 @@ __global__ __launch_bounds__(kTopkWaves * 64) void gate_topk_kernel(
 #pragma unroll
     for (int i = 0; i < G; ++i) { g[i] = 0.f; tok[i] = t0 + i * TPP + sub; }
     if (col < N) {
-        for (int s = 0; s < KS; ++s) {   // fixed order over K-slices; the groups' loads are independent
+        // fixed order over K-slices; 8 slices' loads are issued together (the loop is latency-bound),
+        // a missing slice adds +0.f, which leaves the sum unchanged
+        for (int s0 = 0; s0 < KS; s0 += 8) {
+            float v[8][G];
 #pragma unroll
-            for (int i = 0; i < G; ++i) g[i] += partials[((size_t)s * T + min(tok[i], T - 1)) * NP + col];
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < G; ++i)
+                    v[u][i] = s0 + u < KS ? partials[((size_t)(s0 + u) * T + min(tok[i], T - 1)) * NP + col] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < G; ++i) g[i] += v[u][i];
         }
         const float b = bias != nullptr ? bias[col] : 0.f;
 #pragma unroll

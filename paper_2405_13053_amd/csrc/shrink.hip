@@ -225,10 +225,18 @@ __global__ __launch_bounds__(256) void shrink_finalize_kernel(const float* __res
                 } else {
                     const size_t pair = (size_t)t * k + slot;
                     f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-                    for (int ks = 0; ks < KS; ++ks) {
-                        const float* src = hpart + ((size_t)ks * pairs + pair) * r + q0;
-                        lo += *reinterpret_cast<const f32x4*>(src);
-                        hi += *reinterpret_cast<const f32x4*>(src + 4);
+                    // K-slices are added in order; 8 slices' loads go out together (latency-bound loop)
+                    for (int ks0 = 0; ks0 < KS; ks0 += 8) {
+                        f32x4 vl[8], vh[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const float* src = hpart + ((size_t)min(ks0 + u, KS - 1) * pairs + pair) * r + q0;
+                            vl[u] = *reinterpret_cast<const f32x4*>(src);
+                            vh[u] = *reinterpret_cast<const f32x4*>(src + 4);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            if (ks0 + u < KS) { lo += vl[u]; hi += vh[u]; }
                     }
                     const float sw = scale * topk_w[pair];
 #pragma unroll
