@@ -132,6 +132,38 @@ meteora_status meteora_linear_forward(const void* x, const void* W, const float*
                                       void* ws, size_t ws_bytes, meteora_stream stream);
 
 /*
+ * Weight packing, done once when the adapters are loaded: the stacked adapter
+ * tensors of Sec. 3.3 and the gate weight are static during inference, so their
+ * kernel-side layouts (W_gate split into three bf16 terms in matrix-core operand
+ * order, A in operand order, B transposed) need not be rebuilt for every batch.
+ *   meteora_packed_bytes   size of the packed blob for these shapes (0 if this dtype
+ *                          uses no packed operands, e.g. METEORA_F32).  Host only.
+ *   meteora_pack_weights   fills `packed` (device, 256-byte aligned, caller-owned) from
+ *                          W_gate[d_in,N] fp32, A[N,d_in,r], B[N,r,d_out]; enqueued on
+ *                          `stream`.  The blob is valid for exactly these tensors and
+ *                          shapes; repack after changing any of them.
+ *   meteora_linear_forward_packed   meteora_linear_forward that reads the blob instead
+ *                          of repacking into the workspace.  `packed` = NULL behaves as
+ *                          meteora_linear_forward.  The results are bit-identical.
+ * Errors: METEORA_ERR_WORKSPACE if packed_bytes is smaller than meteora_packed_bytes.
+ */
+size_t meteora_packed_bytes(int d_in, int d_out, int N, int r, meteora_dtype dt);
+
+meteora_status meteora_pack_weights(const float* W_gate, const void* A, const void* B,
+                                    int d_in, int d_out, int N, int r, meteora_dtype dt,
+                                    void* packed, size_t packed_bytes, meteora_stream stream);
+
+meteora_status meteora_linear_forward_packed(const void* x, const void* W, const float* W_gate,
+                                             const float* gate_bias, const void* A, const void* B,
+                                             const void* packed, size_t packed_bytes,
+                                             int T, int d_in, int d_out, int N, int r, int k,
+                                             float scale, meteora_dtype dt,
+                                             void* out /*[T,d_out]*/,
+                                             int32_t* topk_idx_out /*[T,k] or NULL*/,
+                                             float* topk_w_out /*[T,k] or NULL*/,
+                                             void* ws, size_t ws_bytes, meteora_stream stream);
+
+/*
  * Base projection alone, first term of Eq. 1 / Eq. 2: out = x * W
  * (W stored [d_out, d_in]).  Exposed so the dense contraction can be checked
  * and timed on its own.

@@ -4,5 +4,5 @@ The compute lives in libmeteora.so (hand-written HIP for gfx950, C ABI in
 include/meteora.h).  This package is only the argument-marshalling binding.
 """
 from .binding import (MeteoraError, base_gemm, bucket_tokens, gate_topk, library_path,  # noqa: F401
-                      linear_forward, load_library, lora_forward, stage_timing_enable,
-                      stage_timing_read, workspace_bytes)
+                      linear_forward, load_library, lora_forward, pack_weights, packed_bytes,
+                      stage_timing_enable, stage_timing_read, workspace_bytes)

@@ -55,6 +55,13 @@ def load_library():
     lib.meteora_lora_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp, i, vp, sz, vp]
     lib.meteora_linear_forward.restype = i
     lib.meteora_linear_forward.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp, vp, vp, vp, sz, vp]
+    lib.meteora_packed_bytes.restype = sz
+    lib.meteora_packed_bytes.argtypes = [i, i, i, i, i]
+    lib.meteora_pack_weights.restype = i
+    lib.meteora_pack_weights.argtypes = [vp, vp, vp, i, i, i, i, i, vp, sz, vp]
+    lib.meteora_linear_forward_packed.restype = i
+    lib.meteora_linear_forward_packed.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, i, vp, vp,
+                                                  vp, vp, sz, vp]
     lib.meteora_base_gemm.restype = i
     lib.meteora_base_gemm.argtypes = [vp, vp, i, i, i, i, vp, vp]
     lib.meteora_stage_count.restype = i
@@ -164,15 +171,37 @@ def lora_forward(x, A, B, topk_idx, topk_w, scale: float, out: Optional[torch.Te
     return out
 
 
+def packed_bytes(d_in, d_out, N, r, dtype) -> int:
+    dt = BF16 if dtype in (torch.bfloat16, BF16, "bf16") else F32
+    return int(load_library().meteora_packed_bytes(d_in, d_out, N, r, dt))
+
+
+def pack_weights(W_gate, A, B, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """meteora_pack_weights: the kernel-side layouts of W_gate, A, B, built once per set of adapters."""
+    N, d_in, r = A.shape
+    d_out = B.shape[2]
+    _chk(W_gate, "W_gate", torch.float32, (d_in, N)); _chk(A, "A"); _chk(B, "B", A.dtype, (N, r, d_out))
+    nbytes = packed_bytes(d_in, d_out, N, r, A.dtype)
+    if out is None:
+        out = torch.empty((max(nbytes, 1),), dtype=torch.uint8, device=A.device)
+    st = load_library().meteora_pack_weights(_p(W_gate), _p(A), _p(B), d_in, d_out, N, r, _dt(A), _p(out),
+                                             out.numel(), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_pack_weights")
+    return out
+
+
 def linear_forward(x, W, W_gate, gate_bias, A, B, k: int, scale: float, out: Optional[torch.Tensor] = None,
-                   ws: Optional[torch.Tensor] = None, return_routing: bool = False):
-    """meteora_linear_forward: the whole layer (Eq. 2)."""
+                   ws: Optional[torch.Tensor] = None, return_routing: bool = False,
+                   packed: Optional[torch.Tensor] = None):
+    """meteora_linear_forward / meteora_linear_forward_packed (if `packed` is given): the whole layer (Eq. 2)."""
     T, d_in = x.shape
     d_out = W.shape[0]
     N, _, r = A.shape
     _chk(x, "x"); _chk(W, "W", x.dtype, (d_out, d_in)); _chk(W_gate, "W_gate", torch.float32, (d_in, N))
     _chk(gate_bias, "gate_bias", torch.float32, (N,))
     _chk(A, "A", x.dtype, (N, d_in, r)); _chk(B, "B", x.dtype, (N, r, d_out))
+    _chk(packed, "packed", torch.uint8)
     if out is None:
         out = torch.empty((T, d_out), dtype=x.dtype, device=x.device)
     _chk(out, "out", x.dtype, (T, d_out))
@@ -181,9 +210,15 @@ def linear_forward(x, W, W_gate, gate_bias, A, B, k: int, scale: float, out: Opt
         idx = torch.empty((T, k), dtype=torch.int32, device=x.device)
         w = torch.empty((T, k), dtype=torch.float32, device=x.device)
     ws = _ws(ws, workspace_bytes(T, d_in, d_out, N, r, k, x.dtype), x.device)
-    st = load_library().meteora_linear_forward(_p(x), _p(W), _p(W_gate), _p(gate_bias), _p(A), _p(B), T, d_in,
-                                               d_out, N, r, k, float(scale), _dt(x), _p(out), _p(idx), _p(w),
-                                               _p(ws), ws.numel(), _stream())
+    lib = load_library()
+    if packed is None:
+        st = lib.meteora_linear_forward(_p(x), _p(W), _p(W_gate), _p(gate_bias), _p(A), _p(B), T, d_in, d_out, N, r,
+                                        k, float(scale), _dt(x), _p(out), _p(idx), _p(w), _p(ws), ws.numel(),
+                                        _stream())
+    else:
+        st = lib.meteora_linear_forward_packed(_p(x), _p(W), _p(W_gate), _p(gate_bias), _p(A), _p(B), _p(packed),
+                                               packed.numel(), T, d_in, d_out, N, r, k, float(scale), _dt(x),
+                                               _p(out), _p(idx), _p(w), _p(ws), ws.numel(), _stream())
     if st != 0:
         raise MeteoraError(st, "meteora_linear_forward")
     return (out, idx, w) if return_routing else out

@@ -52,6 +52,23 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     return L;
 }
 
+// Packed weights (meteora_pack_weights): the three operand layouts, each 256-byte aligned.
+struct PackLayout { size_t wsplit, apack, btrans, total; };
+
+PackLayout pack_layout(int d_in, int d_out, int N, int r, bool bf16) {
+    PackLayout P{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    P.wsplit = take(gate_wsplit_bytes(d_in, N, bf16));
+    P.apack = take(shrink_apack_bytes(d_in, N, r, bf16));
+    P.btrans = take(prep_btrans_bytes(d_out, N, r, bf16));
+    P.total = off;
+    return P;
+}
+
+// Where the kernels find the packed operands: in the caller's blob, or in the workspace after a prep launch.
+struct PackedPtrs { void* wsplit; void* apack; void* btrans; };
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
@@ -220,7 +237,7 @@ static meteora_status check_lora_args(const void* x, const void* A, const void* 
 static meteora_status run_lora(const void* x, const void* W, const void* A, const void* B, const int32_t* topk_idx,
                                const float* topk_w, int T, int d_in, int d_out, int N, int r, int k, float scale,
                                bool bf16, void* out, int accumulate, void* ws, const WsLayout& L,
-                               hipStream_t st, int tslot, bool have_hist) {
+                               const PackedPtrs& pk, hipStream_t st, int tslot, bool have_hist) {
     int32_t* offsets = at<int32_t>(ws, L.offsets);
     int32_t* btok = at<int32_t>(ws, L.bucket_tok);
     int32_t* bslot = at<int32_t>(ws, L.bucket_slot);
@@ -234,14 +251,14 @@ static meteora_status run_lora(const void* x, const void* W, const void* A, cons
     {
         StageScope sc(ST_SHRINK, st, tslot);
         METEORA_HIP(launch_shrink(x, A, topk_idx, topk_w, offsets, btok, bslot, T, d_in, N, r, k, scale, bf16,
-                                  at<void>(ws, L.apack), at<float>(ws, L.hpart), fused ? nullptr : h32,
+                                  pk.apack, at<float>(ws, L.hpart), fused ? nullptr : h32,
                                   fused ? at<void>(ws, L.hdense) : nullptr, L.ext_stride, st));
     }
     if (fused) {
         // base projection (if W is given) and LoRA expand in one MFMA kernel, one rounding of the output
         StageScope sc(ST_GEMM, st, tslot);
         METEORA_HIP(launch_gemm(x, W, T, W ? d_in : 0, d_out, bf16, at<void>(ws, L.hdense), L.ext_stride,
-                                at<void>(ws, L.btrans), N * r, out, accumulate,
+                                pk.btrans, N * r, out, accumulate,
                                 gemm_splitk_bytes(T, d_in, d_out, bf16) > 0 ? at<float>(ws, L.splitk) : nullptr, st));
     } else {
         if (W) {
@@ -274,8 +291,9 @@ meteora_status meteora_lora_forward(const void* x, const void* A, const void* B,
                                 pb ? B : nullptr, pb ? at<void>(ws, L.btrans) : nullptr, d_in, d_out, N, r,
                                 static_cast<hipStream_t>(stream)));
     }
+    const PackedPtrs pk{nullptr, at<void>(ws, L.apack), at<void>(ws, L.btrans)};
     return run_lora(x, nullptr, A, B, topk_idx, topk_w, T, d_in, d_out, N, r, k, scale, bf16, out, accumulate, ws, L,
-                    static_cast<hipStream_t>(stream), timing_begin_call(), false);
+                    pk, static_cast<hipStream_t>(stream), timing_begin_call(), false);
 }
 
 meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, int d_out, meteora_dtype dt,
@@ -291,10 +309,39 @@ meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, 
     return METEORA_OK;
 }
 
-meteora_status meteora_linear_forward(const void* x, const void* W, const float* W_gate, const float* gate_bias,
-                                      const void* A, const void* B, int T, int d_in, int d_out, int N, int r,
-                                      int k, float scale, meteora_dtype dt, void* out, int32_t* topk_idx_out,
-                                      float* topk_w_out, void* ws, size_t ws_bytes, meteora_stream stream) {
+size_t meteora_packed_bytes(int d_in, int d_out, int N, int r, meteora_dtype dt) {
+    if (!shape_ok(0, d_in, d_out, N, r, 1) || !shape_supported(0, d_in, d_out, N, r, 1)) return 0;
+    if (dt != METEORA_F32 && dt != METEORA_BF16) return 0;
+    return pack_layout(d_in, d_out, N, r, dt == METEORA_BF16).total;
+}
+
+meteora_status meteora_pack_weights(const float* W_gate, const void* A, const void* B, int d_in, int d_out, int N,
+                                    int r, meteora_dtype dt, void* packed, size_t packed_bytes,
+                                    meteora_stream stream) {
+    if (!W_gate || !A || !B) return METEORA_ERR_INVALID_ARG;
+    if (!shape_ok(0, d_in, d_out, N, r, 1)) return METEORA_ERR_INVALID_ARG;
+    if (dt != METEORA_F32 && dt != METEORA_BF16) return METEORA_ERR_UNSUPPORTED;
+    if (!shape_supported(0, d_in, d_out, N, r, 1)) return METEORA_ERR_UNSUPPORTED;
+    if (!aligned16(W_gate) || !aligned16(A) || !aligned16(B)) return METEORA_ERR_UNSUPPORTED;
+    const bool bf16 = dt == METEORA_BF16;
+    const PackLayout P = pack_layout(d_in, d_out, N, r, bf16);
+    if (P.total == 0) return METEORA_OK;   // this dtype reads the tensors as they are
+    if (!packed || !aligned256(packed) || packed_bytes < P.total) return METEORA_ERR_WORKSPACE;
+    const bool pw = gate_wsplit_bytes(d_in, N, bf16) > 0, pa = shrink_apack_bytes(d_in, N, r, bf16) > 0;
+    const bool pb = prep_btrans_bytes(d_out, N, r, bf16) > 0;
+    METEORA_HIP(launch_prep(pw ? W_gate : nullptr, pw ? at<void>(packed, P.wsplit) : nullptr, pa ? A : nullptr,
+                            pa ? at<void>(packed, P.apack) : nullptr, pb ? B : nullptr,
+                            pb ? at<void>(packed, P.btrans) : nullptr, d_in, d_out, N, r,
+                            static_cast<hipStream_t>(stream)));
+    return METEORA_OK;
+}
+
+meteora_status meteora_linear_forward_packed(const void* x, const void* W, const float* W_gate,
+                                             const float* gate_bias, const void* A, const void* B,
+                                             const void* packed, size_t packed_bytes, int T, int d_in, int d_out,
+                                             int N, int r, int k, float scale, meteora_dtype dt, void* out,
+                                             int32_t* topk_idx_out, float* topk_w_out, void* ws, size_t ws_bytes,
+                                             meteora_stream stream) {
     if (!W || !W_gate) return METEORA_ERR_INVALID_ARG;
     meteora_status s = check_lora_args(x, A, B, T, d_in, d_out, N, r, k, scale, dt, out);
     if (s != METEORA_OK) return s;
@@ -304,30 +351,45 @@ meteora_status meteora_linear_forward(const void* x, const void* W, const float*
     const bool bf16 = dt == METEORA_BF16;
     const WsLayout L = ws_layout(T, d_in, d_out, N, r, k, bf16);
     if (!ws || !aligned256(ws) || ws_bytes < L.total) return METEORA_ERR_WORKSPACE;
+    const PackLayout P = pack_layout(d_in, d_out, N, r, bf16);
+    const bool use_packed = packed != nullptr && P.total > 0;
+    if (use_packed && (!aligned256(packed) || packed_bytes < P.total)) return METEORA_ERR_WORKSPACE;
     if (T == 0) return METEORA_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int32_t* idx = topk_idx_out ? topk_idx_out : at<int32_t>(ws, L.topk_idx);
     float* w = topk_w_out ? topk_w_out : at<float>(ws, L.topk_w);
     float* partials = at<float>(ws, L.partials);
     const int tslot = timing_begin_call();
-    {
+    PackedPtrs pk{at<void>(ws, L.wsplit), at<void>(ws, L.apack), at<void>(ws, L.btrans)};
+    if (use_packed) {
+        void* blob = const_cast<void*>(packed);   // read only from here on
+        pk = PackedPtrs{at<void>(blob, P.wsplit), at<void>(blob, P.apack), at<void>(blob, P.btrans)};
+    } else {
         StageScope sc(ST_PREP, st, tslot);
         const bool pw = gate_wsplit_bytes(d_in, N, bf16) > 0, pa = shrink_apack_bytes(d_in, N, r, bf16) > 0;
         const bool pb = prep_btrans_bytes(d_out, N, r, bf16) > 0;
-        METEORA_HIP(launch_prep(pw ? W_gate : nullptr, pw ? at<void>(ws, L.wsplit) : nullptr, pa ? A : nullptr,
-                                pa ? at<void>(ws, L.apack) : nullptr, pb ? B : nullptr,
-                                pb ? at<void>(ws, L.btrans) : nullptr, d_in, d_out, N, r, st));
+        METEORA_HIP(launch_prep(pw ? W_gate : nullptr, pw ? pk.wsplit : nullptr, pa ? A : nullptr,
+                                pa ? pk.apack : nullptr, pb ? B : nullptr, pb ? pk.btrans : nullptr, d_in, d_out,
+                                N, r, st));
     }
     {
         StageScope sc(ST_GATE_LOGITS, st, tslot);
-        METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, at<void>(ws, L.wsplit), partials, st));
+        METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, pk.wsplit, partials, st));
     }
     {
         StageScope sc(ST_GATE_TOPK, st, tslot);
         METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, 1.0f, idx, w,
                                      nullptr, at<int32_t>(ws, L.chunk_counts), st));
     }
-    return run_lora(x, W, A, B, idx, w, T, d_in, d_out, N, r, k, scale, bf16, out, 0, ws, L, st, tslot, true);
+    return run_lora(x, W, A, B, idx, w, T, d_in, d_out, N, r, k, scale, bf16, out, 0, ws, L, pk, st, tslot, true);
+}
+
+meteora_status meteora_linear_forward(const void* x, const void* W, const float* W_gate, const float* gate_bias,
+                                      const void* A, const void* B, int T, int d_in, int d_out, int N, int r,
+                                      int k, float scale, meteora_dtype dt, void* out, int32_t* topk_idx_out,
+                                      float* topk_w_out, void* ws, size_t ws_bytes, meteora_stream stream) {
+    return meteora_linear_forward_packed(x, W, W_gate, gate_bias, A, B, nullptr, 0, T, d_in, d_out, N, r, k, scale,
+                                         dt, out, topk_idx_out, topk_w_out, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -23,7 +23,8 @@ def test_every_declared_symbol_is_exported(lib):
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = sorted(set(re.findall(r"\b(meteora_[a-z_0-9]+)\s*\(", hdr)))
     assert {"meteora_gate_topk", "meteora_bucket_tokens", "meteora_lora_forward", "meteora_linear_forward",
-            "meteora_base_gemm", "meteora_workspace_bytes"} <= set(names)
+            "meteora_base_gemm", "meteora_workspace_bytes", "meteora_packed_bytes", "meteora_pack_weights",
+            "meteora_linear_forward_packed"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in meteora.h but not exported"
 
@@ -115,6 +116,38 @@ def test_lora_and_linear_validation(lib):
     assert lin(Wg=None) == INVALID
     need = m.workspace_bytes(64, 256, 256, 4, 8, 2, "bf16")
     assert lin(wsb=need - 512) == WORKSPACE
+
+
+def test_pack_weights_validation(lib):
+    """Packed-weight entry points: sizes and argument checks (no launch happens on any error path)."""
+    assert lib.meteora_packed_bytes(256, 256, 4, 8, F32) == 0          # fp32 reads the tensors as they are
+    need = lib.meteora_packed_bytes(4096, 4096, 28, 8, BF16)
+    # split gate weight (3 bf16 terms, 32 padded columns) + A in operand order (rank padded to 32) + B transposed
+    assert need >= 4096 * 32 * 3 * 2 + 28 * 4096 * 32 * 2 + 4096 * 256 * 2
+    assert lib.meteora_packed_bytes(4096, 4096, 65, 8, BF16) == 0      # unsupported shape
+    assert m.packed_bytes(4096, 4096, 28, 8, "bf16") == need
+
+    def pack(Wg=P, A=P, B=P, di=256, do=256, N=4, r=8, dt=BF16, pk=WS, pkb=BIG):
+        return lib.meteora_pack_weights(Wg, A, B, di, do, N, r, dt, pk, pkb, None)
+
+    assert pack(Wg=None) == INVALID and pack(A=None) == INVALID and pack(B=None) == INVALID
+    assert pack(N=0) == INVALID
+    assert pack(r=65) == UNSUPPORTED
+    assert pack(dt=5) == UNSUPPORTED
+    assert pack(A=ODD) == UNSUPPORTED
+    assert pack(pk=None) == WORKSPACE
+    assert pack(pkb=64) == WORKSPACE
+    assert pack(dt=F32, pk=None, pkb=0) == OK                           # nothing to pack
+
+    def linp(pk=WS, pkb=BIG, T=64, ws=WS, wsb=BIG, W=P):
+        return lib.meteora_linear_forward_packed(P, W, P, None, P, P, pk, pkb, T, 256, 256, 4, 8, 2, 2.0, BF16, P,
+                                                 None, None, ws, wsb, None)
+
+    assert linp(pkb=64) == WORKSPACE
+    assert linp(pk=ODD) == WORKSPACE
+    assert linp(W=None) == INVALID
+    assert linp(wsb=1024) == WORKSPACE
+    assert linp(T=0) == OK
 
 
 def test_base_gemm_validation(lib):

@@ -184,6 +184,11 @@ def _check_layer(shape, seed, layer=0, rows="all", n_strided=256):
                                 shape.scale, rows=sel)
     err = util.rel_max_err(y_gpu, ref["y"])
     assert err <= util.tol(shape), f"{shape.name}: rel err {err:.3e}"
+    # weights packed once (meteora_pack_weights) instead of per call: the same kernels on the same layouts
+    packed = m.pack_weights(dev["W_gate"], dev["A"], dev["B"])
+    out_p, idx_p, w_p = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], dev["bias"], dev["A"], dev["B"],
+                                         shape.k, shape.scale, return_routing=True, packed=packed)
+    assert torch.equal(out_p, out) and torch.equal(idx_p, idx) and torch.equal(w_p, w)
     return out
 
 
@@ -202,6 +207,19 @@ def test_linear_forward_zero_B_is_base_and_deterministic():
     y1 = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], None, dev["A"], dev["B"], 2, 2.0)
     y2 = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], None, dev["A"], dev["B"], 2, 2.0)
     assert torch.equal(y1, y2)
+
+
+def test_packed_weights_serve_many_batches():
+    """One blob, two different batches and batch sizes: each equals the per-call-packing result."""
+    shape = LS(333, 1024, 776, 28, 8, 2, 2.0, "bf16")
+    ops, dev = util.make_case(shape, seed=44)
+    packed = m.pack_weights(dev["W_gate"], dev["A"], dev["B"])
+    assert packed.numel() == m.packed_bytes(1024, 776, 28, 8, "bf16")
+    for rows in (slice(0, 333), slice(17, 150)):
+        x = dev["x"][rows].contiguous()
+        y_ref = m.linear_forward(x, dev["W"], dev["W_gate"], None, dev["A"], dev["B"], 2, 2.0)
+        y = m.linear_forward(x, dev["W"], dev["W_gate"], None, dev["A"], dev["B"], 2, 2.0, packed=packed)
+        assert torch.equal(y, y_ref)
 
 
 def test_linear_forward_single_adapter_is_merged_gemm():
