@@ -218,7 +218,7 @@ meteora_status meteora_bucket_tokens(const int32_t* topk_idx, int T, int k, int 
         return METEORA_OK;
     }
     METEORA_HIP(launch_bucket(topk_idx, T, k, N, static_cast<int32_t*>(ws), false, counts, offsets, bucket_tok,
-                              bucket_slot, static_cast<hipStream_t>(stream)));
+                              bucket_slot, nullptr, 0, static_cast<hipStream_t>(stream)));
     return METEORA_OK;
 }
 
@@ -245,8 +245,10 @@ static meteora_status run_lora(const void* x, const void* W, const void* A, cons
     const bool fused = gemm_fuses_expand(bf16);
     {
         StageScope sc(ST_BUCKET, st, tslot);
+        const bool clear = fused && !shrink_clears_hdense(bf16, r, T, k);
         METEORA_HIP(launch_bucket(topk_idx, T, k, N, at<int32_t>(ws, L.chunk_counts), have_hist,
-                                  at<int32_t>(ws, L.counts), offsets, btok, bslot, st));
+                                  at<int32_t>(ws, L.counts), offsets, btok, bslot,
+                                  clear ? at<void>(ws, L.hdense) : nullptr, L.ext_stride * (int)sizeof(uint16_t), st));
     }
     {
         StageScope sc(ST_SHRINK, st, tslot);

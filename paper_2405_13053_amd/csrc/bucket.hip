@@ -39,12 +39,19 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
                                                              int32_t* __restrict__ counts,
                                                              int32_t* __restrict__ offsets,
                                                              int32_t* __restrict__ bucket_tok,
-                                                             int32_t* __restrict__ bucket_slot) {
+                                                             int32_t* __restrict__ bucket_slot,
+                                                             u32x4* __restrict__ clear, int clear_row16, int T) {
     __shared__ int part_total[4][kMaxAdapters], part_before[4][kMaxAdapters];
     __shared__ int running[kMaxAdapters];    // next write position of adapter j for this chunk
     __shared__ int wave_hist[4][kMaxAdapters];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = blockIdx.x;
+
+    if (clear != nullptr) {   // this chunk's rows of the dense expand operand start as zeros
+        const int rows = min(kBucketChunkTokens, T - c * kBucketChunkTokens);
+        u32x4* dst = clear + (size_t)c * kBucketChunkTokens * clear_row16;
+        for (int i = threadIdx.x; i < rows * clear_row16; i += 256) dst[i] = u32x4{0u, 0u, 0u, 0u};
+    }
 
     {   // totals over all chunks and over the chunks before this one; wave w takes chunks w, w+4, ...
         // (8 independent loads per step: the loop is bound by load latency, not by bandwidth)
@@ -125,7 +132,7 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
 
 hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* chunk_counts, bool have_hist,
                          int32_t* counts, int32_t* offsets, int32_t* bucket_tok, int32_t* bucket_slot,
-                         hipStream_t stream) {
+                         void* clear_rows, int clear_row_bytes, hipStream_t stream) {
     const int64_t pairs = (int64_t)T * k;
     const int nchunks = bucket_chunks(T);
     if (!have_hist) {
@@ -134,7 +141,8 @@ hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* 
         if (e != hipSuccess) return e;
     }
     bucket_scatter_kernel<<<nchunks, 256, 0, stream>>>(topk_idx, pairs, k, N, nchunks, chunk_counts, counts,
-                                                       offsets, bucket_tok, bucket_slot);
+                                                       offsets, bucket_tok, bucket_slot, (u32x4*)clear_rows,
+                                                       clear_row_bytes / 16, T);
     return hipGetLastError();
 }
 

@@ -32,15 +32,20 @@ hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, in
 constexpr int kBucketChunkTokens = 64;   // tokens (k pairs each) whose pairs one workgroup histograms and scatters
 inline int bucket_chunks(int T) { return (T + kBucketChunkTokens - 1) / kBucketChunkTokens; }
 // have_hist: chunk_counts already holds the histograms (written by launch_gate_topk)
+// clear_rows (optional): a [T][clear_row_bytes] array (row bytes a multiple of 16) that the scatter zeroes,
+// every chunk its own rows: the dense expand operand that launch_shrink then fills in (shrink_clears_hdense)
 hipError_t launch_bucket(const int32_t* topk_idx, int T, int k, int N, int32_t* chunk_counts, bool have_hist,
                          int32_t* counts, int32_t* offsets, int32_t* bucket_tok, int32_t* bucket_slot,
-                         hipStream_t stream);
+                         void* clear_rows, int clear_row_bytes, hipStream_t stream);
 
 // ---- grouped LoRA shrink: h[t,slot,:] = x[t,:] * A[idx[t,slot]] ---------------------------
 // h32 ([T,k,r] fp32) and/or hdense (bf16 [T, ext_stride], column idx*r+q = scale*w*h, other
 // columns zero) are written; either may be NULL.
 // apack / hpart: scratch of shrink_apack_bytes / shrink_hpart_bytes (A in MFMA operand order,
 // per-K-slice partial sums); both sizes are 0 when the plain-FMA kernel is used.
+// false: launch_shrink writes only the selected columns of hdense, so the caller has its rows cleared
+// first (launch_bucket's clear_rows); true: launch_shrink writes every column itself
+bool shrink_clears_hdense(bool bf16, int r, int T, int k);
 size_t shrink_apack_bytes(int d_in, int N, int r, bool bf16);
 size_t shrink_hpart_bytes(int T, int d_in, int r, int k, bool bf16);
 hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, const float* topk_w,

@@ -197,6 +197,188 @@ __global__ __launch_bounds__(256) void shrink_mfma_kernel(const bf16_t* __restri
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// MFMA version for bf16, whole contraction in one workgroup.
+//
+// A tile is up to RB*32 consecutive pairs of one adapter's bucket; the workgroup walks all of
+// d_in in 512-wide slices.  Each of the 4 wavefronts takes a quarter of every slice: it gathers
+// its piece of the token rows straight from HBM into its own LDS region (16-byte global->LDS
+// loads, 16 lanes per 256-byte row segment, XOR-swizzled chunks) and multiplies it by A_a
+// fragments already laid out in MFMA operand order (one contiguous 1 KB block per fragment).
+// The loads of slice s+1 (x piece into the other half of the region, A fragments into the other
+// register set) are in flight while slice s is multiplied; the wavefronts do not synchronise in
+// the loop.  At the end the 4 K quarters are summed through LDS in a fixed order and the tile's
+// pairs are written as h32[pair][r] and/or as their r columns of the dense expand operand
+// hdense[t][a*r+q] = bf16(scale * w[t,slot] * h); the other columns of hdense must already be
+// zero (the bucket scatter clears the rows).
+// ------------------------------------------------------------------------------------------
+__host__ __device__ constexpr int shrink_fullk_region_bytes(int RCB, int RB) {
+    const int xbytes = 2 * RB * 32 * 256, red = RB * 32 * (RCB * 128 + 16);
+    return (int)align_up((size_t)(xbytes > red ? xbytes : red), 1024);
+}
+
+template <int RCB, int RB>
+__global__ __launch_bounds__(256) void shrink_fullk_kernel(const bf16_t* __restrict__ x, const u32x4* __restrict__ apk,
+                                                           const int32_t* __restrict__ offsets,
+                                                           const int32_t* __restrict__ bucket_tok,
+                                                           const int32_t* __restrict__ bucket_slot,
+                                                           const float* __restrict__ topk_w, int T, int d_in, int N,
+                                                           int r, int k, int KS, float scale,
+                                                           float* __restrict__ h32, bf16_t* __restrict__ hdense,
+                                                           int ext_stride) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int TM = RB * 32;                                   // pairs per tile (<= 64)
+    constexpr int kXBytes = RB * 32 * 256;                        // one x piece
+    constexpr int kRegion = shrink_fullk_region_bytes(RCB, RB);   // LDS bytes per wavefront
+    constexpr int kLoads = RB * 8 + 8 * RCB;                      // vector-memory instructions per slice
+    static_assert(TM <= 64 && kLoads < 64, "one lane per tile row; vmcnt holds 6 bits");
+    __shared__ int pair_of_row[TM];
+    const int lane = threadIdx.x & 63, wq = threadIdx.x >> 6;
+    const int tile_id = blockIdx.x;
+
+    // which (adapter, tile of its bucket) is tile_id?  lane j owns adapter j.
+    int a, row_start, nrows;
+    {
+        const int lo = (lane < N) ? offsets[lane] : 0, hi = (lane < N) ? offsets[lane + 1] : 0;
+        const int tiles = ceil_div(hi - lo, TM);
+        int incl = tiles;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int n = __shfl_up(incl, off);
+            if (lane >= off) incl += n;
+        }
+        const unsigned long long m = __ballot(lane < N && tile_id < incl);
+        if (m == 0ull) return;   // past the last tile: the whole workgroup leaves together
+        a = __ffsll((long long)m) - 1;
+        const int excl = __shfl(incl - tiles, a);
+        const int blo = __shfl(lo, a), bhi = __shfl(hi, a);
+        row_start = blo + (tile_id - excl) * TM;
+        nrows = min(TM, bhi - row_start);
+    }
+    // token of tile row `lane` (rows past the end repeat row 0: loaded, multiplied, never stored)
+    int tok;
+    {
+        const int r0 = lane < nrows ? lane : 0;
+        tok = min(max(bucket_tok[row_start + r0], 0), T - 1);
+        if (wq == 0 && lane < TM) pair_of_row[lane] = tok * k + min(max(bucket_slot[row_start + r0], 0), k - 1);
+    }
+    unsigned char* region = smem + wq * kRegion;
+    const int S16 = KS * (kShrKSL / 16);
+    const int rsub = lane >> 4, p = lane & 15;
+
+    auto issue = [&](int s, int buf, bf16x8 (&af)[8][RCB]) {
+        const int kbase = s * kShrKSL + wq * kShrKW;
+#pragma unroll
+        for (int j = 0; j < RB * 8; ++j) {
+            const int row = 4 * j + rsub;
+            const int t = __shfl(tok, row);
+            int kk = kbase + ((p ^ (row & 15)) << 3);
+            kk = kk <= d_in - 8 ? kk : d_in - 8;   // columns past d_in meet zero weights
+            const bf16_t* src = x + (size_t)t * d_in + kk;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(region + buf * kXBytes + j * 1024),
+                                             16, 0, 0);
+        }
+        const u32x4* abase = apk + ((size_t)a * S16 + (size_t)(s * 4 + wq) * 8) * RCB * 64 + lane;
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8)
+#pragma unroll
+            for (int cb = 0; cb < RCB; ++cb) {
+                const u32x4 v = abase[(size_t)(s8 * RCB + cb) * 64];
+                af[s8][cb] = __builtin_bit_cast(bf16x8, v);
+            }
+    };
+
+    f32x16 acc[RB][RCB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < RCB; ++cb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.f;
+    const int lrow = lane & 31, khalf = lane >> 5;
+    const int nrb = ceil_div(nrows, 32);   // row blocks that hold at least one pair
+
+    auto compute = [&](int buf, const bf16x8 (&af)[8][RCB]) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            if (rb < nrb) {   // uniform
+#pragma unroll
+                for (int s8 = 0; s8 < 8; ++s8) {
+                    const int row = rb * 32 + lrow;
+                    const int pos = (s8 * 2 + khalf) ^ (row & 15);
+                    const bf16x8 xf = *reinterpret_cast<const bf16x8*>(region + buf * kXBytes + row * 256 + pos * 16);
+#pragma unroll
+                    for (int cb = 0; cb < RCB; ++cb)
+                        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s8][cb], xf, acc[rb][cb], 0, 0, 0);
+                }
+            }
+        }
+    };
+    // all loads of the older slice have landed when at most the newer slice's kLoads are outstanding
+    auto wait_older = [&](bool newer_in_flight) {
+        if (newer_in_flight) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    // Two slices per round, branch-free while both successors exist (a branch around a load would make
+    // the compiler wait for every outstanding load before the next use of a fragment register).
+    bf16x8 af0[8][RCB], af1[8][RCB];
+    issue(0, 0, af0);
+    int s = 0;
+    for (; s + 2 < KS; s += 2) {
+        issue(s + 1, 1, af1);
+        wait_older(true);
+        compute(0, af0);
+        __builtin_amdgcn_wave_barrier();   // this wavefront's reads of half 0 are done before it is refilled
+        issue(s + 2, 0, af0);
+        wait_older(true);
+        compute(1, af1);
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (s + 1 < KS) {   // two slices left (uniform)
+        issue(s + 1, 1, af1);
+        wait_older(true);
+        compute(0, af0);
+        wait_older(false);
+        compute(1, af1);
+    } else {            // one slice left
+        wait_older(false);
+        compute(0, af0);
+    }
+
+    // ---- sum the 4 K quarters through LDS (fixed order), then emit the tile's pairs ----------------
+    constexpr int kRowBytes = RCB * 128 + 16;
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < RCB; ++cb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int m = rb * 32 + lrow, n = cb * 32 + g * 8 + khalf * 4;
+                f32x4 v = {acc[rb][cb][g * 4 + 0], acc[rb][cb][g * 4 + 1], acc[rb][cb][g * 4 + 2],
+                           acc[rb][cb][g * 4 + 3]};
+                *reinterpret_cast<f32x4*>(region + m * kRowBytes + n * 4) = v;
+            }
+    __syncthreads();
+    for (int e = threadIdx.x; e < nrows * r; e += 256) {
+        const int m = e / r, q = e - m * r;
+        const int off = m * kRowBytes + q * 4;
+        const float v0 = *reinterpret_cast<const float*>(smem + off);
+        const float v1 = *reinterpret_cast<const float*>(smem + kRegion + off);
+        const float v2 = *reinterpret_cast<const float*>(smem + 2 * kRegion + off);
+        const float v3 = *reinterpret_cast<const float*>(smem + 3 * kRegion + off);
+        const float h = (v0 + v1) + (v2 + v3);
+        const int pair = pair_of_row[m];
+        if (h32) h32[(size_t)pair * r + q] = h;
+        if (hdense)
+            hdense[(size_t)(pair / k) * ext_stride + a * r + q] = from_float<bf16_t>(scale * topk_w[pair] * h);
+    }
+}
+
 // Sum the K-slices (fixed order) and emit h32[pair][r] and/or the dense expand operand
 // hdense[t][a*r+q] = bf16(scale * w[t,slot] * h), zero where the token did not select adapter a.
 // One thread per 16-byte chunk (8 columns) of hdense.  R8 = (r % 8 == 0): the chunk lies inside one
@@ -281,6 +463,13 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* __restrict__ p, s
 
 static int shrink_kslices(int d_in) { return ceil_div(d_in, kShrKSL); }
 static bool shrink_uses_mfma(bool bf16, int r) { return bf16 && r <= 64; }
+// Whole-K tiles (one kernel, no partial sums) need enough tiles in flight to cover the memory latency:
+// with fewer than 512 tiles of 32 pairs the K-split kernel + finalize is faster (measured: 4096 tokens
+// x top-2 = 256 tiles: 25 us against 20; 16384 x 2: 54 against 64, and 214 against 255 at d_in = 14336).
+static bool shrink_whole_k(bool bf16, int r, int64_t pairs) {
+    return shrink_uses_mfma(bf16, r) && pairs >= 16384;
+}
+bool shrink_clears_hdense(bool bf16, int r, int T, int k) { return !shrink_whole_k(bf16, r, (int64_t)T * k); }
 
 size_t shrink_apack_bytes(int d_in, int N, int r, bool bf16) {
     if (!shrink_uses_mfma(bf16, r)) return 0;
@@ -301,6 +490,20 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
     if (shrink_uses_mfma(bf16, r)) {
         const int KS = shrink_kslices(d_in), RCB = ceil_div(r, 32), S16 = KS * (kShrKSL / 16);
         // apack has been filled by launch_prep
+        if (shrink_whole_k(bf16, r, pairs)) {
+            auto launch_wk = [&](auto kern) -> hipError_t {
+                const int smem = 4 * shrink_fullk_region_bytes(RCB, 1);
+                hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+                if (err != hipSuccess) return err;
+                const int64_t max_tiles = ceil_div64(pairs, 32) + N;   // every bucket rounds up by at most one tile
+                kern<<<(unsigned)max_tiles, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)apack, offsets,
+                                                                 bucket_tok, bucket_slot, topk_w, T, d_in, N, r, k, KS,
+                                                                 scale, h32, (bf16_t*)hdense, ext_stride);
+                return hipGetLastError();
+            };
+            return RCB == 1 ? launch_wk(shrink_fullk_kernel<1, 1>) : launch_wk(shrink_fullk_kernel<2, 1>);
+        }
         // 64-pair tiles: little padding in small buckets and two workgroups per CU (one loads while the
         // other computes); measured faster than 32- or 128-pair tiles on every configuration
         auto launch = [&](auto kern, int rb) -> hipError_t {

@@ -123,6 +123,9 @@ LORA_SHAPES = [
     LS(517, 1024, 520, 28, 16, 2, 2.0, "bf16", "zipf", "bf16-r16-zipf"),
     LS(70, 264, 136, 6, 5, 3, 0.5, "bf16", "uniform", "odd-r"),
     LS(40, 128, 64, 3, 64, 1, 1.0, "f32", "uniform", "r64-top1"),
+    # >= 16384 (token, slot) pairs: the shrink runs whole-K tiles and the scatter clears the expand operand
+    LS(8300, 520, 136, 28, 16, 2, 2.0, "bf16", "zipf", "whole-K-shrink-ragged"),
+    LS(4200, 264, 72, 5, 40, 4, 1.0, "bf16", "uniform", "whole-K-shrink-r40"),
 ]
 
 
