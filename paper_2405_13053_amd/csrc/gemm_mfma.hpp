@@ -54,7 +54,11 @@ struct GemmArgs {
     int splits, tiles_per_split;
 };
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7); }
+// LDS position of 16-byte chunk `chunk` of a 128-byte tile row.  A ds_read_b128 pass serves 16 lanes =
+// 16 consecutive rows of one chunk; rows alternate between the two halves of the 64 banks, so rows 2m and
+// 2m+1 may share a position and the 8 row pairs need 8 different ones: the pass then touches every bank
+// once.  (chunk ^ (row & 7) puts rows m and m+8 on the same banks: a 2-way conflict on every read.)
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
 // Load a [ROWS x 64] bf16 tile (rows row0.., K columns k0..k0+64 of a row-major matrix with
 // leading dimension ld) into registers: thread tid handles chunk (tid & 7) of rows (tid>>3) + 32*i.
@@ -261,8 +265,8 @@ __device__ __forceinline__ void mma_frags(f32x16 (&acc)[MI][NI], const Frags<MI,
 }
 
 // A [rows x 64-element-tiles] operand as the global->LDS loads see it.  An instruction moves 8 rows
-// (8 lanes x 16 B per 128-byte tile row); lane (rsub, p) fetches chunk p ^ rsub of its row so the
-// LDS image is the swizzled layout.  Wavefront `wave` moves rows (j*4 + wave)*8 .. +8 of the tile
+// (8 lanes x 16 B per 128-byte tile row); lane (rsub, p) fetches the chunk whose swizzled position
+// (see swz) is p, so the LDS image is the swizzled layout.  Wavefront `wave` moves rows (j*4 + wave)*8 .. +8 of the tile
 // as piece j.  The address is rsrc base + voff (per lane: first row of piece 0, swizzled chunk)
 // + a uniform offset (piece and K tile).  The resource covers exactly the matrix, so rows past
 // its last one (ragged edge tiles) are out of range for the hardware and load zeros; they only
@@ -277,8 +281,10 @@ __device__ __forceinline__ DmaOperand dma_operand(const bf16_t* base, int nrows,
     DmaOperand o;
     o.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(base), 0, (uint32_t)nrows * (uint32_t)ld * 2u,
                                                0x00020000);
+    // tile row of this lane in piece j: (j*4 + wave)*8 + rsub, so (row >> 1) & 7 = (wave & 1)*4 + (rsub >> 1)
     const int rsub = lane >> 3, p = lane & 7;
-    o.voff = (uint32_t)(row0 + wave * 8 + rsub) * (uint32_t)ld * 2u + (uint32_t)((p ^ rsub) << 4);
+    o.voff = (uint32_t)(row0 + wave * 8 + rsub) * (uint32_t)ld * 2u +
+             (uint32_t)((p ^ (((wave & 1) << 2) | (rsub >> 1))) << 4);
     o.piece_step = 32u * (uint32_t)ld * 2u;
     return o;
 }
@@ -451,8 +457,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
         constexpr int EST = gemm_epilogue_stride<NI>();   // bytes per staged row
         __syncthreads();                                   // every wavefront is done with the operand tiles
         unsigned char* ep = smem_raw + wave * (MI * 32) * EST;
+        constexpr int LPR = NI * 4, RPI = 64 / LPR;        // lanes per staged row, rows per store instruction
+        const int r_in = lane / LPR, c = (lane % LPR) * 8;
+        const int col = n0 + wn + c;
+        // one block row (32 tile rows) at a time, so the stores of a block row are under way while the next
+        // one is converted; the region is this wavefront's own, and a wavefront's LDS accesses stay in order
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+        for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -462,16 +473,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
                     pk.y = pack_bf16x2(acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]);
                     *reinterpret_cast<uint2*>(ep + (mi * 32 + lrow) * EST + (ni * 32 + g * 8 + khalf * 4) * 2) = pk;
                 }
-        __syncthreads();
-        constexpr int LPR = NI * 4, RPI = 64 / LPR;        // lanes per staged row, rows per store instruction
-        const int r_in = lane / LPR, c = (lane % LPR) * 8;
-        const int col = n0 + wn + c;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-        for (int i = 0; i < MI * 32 / RPI; ++i) {
-            const int r = i * RPI + r_in;
-            const int row = m0 + wm + r;
-            const u32x4 v = *reinterpret_cast<const u32x4*>(ep + r * EST + c * 2);
-            if (row < a.T && col < a.d_out) *reinterpret_cast<u32x4*>(a.out + (size_t)row * a.d_out + col) = v;
+            for (int i = 0; i < 32 / RPI; ++i) {
+                const int r = mi * 32 + i * RPI + r_in;
+                const int row = m0 + wm + r;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(ep + r * EST + c * 2);
+                if (row < a.T && col < a.d_out) *reinterpret_cast<u32x4*>(a.out + (size_t)row * a.d_out + col) = v;
+            }
         }
         return;
     }
