@@ -13,7 +13,7 @@
 // Tiling (gfx950): a workgroup of 4 wavefronts (2x2) owns a BM x BN output tile; each wavefront
 // owns (BM/2) x (BN/2) as MI x NI blocks of v_mfma_f32_32x32x16_bf16.  K advances in steps of
 // 64 through a double-buffered LDS tile; rows are 128 B and their 16-B chunks are XOR-swizzled
-// with the row index so that ds_read_b128 of 8 consecutive rows touches all banks once.
+// with the row index (see swz) so that a ds_read_b128 pass touches every bank once.
 // The MFMA is issued with W as the first operand, so a lane ends up with 4 consecutive output
 // columns of one token row and stores them as one 8-byte word.
 #pragma once
