@@ -7,6 +7,11 @@ every step calls meteora_linear_forward_packed; the same loop with per-call pack
 (meteora_linear_forward) is timed as well and reported beside it.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layer 0] [--no-cpu-baseline]
+
+--layer -1 runs every layer of the configuration one after the other per step (config 5: the seven
+projections of a Llama3-8B block, each a MeteoRA layer with its own gate and adapters, fed the same
+number of tokens); tokens/s is then T / (time of the whole set), and the roofline figures are those of
+the set's GEMM launches together.
 """
 import argparse
 import json
@@ -79,24 +84,33 @@ def main():
 
     torch.cuda.set_device(0)
     seed, layers = gen.config_layers(args.config)
-    shape = layers[args.layer]
-    ops = gen.make_layer(shape, seed, args.layer)
-    dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
-    dev = {n: torch.from_numpy(ops[n]).cuda().to(dt) for n in ("x", "W", "A", "B")}
-    Wg = torch.from_numpy(ops["W_gate"]).cuda()
-    bias = None if ops["bias"] is None else torch.from_numpy(ops["bias"]).cuda()
-    out = torch.empty((shape.T, shape.d_out), dtype=dt, device="cuda")
-    ws = torch.empty(m.workspace_bytes(shape.T, shape.d_in, shape.d_out, shape.N, shape.r, shape.k, dt),
-                     dtype=torch.uint8, device="cuda")
-
-    packed = m.pack_weights(Wg, dev["A"], dev["B"])   # once per set of adapters, outside the timed region
+    which = list(range(len(layers))) if args.layer < 0 else [args.layer]
+    dt_of = lambda sh: torch.bfloat16 if sh.dtype == "bf16" else torch.float32
+    calls = []   # one entry per layer: everything a call needs, resident on the GPU
+    for li in which:
+        sh = layers[li]
+        ops_l = gen.make_layer(sh, seed, li)
+        dt = dt_of(sh)
+        dev = {n: torch.from_numpy(ops_l[n]).cuda().to(dt) for n in ("x", "W", "A", "B")}
+        Wg = torch.from_numpy(ops_l["W_gate"]).cuda()
+        bias = None if ops_l["bias"] is None else torch.from_numpy(ops_l["bias"]).cuda()
+        out = torch.empty((sh.T, sh.d_out), dtype=dt, device="cuda")
+        ws = torch.empty(m.workspace_bytes(sh.T, sh.d_in, sh.d_out, sh.N, sh.r, sh.k, dt), dtype=torch.uint8,
+                         device="cuda")
+        packed = m.pack_weights(Wg, dev["A"], dev["B"])   # once per set of adapters, outside the timed region
+        calls.append((sh, dev, Wg, bias, out, ws, packed))
+        if li == which[0]:
+            ops = ops_l   # the CPU baseline samples the first layer
+    shape = calls[0][0]
 
     def step():
-        m.linear_forward(dev["x"], dev["W"], Wg, bias, dev["A"], dev["B"], shape.k, shape.scale, out=out, ws=ws,
-                         packed=packed)
+        for sh, dev, Wg, bias, out, ws, packed in calls:
+            m.linear_forward(dev["x"], dev["W"], Wg, bias, dev["A"], dev["B"], sh.k, sh.scale, out=out, ws=ws,
+                             packed=packed)
 
     def step_repack():
-        m.linear_forward(dev["x"], dev["W"], Wg, bias, dev["A"], dev["B"], shape.k, shape.scale, out=out, ws=ws)
+        for sh, dev, Wg, bias, out, ws, packed in calls:
+            m.linear_forward(dev["x"], dev["W"], Wg, bias, dev["A"], dev["B"], sh.k, sh.scale, out=out, ws=ws)
 
     def timed(fn):
         for _ in range(args.warmup):
@@ -113,17 +127,23 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     tokens_per_s = shape.T * args.steps / elapsed
 
-    # per-stage durations from hipEvents recorded by the library on the launch stream
+    # per-stage durations from hipEvents recorded by the library on the launch stream (per step: summed over the
+    # layers of the set)
     m.stage_timing_enable(True)
-    n_prof = min(args.steps, 200)
+    n_prof = max(1, min(args.steps, 200 // len(calls)))
     for _ in range(n_prof):
         step()
     torch.cuda.synchronize()
-    stages, calls = m.stage_timing_read()
+    stages, _ = m.stage_timing_read()
     m.stage_timing_enable(False)
-    stage_us = {n: (ms / max(c, 1)) * 1e3 for n, (ms, c) in stages.items() if c > 0}
+    stage_us = {n: ms * 1e3 / n_prof for n, (ms, c) in stages.items() if c > 0}
 
-    alg = algorithmic(shape)
+    alg = {}
+    for sh, *_ in calls:
+        for key, d in algorithmic(sh).items():
+            acc = alg.setdefault(key, {"flops": 0.0, "bytes": 0.0})
+            acc["flops"] += d["flops"]
+            acc["bytes"] += d["bytes"]
     gemm_us = stage_us["gemm"]
     gemm_flops = alg["gemm"]["flops"] + (alg["expand"]["flops"] if "expand" not in stage_us else 0.0)
     achieved = gemm_flops / (gemm_us * 1e-6) / 1e12
@@ -142,13 +162,19 @@ def main():
             d["hbm_frac"] = round(alg[key]["bytes"] / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)
         per_stage[n] = d
 
+    if len(calls) == 1:
+        workload = (f"config {args.config} / {shape.name}: T={shape.T}, {shape.d_in}->{shape.d_out}, N={shape.N}, "
+                    f"r={shape.r}, top-{shape.k}, s={shape.scale}, {shape.routing} routing")
+    else:
+        workload = (f"config {args.config}, all {len(calls)} layers per step (" +
+                    ", ".join(f"{sh.name} {sh.d_in}->{sh.d_out}" for sh, *_ in calls) +
+                    f"): T={shape.T}, N={shape.N}, r={shape.r}, top-{shape.k}")
     res = {
         "metric": "MeteoRA-layer tokens/s at Llama3-8B shapes (28 LoRAs, top-2); % HBM/MFMA peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": shape.dtype, "data": "synthetic",
-        "config": {"workload": f"config {args.config} / {shape.name}: T={shape.T}, {shape.d_in}->{shape.d_out}, "
-                               f"N={shape.N}, r={shape.r}, top-{shape.k}, s={shape.scale}, {shape.routing} routing",
+        "config": {"workload": workload,
                    "inputs_resident_in_hbm": True,
                    "weights": "W_gate, A, B packed once before the timed region (meteora_pack_weights)"},
         "per_call_packing": {"ms_per_step": elapsed_repack * 1e3 / args.steps,
