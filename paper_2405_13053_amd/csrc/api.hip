@@ -378,6 +378,19 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
         StageScope sc(ST_GATE_LOGITS, st, tslot);
         METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, pk.wsplit, partials, st));
     }
+    if (route_small_applies(T, r, bf16)) {
+        // decode-sized batch: top-k, softmax and the shrink of the selected adapters in one launch, then the GEMM
+        {
+            StageScope sc(ST_SHRINK, st, tslot);
+            METEORA_HIP(launch_route_shrink_small(x, partials, gate_kslices(d_in, bf16), gate_bias, A, T, d_in, N, r,
+                                                  k, 1.0f, scale, idx, w, at<void>(ws, L.hdense), L.ext_stride, st));
+        }
+        StageScope sc(ST_GEMM, st, tslot);
+        METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, bf16, at<void>(ws, L.hdense), L.ext_stride, pk.btrans, N * r,
+                                out, 0, gemm_splitk_bytes(T, d_in, d_out, bf16) > 0 ? at<float>(ws, L.splitk) : nullptr,
+                                st));
+        return METEORA_OK;
+    }
     {
         StageScope sc(ST_GATE_TOPK, st, tslot);
         METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, 1.0f, idx, w,

@@ -7,6 +7,7 @@
 //      top-k with a wavefront-wide arg-max (ties -> lowest adapter index), softmax over the k.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "topk_key.hpp"
 #include "prep.hpp"
 
 namespace meteora {
@@ -55,17 +56,6 @@ __global__ __launch_bounds__(256) void gate_logits_fma_kernel(const TX* __restri
 constexpr int kTopkTokensPerWave = 4;
 constexpr int kTopkWaves = kBucketChunkTokens / kTopkTokensPerWave;
 static_assert(kTopkWaves * 64 <= 1024, "one workgroup per bucketing chunk");
-
-__device__ __forceinline__ uint64_t logit_key(float g, int index) {
-    uint32_t u = __float_as_uint(g);
-    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // monotonic map of finite floats to unsigned; -0 < +0 never ties with an index swap
-    return ((uint64_t)u << 32) | (uint64_t)(0xffffffffu - (uint32_t)index);
-}
-__device__ __forceinline__ float key_logit(uint64_t key) {
-    uint32_t u = (uint32_t)(key >> 32);
-    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
-    return __uint_as_float(u);
-}
 
 template <int NP>
 __global__ __launch_bounds__(kTopkWaves * 64) void gate_topk_kernel(

@@ -28,6 +28,16 @@ hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, in
                             float inv_temperature, int32_t* topk_idx, float* topk_w, float* logits,
                             int32_t* chunk_counts, hipStream_t stream);
 
+// ---- small batches (T <= 64, bf16, r in {8, 16, 32}): top-k + softmax and the shrink of the selected
+// adapters in one launch, one workgroup per token; consumes launch_gate_logits' partials and writes
+// topk_idx, topk_w and every column of the token's row of hdense.  Replaces launch_gate_topk,
+// launch_bucket and launch_shrink for the whole-layer call.
+bool route_small_applies(int T, int r, bool bf16);
+hipError_t launch_route_shrink_small(const void* x, const float* partials, int KS, const float* bias, const void* A,
+                                     int T, int d_in, int N, int r, int k, float inv_temperature, float scale,
+                                     int32_t* topk_idx, float* topk_w, void* hdense, int ext_stride,
+                                     hipStream_t stream);
+
 // ---- bucketing (Sec. 3.3: per-adapter token sets as index lists) --------------------------
 constexpr int kBucketChunkTokens = 64;   // tokens (k pairs each) whose pairs one workgroup histograms and scatters
 inline int bucket_chunks(int T) { return (T + kBucketChunkTokens - 1) / kBucketChunkTokens; }

@@ -1,0 +1,154 @@
+// Small batches (decode: a few dozen tokens, fewer tokens than adapters is the paper's hard case,
+// Sec. 3.3): top-k + softmax (Eq. 3) and the LoRA shrink h = x * A_a of the selected adapters in ONE
+// launch, one workgroup per token, token-major.  With so few (token, slot) pairs the bucket lists buy
+// nothing: a pair's A_a (d_in x r, contiguous) is streamed once by the token's own workgroup, so the
+// top-k, scatter, shrink and finalize launches of the large-batch path (each on a ~2.5 us launch
+// floor) collapse into this one.  Consumes the same K-slice logit partials as gate_topk_kernel, adds
+// them in the same order and ranks with the same keys, so the routing is identical.
+#include "common.hpp"
+#include "kernels.hpp"
+#include "topk_key.hpp"
+
+namespace meteora {
+
+constexpr int kSmallThreads = 1024;   // 16 wavefronts per token: the shrink is latency-bound, so many short loops
+constexpr int kSmallWaves = kSmallThreads / 64;
+
+template <int R8>   // R8 = r / 8: 16-byte pieces per row of A_a
+__global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
+    const bf16_t* __restrict__ x, const float* __restrict__ partials, int KS, const float* __restrict__ bias,
+    const bf16_t* __restrict__ A, int T, int d_in, int N, int NP, int k, float inv_temperature, float scale,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, bf16_t* __restrict__ hdense, int ext_stride) {
+    constexpr int r = R8 * 8;
+    constexpr int ROWS = 8 / R8;   // rows of A_a per slot whose loads are in flight together
+    __shared__ int sel_idx[kMaxTopK];
+    __shared__ float sel_w[kMaxTopK];
+    __shared__ float red[kSmallWaves][kMaxTopK][r];
+    const int t = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    // this token's row of the dense expand operand starts as zeros
+    {
+        u32x4* row = reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride);
+        for (int i = threadIdx.x; i < ext_stride / 8; i += kSmallThreads) row[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+    if (wave == 0) {   // top-k and softmax: lane = adapter
+        float g = 0.f;
+        if (lane < N) {
+            for (int s0 = 0; s0 < KS; s0 += 16) {   // K-slices in order, 16 loads in flight
+                float v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = s0 + u < KS ? partials[((size_t)(s0 + u) * T + t) * NP + lane] : 0.f;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) g += v[u];
+            }
+            g += bias != nullptr ? bias[lane] : 0.f;
+            if (g == 0.f) g = 0.f;   // -0 -> +0 so equal logits have equal keys
+        }
+        uint64_t key = lane < N ? logit_key(g, lane) : 0ull;
+        float my_g = 0.f;
+        int my_i = 0;
+        for (int s = 0; s < k; ++s) {
+            uint64_t best = key;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const uint64_t o = __shfl_xor((unsigned long long)best, off);
+                best = o > best ? o : best;
+            }
+            const int win = (int)(0xffffffffu - (uint32_t)best);
+            if (lane == win) key = 0ull;
+            if (lane == s) { my_g = key_logit(best); my_i = win; }
+        }
+        const float gmax = __shfl(my_g, 0);
+        const float e = lane < k ? expf((my_g - gmax) * inv_temperature) : 0.f;
+        float sum = e;
+#pragma unroll
+        for (int off = 1; off < kMaxTopK; off <<= 1) sum += __shfl_xor(sum, off);
+        if (lane < k) {
+            const float w = e / sum;
+            sel_idx[lane] = my_i;
+            sel_w[lane] = w;
+            topk_idx[(size_t)t * k + lane] = my_i;
+            topk_w[(size_t)t * k + lane] = w;
+        }
+    }
+    __syncthreads();
+
+    // shrink: thread `tid` takes rows tid, tid + 1024, ... of A_a (r bf16 = R8 16-byte pieces each); two slots
+    // at a time so that both adapters' loads are in flight together
+    const bf16_t* xt = x + (size_t)t * d_in;
+    for (int slot0 = 0; slot0 < k; slot0 += 2) {
+        const bool two = slot0 + 1 < k;   // uniform
+        const bf16_t* Aa0 = A + (size_t)sel_idx[slot0] * d_in * r;
+        const bf16_t* Aa1 = A + (size_t)sel_idx[two ? slot0 + 1 : slot0] * d_in * r;
+        float acc0[r], acc1[r];
+#pragma unroll
+        for (int q = 0; q < r; ++q) { acc0[q] = 0.f; acc1[q] = 0.f; }
+        for (int i0 = threadIdx.x; i0 < d_in; i0 += kSmallThreads * ROWS) {
+            u32x4 v0[ROWS][R8], v1[ROWS][R8];
+            float xv[ROWS];
+#pragma unroll
+            for (int u = 0; u < ROWS; ++u) {
+                const int i = i0 + kSmallThreads * u;
+                const int ic = i < d_in ? i : d_in - 1;
+                xv[u] = i < d_in ? to_float(xt[ic]) : 0.f;   // rows past the end contribute x = 0
+#pragma unroll
+                for (int c = 0; c < R8; ++c) {
+                    v0[u][c] = reinterpret_cast<const u32x4*>(Aa0 + (size_t)ic * r)[c];
+                    v1[u][c] = reinterpret_cast<const u32x4*>(Aa1 + (size_t)ic * r)[c];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < ROWS; ++u)
+#pragma unroll
+                for (int c = 0; c < R8; ++c)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int q = c * 8 + 2 * e;
+                        acc0[q] = fmaf(xv[u], bf16_bits_to_float(v0[u][c][e] & 0xffffu), acc0[q]);
+                        acc0[q + 1] = fmaf(xv[u], bf16_bits_to_float(v0[u][c][e] >> 16), acc0[q + 1]);
+                        acc1[q] = fmaf(xv[u], bf16_bits_to_float(v1[u][c][e] & 0xffffu), acc1[q]);
+                        acc1[q + 1] = fmaf(xv[u], bf16_bits_to_float(v1[u][c][e] >> 16), acc1[q + 1]);
+                    }
+        }
+        // wavefront sums (fixed butterfly); the wavefronts are added through LDS below
+#pragma unroll
+        for (int q = 0; q < r; ++q) {
+            float s0 = acc0[q], s1 = acc1[q];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) { s0 += __shfl_xor(s0, off); s1 += __shfl_xor(s1, off); }
+            if (lane == 0) {
+                red[wave][slot0][q] = s0;
+                if (two) red[wave][slot0 + 1][q] = s1;
+            }
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < k * r; e += kSmallThreads) {
+        const int slot = e / r, q = e - slot * r;
+        float h = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kSmallWaves; ++wv) h += red[wv][slot][q];   // fixed order
+        hdense[(size_t)t * ext_stride + sel_idx[slot] * r + q] = from_float<bf16_t>(scale * sel_w[slot] * h);
+    }
+}
+
+bool route_small_applies(int T, int r, bool bf16) { return bf16 && T <= 64 && (r == 8 || r == 16 || r == 32); }
+
+hipError_t launch_route_shrink_small(const void* x, const float* partials, int KS, const float* bias, const void* A,
+                                     int T, int d_in, int N, int r, int k, float inv_temperature, float scale,
+                                     int32_t* topk_idx, float* topk_w, void* hdense, int ext_stride,
+                                     hipStream_t stream) {
+    const int NP = padded_adapters(N);
+    auto go = [&](auto kern) {
+        kern<<<T, kSmallThreads, 0, stream>>>((const bf16_t*)x, partials, KS, bias, (const bf16_t*)A, T, d_in, N, NP, k,
+                                    inv_temperature, scale, topk_idx, topk_w, (bf16_t*)hdense, ext_stride);
+        return hipGetLastError();
+    };
+    if (r == 8) return go(route_shrink_small_kernel<1>);
+    if (r == 16) return go(route_shrink_small_kernel<2>);
+    if (r == 32) return go(route_shrink_small_kernel<4>);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace meteora

@@ -225,6 +225,29 @@ def test_packed_weights_serve_many_batches():
         assert torch.equal(y, y_ref)
 
 
+SMALL_BATCH_SHAPES = [
+    LS(1, 512, 256, 28, 8, 2, 2.0, "bf16", "uniform", "T=1"),
+    LS(7, 264, 136, 5, 16, 1, 1.0, "bf16", "zipf", "T=7-r16-top1-ragged"),
+    LS(64, 1024, 520, 64, 32, 8, 0.5, "bf16", "uniform", "T=64-N64-r32-k8"),
+    LS(33, 5120, 264, 28, 8, 2, 2.0, "bf16", "zipf", "T=33-decode-shape"),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL_BATCH_SHAPES, ids=lambda s: s.name)
+def test_small_batch_path_matches_oracle_and_gate_entry_point(shape):
+    """T <= 64: top-k and shrink run token-major in one launch; same routing as meteora_gate_topk, bit for bit."""
+    out = _check_layer(shape, seed=45)
+    ops, dev = util.make_case(shape, seed=45)
+    _, idx, w = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], dev["bias"], dev["A"], dev["B"], shape.k,
+                                 shape.scale, return_routing=True)
+    idx_g, w_g, _ = m.gate_topk(dev["x"], dev["W_gate"], dev["bias"], shape.k)
+    assert torch.equal(idx, idx_g) and torch.equal(w, w_g)
+    # and the LoRA term alone through the bucketed path gives the same layer output to bf16 accuracy
+    base = m.base_gemm(dev["x"], dev["W"])
+    full = m.lora_forward(dev["x"], dev["A"], dev["B"], idx, w, shape.scale, out=base.clone(), accumulate=True)
+    assert util.rel_max_err(full, out.to(torch.float64).cpu().numpy()) <= 2 * util.tol(shape)
+
+
 def test_linear_forward_single_adapter_is_merged_gemm():
     """N=1,k=1: the layer is x(W + s*A*B) (Eq. 1)."""
     shape = LS(100, 256, 264, 1, 8, 1, 2.0, "f32")
