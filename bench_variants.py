@@ -12,7 +12,7 @@ hipBLASLt underneath) as measured context, on the same seeded synthetic workload
 Each variant's output is also compared with this library's (max |diff| / max |y|): they round
 intermediates to bf16, so they agree to bf16 accuracy, not bit for bit.  One JSON line is printed.
 
-    python bench_variants.py [--config 2] [--layer 0] [--steps 20] [--warmup 5]
+    python bench_variants.py [--config 2] [--layer 0] [--steps 20] [--warmup 10]
 """
 import argparse
 import json

@@ -145,6 +145,9 @@ meteora_status meteora_linear_forward(const void* x, const void* W, const float*
  *   meteora_linear_forward_packed   meteora_linear_forward that reads the blob instead
  *                          of repacking into the workspace.  `packed` = NULL behaves as
  *                          meteora_linear_forward.  The results are bit-identical.
+ *                          W_gate, A and B are still required and must be the tensors the
+ *                          blob was packed from: some paths (fp32, decode-sized batches)
+ *                          read them directly.
  * Errors: METEORA_ERR_WORKSPACE if packed_bytes is smaller than meteora_packed_bytes.
  */
 size_t meteora_packed_bytes(int d_in, int d_out, int N, int r, meteora_dtype dt);
