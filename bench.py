@@ -153,9 +153,18 @@ def main():
                 "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get((args.config, args.layer)),
                 "algorithmic_bytes": alg["gemm"]["bytes"], "us": gemm_us}
     per_stage = {}
+    # mid-sized batches: one launch computes the gate logits and the shrink (no bucket / shrink stage is timed);
+    # its algorithmic work is the gate's plus the selected adapters' shrink, with x read once
+    dense_route = "shrink" not in stage_us and "gate_logits" in stage_us
+    if dense_route:
+        alg["gate+shrink"] = {"flops": alg["gate"]["flops"] + alg["shrink"]["flops"],
+                              "bytes": alg["gate"]["bytes"] + alg["shrink"]["bytes"] -
+                                       sum(sh.T * sh.d_in * (2 if sh.dtype == "bf16" else 4) for sh, *_ in calls)}
     for n, us in stage_us.items():
-        key = {"gate_logits": "gate", "gate_topk": None, "bucket": None}.get(n, n)
+        key = {"gate_logits": "gate+shrink" if dense_route else "gate", "gate_topk": None, "bucket": None}.get(n, n)
         d = {"us": round(us, 2)}
+        if n == "gate_logits" and dense_route:
+            d["covers"] = "gate logits and LoRA shrink in one launch; gate_topk = top-k, softmax and selection"
         if key and key in alg:
             d["GB/s"] = round(alg[key]["bytes"] / (us * 1e-6) / 1e9, 1)
             d["TFLOP/s"] = round(alg[key]["flops"] / (us * 1e-6) / 1e12, 2)

@@ -13,7 +13,7 @@ namespace {
 
 struct WsLayout {
     size_t wsplit, partials, chunk_counts, counts, offsets, bucket_tok, bucket_slot, topk_idx, topk_w, h32,
-        hdense, apack, hpart, splitk, btrans, total;
+        hdense, apack, hpart, splitk, btrans, wcat, dpart, total;
     int ext_stride;   // columns of hdense: N*r rounded up to 64 (one K tile of the GEMM)
 };
 
@@ -48,12 +48,15 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     L.hpart = take(shrink_hpart_bytes(T, d_in, r, k, bf16));
     L.splitk = take(gemm_splitk_bytes(T, d_in, d_out, bf16));
     L.btrans = take(prep_btrans_bytes(d_out, N, r, bf16));
+    const bool dense = route_dense_applies(T, d_in, N, r, bf16);
+    L.wcat = take(dense ? prep_wcat_bytes(d_in, N, r, bf16) : 0);
+    L.dpart = take(route_dense_part_bytes(T, d_in, N, r, bf16));
     L.total = off;
     return L;
 }
 
 // Packed weights (meteora_pack_weights): the three operand layouts, each 256-byte aligned.
-struct PackLayout { size_t wsplit, apack, btrans, total; };
+struct PackLayout { size_t wsplit, apack, btrans, wcat, total; };
 
 PackLayout pack_layout(int d_in, int d_out, int N, int r, bool bf16) {
     PackLayout P{};
@@ -62,12 +65,13 @@ PackLayout pack_layout(int d_in, int d_out, int N, int r, bool bf16) {
     P.wsplit = take(gate_wsplit_bytes(d_in, N, bf16));
     P.apack = take(shrink_apack_bytes(d_in, N, r, bf16));
     P.btrans = take(prep_btrans_bytes(d_out, N, r, bf16));
+    P.wcat = take(route_dense_possible(d_in, N, r, bf16) ? prep_wcat_bytes(d_in, N, r, bf16) : 0);
     P.total = off;
     return P;
 }
 
 // Where the kernels find the packed operands: in the caller's blob, or in the workspace after a prep launch.
-struct PackedPtrs { void* wsplit; void* apack; void* btrans; };
+struct PackedPtrs { void* wsplit; void* apack; void* btrans; void* wcat; };
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
@@ -194,7 +198,8 @@ meteora_status meteora_gate_topk(const void* x, const float* W_gate, const float
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* partials = at<float>(ws, L.partials);
     if (gate_wsplit_bytes(d_in, N, bf16) > 0)
-        METEORA_HIP(launch_prep(W_gate, at<void>(ws, L.wsplit), nullptr, nullptr, nullptr, nullptr, d_in, 8, N, 1, st));
+        METEORA_HIP(launch_prep(W_gate, at<void>(ws, L.wsplit), nullptr, nullptr, nullptr, nullptr, nullptr, d_in, 8, N,
+                                1, st));
     METEORA_HIP(launch_gate_logits(x, W_gate, T, d_in, N, bf16, at<void>(ws, L.wsplit), partials, st));
     METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, inv_temperature,
                                  topk_idx, topk_w, logits, nullptr, st));
@@ -290,10 +295,10 @@ meteora_status meteora_lora_forward(const void* x, const void* A, const void* B,
     {
         const bool pa = shrink_apack_bytes(d_in, N, r, bf16) > 0, pb = prep_btrans_bytes(d_out, N, r, bf16) > 0;
         METEORA_HIP(launch_prep(nullptr, nullptr, pa ? A : nullptr, pa ? at<void>(ws, L.apack) : nullptr,
-                                pb ? B : nullptr, pb ? at<void>(ws, L.btrans) : nullptr, d_in, d_out, N, r,
+                                pb ? B : nullptr, pb ? at<void>(ws, L.btrans) : nullptr, nullptr, d_in, d_out, N, r,
                                 static_cast<hipStream_t>(stream)));
     }
-    const PackedPtrs pk{nullptr, at<void>(ws, L.apack), at<void>(ws, L.btrans)};
+    const PackedPtrs pk{nullptr, at<void>(ws, L.apack), at<void>(ws, L.btrans), nullptr};
     return run_lora(x, nullptr, A, B, topk_idx, topk_w, T, d_in, d_out, N, r, k, scale, bf16, out, accumulate, ws, L,
                     pk, static_cast<hipStream_t>(stream), timing_begin_call(), false);
 }
@@ -330,11 +335,11 @@ meteora_status meteora_pack_weights(const float* W_gate, const void* A, const vo
     if (P.total == 0) return METEORA_OK;   // this dtype reads the tensors as they are
     if (!packed || !aligned256(packed) || packed_bytes < P.total) return METEORA_ERR_WORKSPACE;
     const bool pw = gate_wsplit_bytes(d_in, N, bf16) > 0, pa = shrink_apack_bytes(d_in, N, r, bf16) > 0;
-    const bool pb = prep_btrans_bytes(d_out, N, r, bf16) > 0;
-    METEORA_HIP(launch_prep(pw ? W_gate : nullptr, pw ? at<void>(packed, P.wsplit) : nullptr, pa ? A : nullptr,
+    const bool pb = prep_btrans_bytes(d_out, N, r, bf16) > 0, pc = route_dense_possible(d_in, N, r, bf16);
+    METEORA_HIP(launch_prep(W_gate, pw ? at<void>(packed, P.wsplit) : nullptr, A,
                             pa ? at<void>(packed, P.apack) : nullptr, pb ? B : nullptr,
-                            pb ? at<void>(packed, P.btrans) : nullptr, d_in, d_out, N, r,
-                            static_cast<hipStream_t>(stream)));
+                            pb ? at<void>(packed, P.btrans) : nullptr, pc ? at<void>(packed, P.wcat) : nullptr, d_in,
+                            d_out, N, r, static_cast<hipStream_t>(stream)));
     return METEORA_OK;
 }
 
@@ -362,17 +367,37 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
     float* w = topk_w_out ? topk_w_out : at<float>(ws, L.topk_w);
     float* partials = at<float>(ws, L.partials);
     const int tslot = timing_begin_call();
-    PackedPtrs pk{at<void>(ws, L.wsplit), at<void>(ws, L.apack), at<void>(ws, L.btrans)};
+    // mid-sized batch: gate logits and the shrink of every adapter in one MFMA launch, selection afterwards
+    const bool dense = route_dense_applies(T, d_in, N, r, bf16);
+    PackedPtrs pk{at<void>(ws, L.wsplit), at<void>(ws, L.apack), at<void>(ws, L.btrans), at<void>(ws, L.wcat)};
     if (use_packed) {
         void* blob = const_cast<void*>(packed);   // read only from here on
-        pk = PackedPtrs{at<void>(blob, P.wsplit), at<void>(blob, P.apack), at<void>(blob, P.btrans)};
+        pk = PackedPtrs{at<void>(blob, P.wsplit), at<void>(blob, P.apack), at<void>(blob, P.btrans),
+                        at<void>(blob, P.wcat)};
     } else {
+        // only the operands this batch size reads are packed
         StageScope sc(ST_PREP, st, tslot);
-        const bool pw = gate_wsplit_bytes(d_in, N, bf16) > 0, pa = shrink_apack_bytes(d_in, N, r, bf16) > 0;
+        const bool pw = !dense && gate_wsplit_bytes(d_in, N, bf16) > 0;
+        const bool pa = !dense && shrink_apack_bytes(d_in, N, r, bf16) > 0;
         const bool pb = prep_btrans_bytes(d_out, N, r, bf16) > 0;
-        METEORA_HIP(launch_prep(pw ? W_gate : nullptr, pw ? pk.wsplit : nullptr, pa ? A : nullptr,
-                                pa ? pk.apack : nullptr, pb ? B : nullptr, pb ? pk.btrans : nullptr, d_in, d_out,
-                                N, r, st));
+        METEORA_HIP(launch_prep(W_gate, pw ? pk.wsplit : nullptr, A, pa ? pk.apack : nullptr, pb ? B : nullptr,
+                                pb ? pk.btrans : nullptr, dense ? pk.wcat : nullptr, d_in, d_out, N, r, st));
+    }
+    if (dense) {
+        float* dpart = at<float>(ws, L.dpart);
+        {
+            StageScope sc(ST_GATE_LOGITS, st, tslot);
+            METEORA_HIP(launch_route_dense_products(x, pk.wcat, T, d_in, N, r, dpart, st));
+        }
+        {
+            StageScope sc(ST_GATE_TOPK, st, tslot);
+            METEORA_HIP(launch_route_dense_select(dpart, gate_bias, T, d_in, N, r, k, 1.0f, scale, idx, w,
+                                                  at<void>(ws, L.hdense), L.ext_stride, st));
+        }
+        StageScope sc(ST_GEMM, st, tslot);
+        METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, bf16, at<void>(ws, L.hdense), L.ext_stride, pk.btrans, N * r,
+                                out, 0, nullptr, st));
+        return METEORA_OK;
     }
     {
         StageScope sc(ST_GATE_LOGITS, st, tslot);

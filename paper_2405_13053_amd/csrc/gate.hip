@@ -43,12 +43,8 @@ __global__ __launch_bounds__(256) void gate_logits_fma_kernel(const TX* __restri
 // Stage 2: wavefront-level top-k.
 //
 // A token's NP (32 or 64) logit columns sit in NP adjacent lanes, so a wavefront ranks 64/NP tokens
-// at a time.  A logit and its adapter index are packed into one 64-bit key, (order-preserving bits
-// of the fp32 value) << 32 | (0xffffffff - index), so the wavefront-wide maximum of the keys is the
-// largest logit with the LOWEST index among equal logits: exactly the tie-break of the layer.  Lanes
-// that are padding or already selected carry key 0 and can never win.  Selecting k adapters is k
-// butterfly maxima (log2(NP) shuffles each); the groups a wavefront owns are interleaved so their
-// shuffle latencies overlap.
+// at a time (wave_topk_softmax); the groups a wavefront owns are interleaved so their shuffle
+// latencies overlap.
 //
 // A workgroup of 16 wavefronts owns one bucketing chunk of 64 tokens (4 per wavefront) and also
 // leaves the chunk's adapter histogram for the scatter pass.
@@ -98,40 +94,14 @@ __global__ __launch_bounds__(kTopkWaves * 64) void gate_topk_kernel(
             if (logits && tok[i] < T) logits[(size_t)tok[i] * N + col] = g[i];
         }
     }
-    uint64_t key[G];
-    float sel_g[G];   // lane col = s < k of each token keeps its s-th selected logit and index
-    int sel_i[G];
-#pragma unroll
-    for (int i = 0; i < G; ++i) { key[i] = col < N ? logit_key(g[i], col) : 0ull; sel_g[i] = 0.f; sel_i[i] = 0; }
-    for (int s = 0; s < k; ++s) {
-        uint64_t best[G];
-#pragma unroll
-        for (int i = 0; i < G; ++i) best[i] = key[i];
-#pragma unroll
-        for (int off = NP / 2; off >= 1; off >>= 1) {
-#pragma unroll
-            for (int i = 0; i < G; ++i) {
-                const uint64_t o = __shfl_xor((unsigned long long)best[i], off);
-                best[i] = o > best[i] ? o : best[i];
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < G; ++i) {
-            const int win = (int)(0xffffffffu - (uint32_t)best[i]);
-            if (col == win) key[i] = 0ull;
-            if (col == s) { sel_g[i] = key_logit(best[i]); sel_i[i] = win; }
-        }
-    }
+    int sel_i[G];     // lane col = s < k of each token keeps its s-th selected adapter and weight
+    float sel_w[G];
+    wave_topk_softmax<NP, G>(g, lane, N, k, inv_temperature, sel_i, sel_w);
 #pragma unroll
     for (int i = 0; i < G; ++i) {
-        const float gmax = __shfl(sel_g[i], lane & ~(NP - 1));
-        const float e = (col < k) ? expf((sel_g[i] - gmax) * inv_temperature) : 0.f;
-        float sum = e;
-#pragma unroll
-        for (int off = 1; off < kMaxTopK; off <<= 1) sum += __shfl_xor(sum, off);
         if (col < k && tok[i] < T) {
             topk_idx[(size_t)tok[i] * k + col] = sel_i[i];
-            topk_w[(size_t)tok[i] * k + col] = e / sum;
+            topk_w[(size_t)tok[i] * k + col] = sel_w[i];
             atomicAdd(&hist[sel_i[i]], 1);
         }
     }

@@ -30,11 +30,16 @@ constexpr int kGemmChunks = 8;       // 16-byte chunks per LDS row
 // rows padded by 16 bytes; the dynamic LDS size is the larger of the operand ring and this stage.
 template <int NI>
 __host__ __device__ constexpr int gemm_epilogue_stride() { return NI * 64 + 16; }
+// fp32 partial tiles (split K) are staged one block row (32 tile rows) per wavefront at a time
+template <int NI>
+__host__ __device__ constexpr int gemm_partial_stride() { return NI * 128 + 16; }
 template <int MI, int NI>
 __host__ __device__ constexpr int gemm_lds_bytes() {
     constexpr int ring = 2 * (MI * 64 + NI * 64) * kGemmBK * 2;
     constexpr int stage = 4 * (MI * 32) * gemm_epilogue_stride<NI>();
-    return ring > stage ? ring : stage;
+    constexpr int pstage = 4 * 32 * gemm_partial_stride<NI>();
+    constexpr int m = ring > stage ? ring : stage;
+    return m > pstage ? m : pstage;
 }
 
 struct GemmArgs {
@@ -300,6 +305,17 @@ __device__ __forceinline__ void dma_piece(bf16_t* lds_tile, const DmaOperand& o,
 // these groups alternate them with the MFMAs instead.  Masks: 0x008 MFMA, 0x100 LDS read, 0x020 VMEM read.
 #define METEORA_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
+// Tail of the last phase of a K tile: RM MFMAs with RV global->LDS loads spread evenly between them.
+template <int RM, int RV, int J>
+__device__ __forceinline__ void paced_tail() {
+    if constexpr (J < RM) {
+        METEORA_SGB(0x008, 1);
+        constexpr int nv = RV / RM + (J < RV % RM ? 1 : 0);
+        if constexpr (nv > 0) METEORA_SGB(0x020, nv);
+        paced_tail<RM, RV, J + 1>();
+    }
+}
+
 // Map a workgroup id to an output tile: ids are dealt round-robin to the 8 XCDs, so each XCD
 // gets a contiguous run of the tile order, and the order walks groups of 4 tile rows column by
 // column: the 32 tiles an XCD works on at a time share few rows of x and W in its L2.
@@ -381,18 +397,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
     };
 
     Frags<MI, NI> f0, f1;
-    if (nk > 0) {
+    if (nk > 1) {
+        // both slots are free: request the first two tiles together, wait for the older one only
+        request_tile(0, 0);
+        request_tile(1, 1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PX + PW) : "memory");
+        __syncthreads();
+        load_frags<MI, NI>(f0, smem, smem + BM * kGemmBK, wm, wn, lrow, khalf, 0);
+    } else if (nk > 0) {
         request_tile(0, 0);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (nk > 1) request_tile(1, 1);
         load_frags<MI, NI>(f0, smem, smem + BM * kGemmBK, wm, wn, lrow, khalf, 0);
     }
     // One K tile = 4 phases of (MI*NI MFMA + the fragment reads of the next k-step); sched_barrier keeps
     // each phase's reads from sinking into the next phase, where they would be waited on at once.
     // In the 256x256 kernel the reads are issued one per MFMA in the first half of the phase, so each
     // has at least half a phase of MFMAs to land under.
-    constexpr bool kPaced = (MI == 4 && NI == 4);
+    constexpr bool kPaced = (MI == 4 && NI == 4);   // measured: no gain from the hints on the smaller tiles
+    static_assert(!kPaced || MI * NI >= MI + NI, "a phase needs one MFMA per fragment read");
     auto phase = [&](Frags<MI, NI>& fnext, const Frags<MI, NI>& fcur, const bf16_t* xs, int ks) {
         load_frags<MI, NI>(fnext, xs, xs + BM * kGemmBK, wm, wn, lrow, khalf, ks);
         mma_frags<MI, NI>(acc, fcur);
@@ -430,8 +453,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
             if constexpr (kPaced) {
 #pragma unroll
                 for (int i = 0; i < NR; ++i) { METEORA_SGB(0x008, 1); METEORA_SGB(0x100, 1); METEORA_SGB(0x020, 1); }
-#pragma unroll
-                for (int i = NR; i < NPC; ++i) { METEORA_SGB(0x008, 1); METEORA_SGB(0x020, 1); }
+                // the remaining pieces spread evenly over the remaining MFMAs
+                constexpr int RM = MI * NI - NR, RV = NPC - NR;
+                if constexpr (RM > 0) {
+                    paced_tail<RM, RV, 0>();
+                } else if constexpr (RV > 0) {
+                    METEORA_SGB(0x020, RV);
+                }
             }
         } else {
             if (it + 1 < nk) load_frags<MI, NI>(f0, xn, xn + BM * kGemmBK, wm, wn, lrow, khalf, 0);
@@ -487,6 +515,41 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
         return;
     }
 
+    if (a.partial != nullptr) {
+        // fp32 split-K tile: same staging, one block row at a time, so the stores are 16-byte pieces of whole rows
+        constexpr int PST = gemm_partial_stride<NI>();
+        __syncthreads();
+        unsigned char* ep = smem_raw + wave * 32 * PST;
+        constexpr int PPR = NI * 8;                        // 16-byte pieces per staged row
+        float* dst = a.partial + (size_t)blockIdx.y * a.T * a.d_out;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 v = {acc[mi][ni][g * 4 + 0], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2],
+                                     acc[mi][ni][g * 4 + 3]};
+                    *reinterpret_cast<f32x4*>(ep + lrow * PST + (ni * 32 + g * 8 + khalf * 4) * 4) = v;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int i = 0; i < 32 * PPR / 64; ++i) {
+                const int p = i * 64 + lane;
+                const int r = p / PPR, c = (p % PPR) * 4;
+                const int row = m0 + wm + mi * 32 + r, col = n0 + wn + c;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(ep + r * PST + c * 4);
+                if (row < a.T && col < a.d_out) *reinterpret_cast<f32x4*>(dst + (size_t)row * a.d_out + col) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        return;
+    }
+
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const int row = m0 + wm + mi * 32 + lrow;
@@ -499,11 +562,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
                 if (col >= a.d_out) continue;
                 float v0 = acc[mi][ni][g * 4 + 0], v1 = acc[mi][ni][g * 4 + 1];
                 float v2 = acc[mi][ni][g * 4 + 2], v3 = acc[mi][ni][g * 4 + 3];
-                if (a.partial != nullptr) {
-                    const f32x4 v = {v0, v1, v2, v3};
-                    *reinterpret_cast<f32x4*>(a.partial + ((size_t)blockIdx.y * a.T + row) * a.d_out + col) = v;
-                    continue;
-                }
                 uint2* dst = reinterpret_cast<uint2*>(a.out + (size_t)row * a.d_out + col);
                 if (a.accumulate) {
                     const uint2 old = *dst;

@@ -12,9 +12,13 @@ namespace meteora {
 // stacked B -> its transpose Bt[d_out, N*r rounded up to 64] (zero-padded) for the GEMM's K-extension.
 // Any pair (W_gate, wsplit) / (A, apack) / (B, btrans) may be NULL to skip it; sizes are gate_wsplit_bytes,
 // shrink_apack_bytes and prep_btrans_bytes (0 = that operand is not packed for this dtype/rank: pass NULL).
+// wcat (optional, needs W_gate and A, d_in % 64 == 0): Wcat[prep_wcat_rows, d_in] bf16 for the dense routing path,
+// rows = hi | mid | lo terms of the gate columns (padded_adapters(N) rows each), then column q of A_a as row a*r+q.
 size_t prep_btrans_bytes(int d_out, int N, int r, bool bf16);
+int prep_wcat_rows(int N, int r);
+size_t prep_wcat_bytes(int d_in, int N, int r, bool bf16);
 hipError_t launch_prep(const float* W_gate, void* wsplit, const void* A, void* apack, const void* B, void* btrans,
-                       int d_in, int d_out, int N, int r, hipStream_t stream);
+                       void* wcat, int d_in, int d_out, int N, int r, hipStream_t stream);
 
 // ---- gate (Sec. 3.1: G(x), I(x), Eq. 3) ------------------------------------------------
 // Number of K-slices the logit kernel splits d_in into (partials[KS][T][NP]).
@@ -37,6 +41,26 @@ hipError_t launch_route_shrink_small(const void* x, const float* partials, int K
                                      int T, int d_in, int N, int r, int k, float inv_temperature, float scale,
                                      int32_t* topk_idx, float* topk_w, void* hdense, int ext_stride,
                                      hipStream_t stream);
+
+// ---- mid-sized batches (64 < T <= kRouteDenseMaxTokens, bf16, r % 8 == 0, d_in % 64 == 0): one MFMA launch
+// computes the split-bf16 gate logits and x * A_i of every adapter as fp32 K-split partials
+// part[splits][T][prep_wcat_rows], then one launch per 64 tokens adds the splits, ranks (Sec. 3.1, Eq. 3) and
+// writes topk_idx, topk_w and every column of the tokens' rows of hdense.  Replaces launch_gate_logits,
+// launch_gate_topk, launch_bucket and launch_shrink for the whole-layer call.
+constexpr int kRouteDenseMaxTokens = 8192;
+bool route_dense_possible(int d_in, int N, int r, bool bf16);            // whatever T: is Wcat worth packing
+bool route_dense_applies(int T, int d_in, int N, int r, bool bf16);
+size_t route_dense_part_bytes(int T, int d_in, int N, int r, bool bf16);  // 0 if the path does not apply
+hipError_t launch_route_dense_products(const void* x, const void* wcat, int T, int d_in, int N, int r, float* part,
+                                       hipStream_t stream);
+hipError_t launch_route_dense_select(const float* part, const float* bias, int T, int d_in, int N, int r, int k,
+                                     float inv_temperature, float scale, int32_t* topk_idx, float* topk_w,
+                                     void* hdense, int ext_stride, hipStream_t stream);
+// the GEMM behind launch_route_dense_products: partial[split][T][rows] = x * Wcat^T over the split's K range
+bool gemm_dense_splitk_ok(int T, int d_in, int rows);
+int gemm_dense_splits(int T, int d_in, int rows);
+hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int d_in, int rows, float* partial,
+                                    hipStream_t stream);
 
 // ---- bucketing (Sec. 3.3: per-adapter token sets as index lists) --------------------------
 constexpr int kBucketChunkTokens = 64;   // tokens (k pairs each) whose pairs one workgroup histograms and scatters

@@ -4,13 +4,27 @@
 //   - stacked LoRA A[N, d_in, r] (Sec. 3.3) -> fragments with the rank padded to 32 columns;
 //   - stacked LoRA B[N, r, d_out] viewed as [N*r, d_out] -> its transpose Bt[d_out, ext_stride]
 //     (columns >= N*r zero), the layout the GEMM's K-extension streams like W.
+//   - for the dense routing path, Wcat[3*NP + N*r, d_in]: the three gate terms and every column of every
+//     A_i as rows contiguous along d_in, the layout the GEMM kernel streams like W.
 // All run in ONE launch (disjoint workgroup ranges); a wavefront writes one fragment, a workgroup
-// one 64x64 tile of the transpose.
+// one 64x64 tile of a transpose.
 #include "common.hpp"
 #include "kernels.hpp"
 #include "prep.hpp"
 
 namespace meteora {
+
+// The three bf16 terms of an fp32 gate weight: hi + mid + lo == w exactly (8 + 8 + 8 significand bits).
+__device__ __forceinline__ void split3(float w, uint16_t& hi, uint16_t& mid, uint16_t& lo) {
+    const bf16_t h = static_cast<bf16_t>(w);
+    const float r1 = w - static_cast<float>(h);     // exact
+    const bf16_t m = static_cast<bf16_t>(r1);
+    const float r2 = r1 - static_cast<float>(m);    // exact, fits 8 bits
+    const bf16_t l = static_cast<bf16_t>(r2);
+    hi = __builtin_bit_cast(uint16_t, h);
+    mid = __builtin_bit_cast(uint16_t, m);
+    lo = __builtin_bit_cast(uint16_t, l);
+}
 
 // fragment (ks, wq, s, cb): blocks ((((ks*4+wq)*8+s)*3 + term)*NCB + cb); lane l holds
 // k = ks*512 + wq*128 + s*16 + (l>>5)*8 + j of column n = cb*32 + (l&31).
@@ -27,14 +41,7 @@ __device__ __forceinline__ void wsplit_fragment(const float* __restrict__ W_gate
     for (int j = 0; j < 8; ++j) {
         const int k = k0 + j;
         const float w = (k < d_in && n < N) ? W_gate[(size_t)k * N + n] : 0.f;
-        const bf16_t h = static_cast<bf16_t>(w);
-        const float r1 = w - static_cast<float>(h);     // exact
-        const bf16_t m = static_cast<bf16_t>(r1);
-        const float r2 = r1 - static_cast<float>(m);    // exact, fits 8 bits
-        const bf16_t l = static_cast<bf16_t>(r2);
-        hi.h[j] = __builtin_bit_cast(uint16_t, h);
-        mid.h[j] = __builtin_bit_cast(uint16_t, m);
-        lo.h[j] = __builtin_bit_cast(uint16_t, l);
+        split3(w, hi.h[j], mid.h[j], lo.h[j]);
     }
     const size_t base = ((size_t)((ks * 4 + wq) * 8 + s) * 3 * NCB + cb) * 64 + lane;
     wsp[base] = hi.v;
@@ -88,17 +95,62 @@ __device__ __forceinline__ void btrans_tile(const uint16_t* __restrict__ B, int 
     }
 }
 
+// tile (ti, tr) of Wcat[rows, d_in]: row R = term*NP + j (term 0..2 = hi, mid, lo of W_gate[:, j]; zero for
+// j >= N), then row 3*NP + a*r + q = A[a][:, q], then zero rows up to `rows`.  Sources are read along the
+// row index (contiguous in W_gate and, per adapter, in A), transposed through LDS, stored along d_in.
+__device__ __forceinline__ void wcat_tile(const float* __restrict__ W_gate, const uint16_t* __restrict__ A, int d_in,
+                                          int N, int NP, int r, int rows, int tile, int tid,
+                                          uint16_t* __restrict__ Wcat) {
+    constexpr int LD = 66;
+    __shared__ uint16_t t[64 * LD];   // t[i][row]
+    const int tiles_i = d_in / 64;
+    const int i0 = (tile % tiles_i) * 64, R0 = (tile / tiles_i) * 64;
+    for (int e = tid; e < 64 * 64; e += 256) {
+        const int rr = e & 63, ii = e >> 6;
+        const int R = R0 + rr, i = i0 + ii;
+        uint16_t v = 0;
+        if (R < 3 * NP) {
+            const int term = R / NP, j = R - term * NP;
+            if (j < N) {
+                uint16_t h, m, l;
+                split3(W_gate[(size_t)i * N + j], h, m, l);
+                v = term == 0 ? h : (term == 1 ? m : l);
+            }
+        } else if (R < 3 * NP + N * r) {
+            const int c = R - 3 * NP, a = c / r, q = c - a * r;
+            v = A[((size_t)a * d_in + i) * r + q];
+        }
+        t[ii * LD + rr] = v;
+    }
+    __syncthreads();
+    const int rr = tid >> 2, iq = (tid & 3) * 16;
+    if (R0 + rr < rows) {
+        union { uint16_t h[16]; u32x4 v[2]; } p;
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) p.h[jj] = t[(iq + jj) * LD + rr];
+        u32x4* dst = reinterpret_cast<u32x4*>(Wcat + (size_t)(R0 + rr) * d_in + i0 + iq);
+        dst[0] = p.v[0];
+        dst[1] = p.v[1];
+    }
+}
+
 __global__ __launch_bounds__(256) void prep_kernel(const float* __restrict__ W_gate, const bf16_t* __restrict__ A,
                                                    int d_in, int N, int r, int wblocks, int wfrags, int64_t afrags,
                                                    u32x4* __restrict__ wsp, u32x4* __restrict__ apk,
                                                    const uint16_t* __restrict__ B, uint16_t* __restrict__ Bt,
-                                                   int d_out, int ext_stride, int bblocks) {
+                                                   int d_out, int ext_stride, int bblocks,
+                                                   uint16_t* __restrict__ Wcat, int cat_rows, int cblocks) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if ((int)blockIdx.x < bblocks) {   // uniform per workgroup
         btrans_tile(B, d_out, N * r, ext_stride, blockIdx.x, threadIdx.x, Bt);
         return;
     }
-    const int blk = blockIdx.x - bblocks;
+    if ((int)blockIdx.x < bblocks + cblocks) {
+        wcat_tile(W_gate, reinterpret_cast<const uint16_t*>(A), d_in, N, padded_adapters(N), r, cat_rows,
+                  blockIdx.x - bblocks, threadIdx.x, Wcat);
+        return;
+    }
+    const int blk = blockIdx.x - bblocks - cblocks;
     if (blk < wblocks) {
         const int frag = blk * 4 + wave;
         if (frag < wfrags) wsplit_fragment(W_gate, d_in, N, padded_adapters(N) / 32, frag, lane, wsp);
@@ -113,18 +165,28 @@ size_t prep_btrans_bytes(int d_out, int N, int r, bool bf16) {
     return bf16 ? (size_t)d_out * align_up((size_t)N * r, 64) * sizeof(uint16_t) : 0;
 }
 
+int prep_wcat_rows(int N, int r) { return (int)align_up((size_t)3 * padded_adapters(N) + (size_t)N * r, 8); }
+
+size_t prep_wcat_bytes(int d_in, int N, int r, bool bf16) {
+    return (bf16 && d_in % 64 == 0) ? (size_t)prep_wcat_rows(N, r) * d_in * sizeof(uint16_t) : 0;
+}
+
 hipError_t launch_prep(const float* W_gate, void* wsplit, const void* A, void* apack, const void* B, void* btrans,
-                       int d_in, int d_out, int N, int r, hipStream_t stream) {
+                       void* wcat, int d_in, int d_out, int N, int r, hipStream_t stream) {
     const int wfrags = (W_gate && wsplit) ? wsplit_fragments(d_in, N) : 0;
     const int64_t afrags = (A && apack) ? apack_fragments(d_in, N, r) : 0;
     const int ext_stride = (int)align_up((size_t)N * r, 64);
     const int bblocks = (B && btrans) ? (ext_stride / 64) * ceil_div(d_out, 64) : 0;
     const int wblocks = ceil_div(wfrags, 4);
-    const int64_t blocks = (int64_t)bblocks + wblocks + ceil_div64(afrags, 4);
+    const int cat_rows = prep_wcat_rows(N, r);
+    if (wcat && (!W_gate || !A || d_in % 64 != 0)) return hipErrorInvalidValue;
+    const int cblocks = wcat ? ceil_div(cat_rows, 64) * (d_in / 64) : 0;
+    const int64_t blocks = (int64_t)bblocks + cblocks + wblocks + ceil_div64(afrags, 4);
     if (blocks == 0) return hipSuccess;
     prep_kernel<<<(unsigned)blocks, 256, 0, stream>>>(W_gate, (const bf16_t*)A, d_in, N, r, wblocks, wfrags, afrags,
                                                       (u32x4*)wsplit, (u32x4*)apack, (const uint16_t*)B,
-                                                      (uint16_t*)btrans, d_out, ext_stride, bblocks);
+                                                      (uint16_t*)btrans, d_out, ext_stride, bblocks, (uint16_t*)wcat,
+                                                      cat_rows, cblocks);
     return hipGetLastError();
 }
 

@@ -1,0 +1,152 @@
+// Mid-sized batches (a few hundred to a few thousand tokens): routing and LoRA shrink without bucket lists.
+//
+// At these sizes the gate logits, top-k, bucketing, grouped shrink and its finalize are five short launches
+// that each read little and sit on launch and fill/drain time.  Here one MFMA launch computes, for every
+// token, the split-bf16 gate logits (Sec. 3.1) AND x * A_i for EVERY adapter i (the shrink of Eq. 2 before
+// the selection): x[T, d_in] times Wcat[3*NP + N*r, d_in]^T, a 320-column GEMM at N = 28, r = 8, whose
+// extra flops (N/k times the selected adapters') are cheap next to a second gathered pass over x.
+// This file's kernel then, per token, adds the K-splits in a fixed order, picks the top-k (ties to the lowest
+// index), takes the softmax over the k selected (Eq. 3) and writes the token's row of the dense expand
+// operand: hdense[t, a*r + q] = bf16(scale * w * h) for the selected adapters a, zero elsewhere.
+// The values are those of the bucketed path up to fp32 summation order; the ranking routine is the same.
+#include "common.hpp"
+#include "kernels.hpp"
+#include "topk_key.hpp"
+
+namespace meteora {
+
+// 16 tokens per workgroup: the kernel is two dependent rounds of loads, so it wants every CU busy rather than
+// long workgroups (T = 4096 gives 256 workgroups)
+constexpr int kSelTokens = 16;
+constexpr int kSelTokensPerWave = 4;
+constexpr int kSelThreads = kSelTokens / kSelTokensPerWave * 64;
+
+constexpr int kSelNP = 32;   // gate columns per term in Wcat: the path takes N <= 32 only (more adapters exceed its row limit)
+
+__global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
+    const float* __restrict__ part, int S, int CR, const float* __restrict__ bias, int T, int N, int r, int k,
+    float inv_temperature, float scale, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    bf16_t* __restrict__ hdense, int ext_stride) {
+    constexpr int NP = kSelNP;
+    constexpr int TPP = 64 / NP;                     // tokens ranked per pass
+    constexpr int G = kSelTokensPerWave / TPP;       // passes (groups) per wavefront
+    __shared__ int s_idx[kSelTokens][kMaxTopK];
+    __shared__ float s_w[kSelTokens][kMaxTopK];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & (NP - 1), sub = lane / NP;
+    const int t0 = blockIdx.x * kSelTokens;
+
+    // ---- logits: splits in order, within a split (lo + mid) + hi; 4 splits' loads in flight ----
+    float g[G];
+    int lt[G];   // token index inside the workgroup
+#pragma unroll
+    for (int i = 0; i < G; ++i) { g[i] = 0.f; lt[i] = wave * kSelTokensPerWave + i * TPP + sub; }
+    if (col < N) {
+        for (int s0 = 0; s0 < S; s0 += 4) {
+            float v[4][3][G];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int term = 0; term < 3; ++term)
+#pragma unroll
+                    for (int i = 0; i < G; ++i) {
+                        const int t = min(t0 + lt[i], T - 1);
+                        v[u][term][i] = s0 + u < S ? part[((size_t)(s0 + u) * T + t) * CR + term * NP + col] : 0.f;
+                    }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < G; ++i) g[i] += (v[u][2][i] + v[u][1][i]) + v[u][0][i];
+        }
+        const float b = bias != nullptr ? bias[col] : 0.f;
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            g[i] += b;
+            if (g[i] == 0.f) g[i] = 0.f;   // -0 -> +0 so equal logits have equal keys
+        }
+    }
+    int sel_i[G];
+    float sel_w[G];
+    wave_topk_softmax<NP, G>(g, lane, N, k, inv_temperature, sel_i, sel_w);
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        if (col < k) {
+            s_idx[lt[i]][col] = sel_i[i];
+            s_w[lt[i]][col] = sel_w[i];
+            const int t = t0 + lt[i];
+            if (t < T) {
+                topk_idx[(size_t)t * k + col] = sel_i[i];
+                topk_w[(size_t)t * k + col] = sel_w[i];
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- rows of hdense: a thread owns 8 columns (one adapter's, r % 8 == 0) of one token ----
+    const int C8 = ext_stride / 8;
+    for (int e = threadIdx.x; e < kSelTokens * C8; e += kSelThreads) {
+        const int tl = e / C8, c0 = (e - tl * C8) * 8;
+        const int t = t0 + tl;
+        if (t >= T) continue;
+        const int a = c0 / r;
+        bool hit = false;
+        float sw = 0.f;
+        if (c0 < N * r)
+            for (int s = 0; s < k; ++s)
+                if (s_idx[tl][s] == a) { hit = true; sw = scale * s_w[tl][s]; }
+        u32x4 pk = {0u, 0u, 0u, 0u};
+        if (hit) {
+            f32x4 h0 = {0.f, 0.f, 0.f, 0.f}, h1 = {0.f, 0.f, 0.f, 0.f};
+            const float* src = part + (size_t)t * CR + 3 * NP + c0;
+            for (int s0 = 0; s0 < S; s0 += 8) {   // splits in order, 16 loads in flight
+                f32x4 v0[8], v1[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float* p = src + (size_t)min(s0 + u, S - 1) * T * CR;
+                    v0[u] = *reinterpret_cast<const f32x4*>(p);
+                    v1[u] = *reinterpret_cast<const f32x4*>(p + 4);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < S) { h0 += v0[u]; h1 += v1[u]; }
+            }
+            pk[0] = pack_bf16x2(sw * h0[0], sw * h0[1]); pk[1] = pack_bf16x2(sw * h0[2], sw * h0[3]);
+            pk[2] = pack_bf16x2(sw * h1[0], sw * h1[1]); pk[3] = pack_bf16x2(sw * h1[2], sw * h1[3]);
+        }
+        *reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride + c0) = pk;
+    }
+}
+
+// Shapes the dense path takes, whatever the batch size (decides whether Wcat is part of the packed weights).
+bool route_dense_possible(int d_in, int N, int r, bool bf16) {
+    return bf16 && r % 8 == 0 && d_in % 64 == 0 && padded_adapters(N) == kSelNP && prep_wcat_rows(N, r) <= 320;
+}
+
+bool route_dense_applies(int T, int d_in, int N, int r, bool bf16) {
+    return route_dense_possible(d_in, N, r, bf16) && T > 64 && T <= kRouteDenseMaxTokens &&
+           gemm_dense_splitk_ok(T, d_in, prep_wcat_rows(N, r));
+}
+
+size_t route_dense_part_bytes(int T, int d_in, int N, int r, bool bf16) {
+    if (!route_dense_applies(T, d_in, N, r, bf16)) return 0;
+    const int CR = prep_wcat_rows(N, r);
+    return (size_t)gemm_dense_splits(T, d_in, CR) * T * CR * sizeof(float);
+}
+
+hipError_t launch_route_dense_products(const void* x, const void* wcat, int T, int d_in, int N, int r, float* part,
+                                       hipStream_t stream) {
+    return launch_gemm_dense_splitk(x, wcat, T, d_in, prep_wcat_rows(N, r), part, stream);
+}
+
+hipError_t launch_route_dense_select(const float* part, const float* bias, int T, int d_in, int N, int r, int k,
+                                     float inv_temperature, float scale, int32_t* topk_idx, float* topk_w,
+                                     void* hdense, int ext_stride, hipStream_t stream) {
+    const int CR = prep_wcat_rows(N, r);
+    const int S = gemm_dense_splits(T, d_in, CR);
+    const int blocks = ceil_div(T, kSelTokens);
+    route_dense_select_kernel<<<blocks, kSelThreads, 0, stream>>>(part, S, CR, bias, T, N, r, k, inv_temperature, scale,
+                                                                  topk_idx, topk_w, (bf16_t*)hdense, ext_stride);
+    return hipGetLastError();
+}
+
+}  // namespace meteora

@@ -4,7 +4,7 @@
 // nothing: a pair's A_a (d_in x r, contiguous) is streamed once by the token's own workgroup, so the
 // top-k, scatter, shrink and finalize launches of the large-batch path (each on a ~2.5 us launch
 // floor) collapse into this one.  Consumes the same K-slice logit partials as gate_topk_kernel, adds
-// them in the same order and ranks with the same keys, so the routing is identical.
+// them in the same order and ranks with the same routine, so the routing is identical.
 #include "common.hpp"
 #include "kernels.hpp"
 #include "topk_key.hpp"
@@ -45,31 +45,15 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
             g += bias != nullptr ? bias[lane] : 0.f;
             if (g == 0.f) g = 0.f;   // -0 -> +0 so equal logits have equal keys
         }
-        uint64_t key = lane < N ? logit_key(g, lane) : 0ull;
-        float my_g = 0.f;
-        int my_i = 0;
-        for (int s = 0; s < k; ++s) {
-            uint64_t best = key;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const uint64_t o = __shfl_xor((unsigned long long)best, off);
-                best = o > best ? o : best;
-            }
-            const int win = (int)(0xffffffffu - (uint32_t)best);
-            if (lane == win) key = 0ull;
-            if (lane == s) { my_g = key_logit(best); my_i = win; }
-        }
-        const float gmax = __shfl(my_g, 0);
-        const float e = lane < k ? expf((my_g - gmax) * inv_temperature) : 0.f;
-        float sum = e;
-#pragma unroll
-        for (int off = 1; off < kMaxTopK; off <<= 1) sum += __shfl_xor(sum, off);
+        const float gg[1] = {g};
+        int my_i[1];
+        float my_w[1];
+        wave_topk_softmax<64, 1>(gg, lane, N, k, inv_temperature, my_i, my_w);
         if (lane < k) {
-            const float w = e / sum;
-            sel_idx[lane] = my_i;
-            sel_w[lane] = w;
-            topk_idx[(size_t)t * k + lane] = my_i;
-            topk_w[(size_t)t * k + lane] = w;
+            sel_idx[lane] = my_i[0];
+            sel_w[lane] = my_w[0];
+            topk_idx[(size_t)t * k + lane] = my_i[0];
+            topk_w[(size_t)t * k + lane] = my_w[0];
         }
     }
     __syncthreads();

@@ -248,6 +248,55 @@ def test_small_batch_path_matches_oracle_and_gate_entry_point(shape):
     assert util.rel_max_err(full, out.to(torch.float64).cpu().numpy()) <= 2 * util.tol(shape)
 
 
+# mid-sized batches (64 < T <= 8192, bf16, r % 8 == 0, d_in % 64 == 0, 96 + N*r <= 320): gate logits and the shrink
+# of every adapter in one MFMA launch, selection afterwards; 128x128 tiles up to 4096 tokens, 128x320 above
+DENSE_ROUTE_SHAPES = [
+    LS(65, 64, 72, 3, 8, 1, 2.0, "bf16", "uniform", "T=65-one-K-tile"),
+    LS(129, 320, 264, 9, 24, 4, 0.7, "bf16", "zipf", "T=129-r24-k4-bias"),
+    LS(1000, 1088, 520, 28, 8, 2, 2.0, "bf16", "zipf", "T=1000-ragged-K17"),
+    LS(700, 512, 256, 7, 32, 7, 1.0, "bf16", "uniform", "T=700-r32-k=N"),
+    LS(4097, 256, 136, 28, 8, 2, 2.0, "bf16", "uniform", "T=4097-wide-tiles"),
+    LS(5000, 832, 264, 14, 16, 3, 2.0, "bf16", "zipf", "T=5000-r16-wide-tiles"),
+]
+
+
+@pytest.mark.parametrize("shape", DENSE_ROUTE_SHAPES, ids=lambda s: s.name)
+def test_dense_route_path_matches_oracle_and_bucketed_path(shape):
+    """Same routing as meteora_gate_topk bit for bit; the layer equals base GEMM + bucketed LoRA to bf16 accuracy."""
+    rows = "all" if shape.T <= 1000 else "sample"
+    out = _check_layer(shape, seed=46, rows=rows)
+    ops, dev = util.make_case(shape, seed=46)
+    _, idx, w = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], dev["bias"], dev["A"], dev["B"], shape.k,
+                                 shape.scale, return_routing=True)
+    idx_g, w_g, _ = m.gate_topk(dev["x"], dev["W_gate"], dev["bias"], shape.k)
+    assert torch.equal(idx, idx_g)
+    assert float((w - w_g).abs().max()) <= 1e-5     # the two paths add the logit terms in different orders
+    base = m.base_gemm(dev["x"], dev["W"])
+    full = m.lora_forward(dev["x"], dev["A"], dev["B"], idx, w, shape.scale, out=base.clone(), accumulate=True)
+    assert util.rel_max_err(full, out.to(torch.float64).cpu().numpy()) <= 2 * util.tol(shape)
+
+
+def test_dense_route_exact_ties_and_zero_gate():
+    """Duplicated gate columns tie exactly: the lower index wins on this path too; a zero gate picks 0..k-1."""
+    shape = LS(300, 512, 264, 12, 8, 3, 2.0, "bf16")
+    ops, dev = util.make_case(shape, seed=47, condition=False)
+    Wg = ops["W_gate"].copy()
+    Wg[:, 5] = Wg[:, 2]
+    Wg[:, 9] = Wg[:, 2]
+    for gate in (Wg, np.zeros_like(Wg)):
+        g = torch.from_numpy(gate).cuda()
+        _, idx, w = m.linear_forward(dev["x"], dev["W"], g, None, dev["A"], dev["B"], 3, 2.0, return_routing=True)
+        idx = _np(idx)
+        if not gate.any():
+            assert np.array_equal(idx, np.tile(np.arange(3, dtype=np.int32), (300, 1)))
+            np.testing.assert_allclose(_np(w), 1.0 / 3, rtol=0, atol=1e-7)
+        else:
+            has2 = (idx == 2).any(axis=1)
+            # whenever one of the tied columns is chosen, the lowest of them (2) is among the choices
+            assert np.all(has2 | ~((idx == 5) | (idx == 9)).any(axis=1))
+            assert np.all(~(idx == 9).any(axis=1) | (idx == 5).any(axis=1))
+
+
 def test_linear_forward_single_adapter_is_merged_gemm():
     """N=1,k=1: the layer is x(W + s*A*B) (Eq. 1)."""
     shape = LS(100, 256, 264, 1, 8, 1, 2.0, "f32")
