@@ -131,10 +131,20 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
         const size_t n8 = (size_t)a.T * a.d_out / 8;
         gemm_splitk_reduce_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, stream>>>(a.partial, nsplit, a.T, a.d_out,
                                                                                    a.out, a.accumulate);
-    } else if (dma_ok)
+    } else if (dma_ok && MI == 4 && NI == 4) {
+        static bool w3_attr_set = false;
+        if (!w3_attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmW3LdsBytes);
+            if (e != hipSuccess) return e;
+            w3_attr_set = true;
+        }
+        gemm_mfma_w3_kernel<<<a.tiles_m * a.tiles_n, 256, kGemmW3LdsBytes, stream>>>(a);
+    } else if (dma_ok) {
         gemm_mfma_dma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
-    else
+    } else {
         gemm_mfma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
+    }
     return hipGetLastError();
 }
 

@@ -332,6 +332,113 @@ __device__ __forceinline__ void tile_of_workgroup(int wg, int tiles_m, int tiles
     tile_n = in_group / gm;
 }
 
+// Epilogue shared by the pipelined kernels: store a workgroup's accumulators.
+template <int MI, int NI>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[MI][NI], unsigned char* smem_raw, int m0,
+                                              int n0, int wm, int wn, int wave, int lane) {
+    const int lrow = lane & 31, khalf = lane >> 5;
+    // Epilogue.  A lane holds 4 consecutive columns per block row, so direct stores are 8-byte pieces
+    // of 32 different rows per instruction; when the output is simply written (no split-K partials,
+    // no accumulate) the bf16 tile is staged in this wavefront's own LDS region and stored as
+    // 16-byte pieces that cover whole 128-byte lines.
+    if (a.partial == nullptr && !a.accumulate) {
+        constexpr int EST = gemm_epilogue_stride<NI>();   // bytes per staged row
+        __syncthreads();                                   // every wavefront is done with the operand tiles
+        unsigned char* ep = smem_raw + wave * (MI * 32) * EST;
+        constexpr int LPR = NI * 4, RPI = 64 / LPR;        // lanes per staged row, rows per store instruction
+        const int r_in = lane / LPR, c = (lane % LPR) * 8;
+        const int col = n0 + wn + c;
+        // one block row (32 tile rows) at a time, so the stores of a block row are under way while the next
+        // one is converted; the region is this wavefront's own, and a wavefront's LDS accesses stay in order
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint2 pk;
+                    pk.x = pack_bf16x2(acc[mi][ni][g * 4 + 0], acc[mi][ni][g * 4 + 1]);
+                    pk.y = pack_bf16x2(acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]);
+                    *reinterpret_cast<uint2*>(ep + (mi * 32 + lrow) * EST + (ni * 32 + g * 8 + khalf * 4) * 2) = pk;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int i = 0; i < 32 / RPI; ++i) {
+                const int r = mi * 32 + i * RPI + r_in;
+                const int row = m0 + wm + r;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(ep + r * EST + c * 2);
+                if (row < a.T && col < a.d_out) *reinterpret_cast<u32x4*>(a.out + (size_t)row * a.d_out + col) = v;
+            }
+        }
+        return;
+    }
+
+    if (a.partial != nullptr) {
+        // fp32 split-K tile: same staging, one block row at a time, so the stores are 16-byte pieces of whole rows
+        constexpr int PST = gemm_partial_stride<NI>();
+        __syncthreads();
+        unsigned char* ep = smem_raw + wave * 32 * PST;
+        constexpr int PPR = NI * 8;                        // 16-byte pieces per staged row
+        float* dst = a.partial + (size_t)blockIdx.y * a.T * a.d_out;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 v = {acc[mi][ni][g * 4 + 0], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2],
+                                     acc[mi][ni][g * 4 + 3]};
+                    *reinterpret_cast<f32x4*>(ep + lrow * PST + (ni * 32 + g * 8 + khalf * 4) * 4) = v;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int i = 0; i < 32 * PPR / 64; ++i) {
+                const int p = i * 64 + lane;
+                const int r = p / PPR, c = (p % PPR) * 4;
+                const int row = m0 + wm + mi * 32 + r, col = n0 + wn + c;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(ep + r * PST + c * 4);
+                if (row < a.T && col < a.d_out) *reinterpret_cast<f32x4*>(dst + (size_t)row * a.d_out + col) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        return;
+    }
+
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        const int row = m0 + wm + mi * 32 + lrow;
+        if (row >= a.T) continue;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = n0 + wn + ni * 32 + g * 8 + khalf * 4;
+                if (col >= a.d_out) continue;
+                float v0 = acc[mi][ni][g * 4 + 0], v1 = acc[mi][ni][g * 4 + 1];
+                float v2 = acc[mi][ni][g * 4 + 2], v3 = acc[mi][ni][g * 4 + 3];
+                uint2* dst = reinterpret_cast<uint2*>(a.out + (size_t)row * a.d_out + col);
+                if (a.accumulate) {
+                    const uint2 old = *dst;
+                    v0 += bf16_bits_to_float(old.x & 0xffffu);
+                    v1 += bf16_bits_to_float(old.x >> 16);
+                    v2 += bf16_bits_to_float(old.y & 0xffffu);
+                    v3 += bf16_bits_to_float(old.y >> 16);
+                }
+                uint2 pk;
+                pk.x = pack_bf16x2(v0, v1);
+                pk.y = pack_bf16x2(v2, v3);
+                *dst = pk;
+            }
+        }
+    }
+}
+
 template <int MI, int NI>
 __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
     constexpr int BM = MI * 64, BN = NI * 64;
@@ -477,106 +584,163 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
     for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{});
     for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{});
 
-    // Epilogue.  A lane holds 4 consecutive columns per block row, so direct stores are 8-byte pieces
-    // of 32 different rows per instruction; when the output is simply written (no split-K partials,
-    // no accumulate) the bf16 tile is staged in this wavefront's own LDS region and stored as
-    // 16-byte pieces that cover whole 128-byte lines.
-    if (a.partial == nullptr && !a.accumulate) {
-        constexpr int EST = gemm_epilogue_stride<NI>();   // bytes per staged row
-        __syncthreads();                                   // every wavefront is done with the operand tiles
-        unsigned char* ep = smem_raw + wave * (MI * 32) * EST;
-        constexpr int LPR = NI * 4, RPI = 64 / LPR;        // lanes per staged row, rows per store instruction
-        const int r_in = lane / LPR, c = (lane % LPR) * 8;
-        const int col = n0 + wn + c;
-        // one block row (32 tile rows) at a time, so the stores of a block row are under way while the next
-        // one is converted; the region is this wavefront's own, and a wavefront's LDS accesses stay in order
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    uint2 pk;
-                    pk.x = pack_bf16x2(acc[mi][ni][g * 4 + 0], acc[mi][ni][g * 4 + 1]);
-                    pk.y = pack_bf16x2(acc[mi][ni][g * 4 + 2], acc[mi][ni][g * 4 + 3]);
-                    *reinterpret_cast<uint2*>(ep + (mi * 32 + lrow) * EST + (ni * 32 + g * 8 + khalf * 4) * 2) = pk;
-                }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int i = 0; i < 32 / RPI; ++i) {
-                const int r = mi * 32 + i * RPI + r_in;
-                const int row = m0 + wm + r;
-                const u32x4 v = *reinterpret_cast<const u32x4*>(ep + r * EST + c * 2);
-                if (row < a.T && col < a.d_out) *reinterpret_cast<u32x4*>(a.out + (size_t)row * a.d_out + col) = v;
-            }
-        }
-        return;
-    }
+    gemm_epilogue<MI, NI>(a, acc, smem_raw, m0, n0, wm, wn, wave, lane);
+}
 
-    if (a.partial != nullptr) {
-        // fp32 split-K tile: same staging, one block row at a time, so the stores are 16-byte pieces of whole rows
-        constexpr int PST = gemm_partial_stride<NI>();
+// ------------------------------------------------------------------------------------------
+// 256 x 256 tile with a three-deep ring for the W operand (the whole 160 KB of LDS: 2 x-slots and 3
+// W-slots of 32 KB).  A global->LDS load occupies the CU's address unit for ~16 cycles, so the four
+// wavefronts can sustain one load per two MFMAs each; issued as one per MFMA (all 16 of a tile in the
+// last phase, the only time a two-slot ring has a free slot) they stall the MFMAs queued behind them.
+// Here tile it+2's W pieces go out during the first three phases of tile it, into the W-slot that no
+// wavefront has read since the previous barrier, and only its x pieces wait for the barrier, one per
+// two MFMAs in the last phase.  Loads complete in order, so the barrier of tile it waits for
+// everything but the newest W pieces (vmcnt = pieces per wavefront).  No split-K.
+// ------------------------------------------------------------------------------------------
+constexpr int kGemmW3LdsBytes = (2 * 256 + 3 * 256) * kGemmBK * 2;
+
+__global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
+    constexpr int MI = 4, NI = 4, BM = 256, BN = 256;
+    constexpr int PX = BM / 32, PW = BN / 32;   // pieces per wavefront per tile
+    static_assert(PX == MI + NI && PW == 8, "the phase schedules below are written for 8 + 8 pieces");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+    constexpr int kXElems = BM * kGemmBK, kWElems = BN * kGemmBK;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
+    const int lrow = lane & 31, khalf = lane >> 5;
+    int tile_m, tile_n;
+    tile_of_workgroup(blockIdx.x, a.tiles_m, a.tiles_n, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
+
+    const int nk_main = a.d_in / kGemmBK;
+    const int nk_ext = a.ext_k > 0 ? a.ext_stride / kGemmBK : 0;
+    const int nk = nk_main + nk_ext;
+
+    const DmaOperand ox = dma_operand(a.x, a.T, a.d_in, m0, wave, lane);
+    const DmaOperand ow = dma_operand(a.W, a.d_out, a.d_in, n0, wave, lane);
+    const DmaOperand oh = dma_operand(a.hd, nk_ext > 0 ? a.T : 0, a.ext_stride, m0, wave, lane);
+    const DmaOperand ob = dma_operand(a.Bt, nk_ext > 0 ? a.d_out : 0, a.ext_stride, n0, wave, lane);
+
+    auto xslot = [&](int it) { return smem + (it & 1) * kXElems; };
+    auto wslot = [&](int it) { return smem + 2 * kXElems + (it % 3) * kWElems; };
+    // piece i of the x-like / W-like operand of local tile `it` (main tiles first, then the extension)
+    auto request_x = [&](int it, int i, auto is_ext) {
+        if constexpr (decltype(is_ext)::value) dma_piece(xslot(it), oh, it - nk_main, i, wave);
+        else dma_piece(xslot(it), ox, it, i, wave);
+    };
+    auto request_w = [&](int it, int i, auto is_ext) {
+        if constexpr (decltype(is_ext)::value) dma_piece(wslot(it), ob, it - nk_main, i, wave);
+        else dma_piece(wslot(it), ow, it, i, wave);
+    };
+    auto request_tile = [&](int it) {
+#pragma unroll
+        for (int i = 0; i < PX; ++i) {
+            if (it < nk_main) request_x(it, i, std::false_type{});
+            else request_x(it, i, std::true_type{});
+        }
+#pragma unroll
+        for (int i = 0; i < PW; ++i) {
+            if (it < nk_main) request_w(it, i, std::false_type{});
+            else request_w(it, i, std::true_type{});
+        }
+    };
+
+    Frags<MI, NI> f0, f1;
+    if (nk > 1) {
+        request_tile(0);
+        request_tile(1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PX + PW) : "memory");
         __syncthreads();
-        unsigned char* ep = smem_raw + wave * 32 * PST;
-        constexpr int PPR = NI * 8;                        // 16-byte pieces per staged row
-        float* dst = a.partial + (size_t)blockIdx.y * a.T * a.d_out;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const f32x4 v = {acc[mi][ni][g * 4 + 0], acc[mi][ni][g * 4 + 1], acc[mi][ni][g * 4 + 2],
-                                     acc[mi][ni][g * 4 + 3]};
-                    *reinterpret_cast<f32x4*>(ep + lrow * PST + (ni * 32 + g * 8 + khalf * 4) * 4) = v;
-                }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int i = 0; i < 32 * PPR / 64; ++i) {
-                const int p = i * 64 + lane;
-                const int r = p / PPR, c = (p % PPR) * 4;
-                const int row = m0 + wm + mi * 32 + r, col = n0 + wn + c;
-                const f32x4 v = *reinterpret_cast<const f32x4*>(ep + r * PST + c * 4);
-                if (row < a.T && col < a.d_out) *reinterpret_cast<f32x4*>(dst + (size_t)row * a.d_out + col) = v;
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        }
-        return;
+        load_frags<MI, NI>(f0, xslot(0), wslot(0), wm, wn, lrow, khalf, 0);
+    } else if (nk > 0) {
+        request_tile(0);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        load_frags<MI, NI>(f0, xslot(0), wslot(0), wm, wn, lrow, khalf, 0);
     }
 
+    // REQ: 0 = tile it+2 is a main tile, 1 = it is an extension tile, 2 = there is none (last two tiles)
+    auto tile_step = [&](int it, auto req) {
+        constexpr int REQ = decltype(req)::value;
+        using IsExt = std::integral_constant<bool, REQ == 1>;
+        const bf16_t* xs = xslot(it);
+        const bf16_t* ws = wslot(it);
+        // phases 1-3: 16 MFMAs of k-step ks-1, the 8 fragment reads of k-step ks one per MFMA, and W pieces
+        // [P0, P0 + NPC) of tile it+2 after reads 1, 3, 5 (program order = the order LDS accesses keep)
+        auto phase = [&](Frags<MI, NI>& fnext, const Frags<MI, NI>& fcur, int ks, auto p0, auto npc) {
+            constexpr int P0 = decltype(p0)::value, NPC = decltype(npc)::value;
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-        const int row = m0 + wm + mi * 32 + lrow;
-        if (row >= a.T) continue;
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int col = n0 + wn + ni * 32 + g * 8 + khalf * 4;
-                if (col >= a.d_out) continue;
-                float v0 = acc[mi][ni][g * 4 + 0], v1 = acc[mi][ni][g * 4 + 1];
-                float v2 = acc[mi][ni][g * 4 + 2], v3 = acc[mi][ni][g * 4 + 3];
-                uint2* dst = reinterpret_cast<uint2*>(a.out + (size_t)row * a.d_out + col);
-                if (a.accumulate) {
-                    const uint2 old = *dst;
-                    v0 += bf16_bits_to_float(old.x & 0xffffu);
-                    v1 += bf16_bits_to_float(old.x >> 16);
-                    v2 += bf16_bits_to_float(old.y & 0xffffu);
-                    v3 += bf16_bits_to_float(old.y >> 16);
-                }
-                uint2 pk;
-                pk.x = pack_bf16x2(v0, v1);
-                pk.y = pack_bf16x2(v2, v3);
-                *dst = pk;
+            for (int i = 0; i < MI + NI; ++i) {
+                load_frag1<MI, NI>(fnext, xs, ws, wm, wn, lrow, khalf, ks, i);
+                if constexpr (REQ < 2)
+                    if ((i & 1) && (i >> 1) < NPC) request_w(it + 2, P0 + (i >> 1), IsExt{});
             }
+            mma_frags<MI, NI>(acc, fcur);
+#pragma unroll
+            for (int i = 0; i < MI + NI; ++i) {
+                METEORA_SGB(0x008, 1);
+                METEORA_SGB(0x100, 1);
+                if (REQ < 2 && (i & 1) && (i >> 1) < NPC) METEORA_SGB(0x020, 1);
+            }
+            METEORA_SGB(0x008, MI * NI - (MI + NI));
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        phase(f1, f0, 1, std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{});
+        phase(f0, f1, 2, std::integral_constant<int, 3>{}, std::integral_constant<int, 3>{});
+        phase(f1, f0, 3, std::integral_constant<int, 6>{}, std::integral_constant<int, 2>{});
+        // tile it+1 (x requested one tile ago, W before that) must have landed, and every wavefront's reads of
+        // tile it must be complete; the W pieces of tile it+2 just issued may still be in flight
+        // (a plain s_barrier: __syncthreads() carries a fence, for which the compiler waits for every load)
+        if constexpr (REQ < 2) {
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PW) : "memory");
+        } else {
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
         }
-    }
+        const bf16_t* xn = xslot(it + 1);
+        const bf16_t* wnx = wslot(it + 1);
+        if constexpr (REQ < 2) {
+            // first fragments of tile it+1, and the x pieces of tile it+2 into the x-slot just drained:
+            // one piece per two MFMAs
+#pragma unroll
+            for (int i = 0; i < MI + NI; ++i) {
+                load_frag1<MI, NI>(f0, xn, wnx, wm, wn, lrow, khalf, 0, i);
+                request_x(it + 2, i, IsExt{});
+            }
+            mma_frags<MI, NI>(acc, f1);
+#pragma unroll
+            for (int i = 0; i < MI + NI; ++i) {
+                METEORA_SGB(0x008, 1);
+                METEORA_SGB(0x100, 1);
+                METEORA_SGB(0x008, 1);
+                METEORA_SGB(0x020, 1);
+            }
+        } else {
+            if (it + 1 < nk) load_frags<MI, NI>(f0, xn, wnx, wm, wn, lrow, khalf, 0);
+            mma_frags<MI, NI>(acc, f1);
+#pragma unroll
+            for (int i = 0; i < MI + NI; ++i) { METEORA_SGB(0x008, 1); METEORA_SGB(0x100, 1); }
+            METEORA_SGB(0x008, MI * NI - (MI + NI));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int it = 0;
+    for (; it + 2 < nk_main; ++it) tile_step(it, std::integral_constant<int, 0>{});
+    for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{});
+    for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{});
+
+    gemm_epilogue<MI, NI>(a, acc, smem_raw, m0, n0, wm, wn, wave, lane);
 }
 
 }  // namespace meteora
