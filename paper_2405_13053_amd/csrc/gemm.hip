@@ -134,12 +134,12 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
     } else if (dma_ok && MI == 4 && NI == 4) {
         static bool w3_attr_set = false;
         if (!w3_attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmW3LdsBytes);
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<4, 4>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, gemm_w3_lds_bytes<4, 4>());
             if (e != hipSuccess) return e;
             w3_attr_set = true;
         }
-        gemm_mfma_w3_kernel<<<a.tiles_m * a.tiles_n, 256, kGemmW3LdsBytes, stream>>>(a);
+        gemm_mfma_w3_kernel<4, 4><<<a.tiles_m * a.tiles_n, 256, gemm_w3_lds_bytes<4, 4>(), stream>>>(a);
     } else if (dma_ok) {
         gemm_mfma_dma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
     } else {
@@ -152,9 +152,9 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
 // Dense routing operand: partial[split][T][rows] = x[T, K-range of split] * Wcat[rows, same K]^T in fp32,
 // no reduction (the select kernel adds the splits in order).
 // ------------------------------------------------------------------------------------------
-// Up to 4096 tokens: 128 x 128 tiles, two workgroups per CU (one computes while the other waits for its loads:
-// with one K tile in flight per workgroup the loop runs at memory latency), about 384 workgroups; above:
-// 128 x 320 tiles (x is read once), one workgroup per CU.  Measured on T = 4096 and 8192, d_in = 4096 and 14336.
+// Up to 4096 tokens: 128 x 128 tiles, two workgroups per CU (one computes while the other waits for its
+// loads), about 384 workgroups; above: 128 x 320 tiles (x is read once), one workgroup per CU.  Both with
+// the three-deep W ring.  Measured on T = 4096 and 8192, d_in = 4096 and 14336.
 static bool dense_small_tiles(int T) { return T <= 4096; }
 
 bool gemm_dense_splitk_ok(int T, int d_in, int rows) {
@@ -171,19 +171,21 @@ int gemm_dense_splits(int T, int d_in, int rows) {
     return S < 1 ? 1 : S;
 }
 
-template <int MI, int NI>
+template <int MI, int NI, bool W3>
 static hipError_t launch_dense(GemmArgs a, hipStream_t stream) {
-    constexpr int smem = gemm_lds_bytes<MI, NI>();
+    static_assert(W3, "the dense products use the three-deep W ring");
+    constexpr int smem = gemm_w3_lds_bytes<MI, NI>();
+    auto kern = &gemm_mfma_w3_kernel<MI, NI>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_dma_kernel<MI, NI>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     a.tiles_m = ceil_div(a.T, MI * 64);
     a.tiles_n = ceil_div(a.d_out, NI * 64);
-    gemm_mfma_dma_kernel<MI, NI><<<dim3(a.tiles_m * a.tiles_n, a.splits), 256, smem, stream>>>(a);
+    kern<<<dim3(a.tiles_m * a.tiles_n, a.splits), 256, smem, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -195,7 +197,7 @@ hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int 
     a.partial = partial;
     a.splits = gemm_dense_splits(T, d_in, rows);
     a.tiles_per_split = ceil_div(d_in / kGemmBK, a.splits);
-    return dense_small_tiles(T) ? launch_dense<2, 2>(a, stream) : launch_dense<2, 5>(a, stream);
+    return dense_small_tiles(T) ? launch_dense<2, 2, true>(a, stream) : launch_dense<2, 5, true>(a, stream);
 }
 
 bool gemm_fuses_expand(bool bf16) { return bf16; }

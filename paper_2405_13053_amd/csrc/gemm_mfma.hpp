@@ -18,6 +18,7 @@
 // columns of one token row and stores them as one 8-byte word.
 #pragma once
 #include <type_traits>
+#include <utility>
 
 #include "common.hpp"
 
@@ -588,21 +589,51 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// 256 x 256 tile with a three-deep ring for the W operand (the whole 160 KB of LDS: 2 x-slots and 3
-// W-slots of 32 KB).  A global->LDS load occupies the CU's address unit for ~16 cycles, so the four
-// wavefronts can sustain one load per two MFMAs each; issued as one per MFMA (all 16 of a tile in the
-// last phase, the only time a two-slot ring has a free slot) they stall the MFMAs queued behind them.
+// The same pipeline with a three-deep ring for the W operand (2 x-slots + 3 W-slots: the whole 160 KB of
+// LDS for the 256 x 256 tile).  A global->LDS load occupies the CU's address unit for ~16 cycles, so the
+// four wavefronts can sustain one load per two MFMAs each; issued as one per MFMA (all pieces of a tile in
+// the last phase, the only time a two-slot ring has a free slot) they stall the MFMAs queued behind them.
 // Here tile it+2's W pieces go out during the first three phases of tile it, into the W-slot that no
-// wavefront has read since the previous barrier, and only its x pieces wait for the barrier, one per
-// two MFMAs in the last phase.  Loads complete in order, so the barrier of tile it waits for
-// everything but the newest W pieces (vmcnt = pieces per wavefront).  No split-K.
+// wavefront has read since the previous barrier, and only its x pieces wait for the barrier, spread over
+// the MFMAs of the last phase.  Loads complete in order, so the barrier of tile it waits for everything
+// but the newest W pieces (vmcnt = W pieces per wavefront).
 // ------------------------------------------------------------------------------------------
-constexpr int kGemmW3LdsBytes = (2 * 256 + 3 * 256) * kGemmBK * 2;
+template <int MI, int NI>
+__host__ __device__ constexpr int gemm_w3_lds_bytes() {
+    constexpr int ring = (2 * MI * 64 + 3 * NI * 64) * kGemmBK * 2;
+    constexpr int stage = 4 * (MI * 32) * gemm_epilogue_stride<NI>();
+    constexpr int pstage = 4 * 32 * gemm_partial_stride<NI>();
+    constexpr int m = ring > stage ? ring : stage;
+    return m > pstage ? m : pstage;
+}
 
+// how many of NPC pieces go out right after the i-th of NR fragment reads (evenly spread, the last read included)
+__host__ __device__ constexpr int pieces_after_read(int i, int NPC, int NR) {
+    return (i + 1) * NPC / NR - i * NPC / NR;
+}
+
+template <int N>
+__device__ __forceinline__ void sgb_vmem() {
+    if constexpr (N > 0) METEORA_SGB(0x020, N);
+}
+template <int N>
+__device__ __forceinline__ void sgb_mfma() {
+    if constexpr (N > 0) METEORA_SGB(0x008, N);
+}
+
+// Order of one phase: per fragment read, one MFMA, the read, MPR-1 more MFMAs, then the read's share of NPC loads.
+template <int MPR, int NPC, int NR, int... I>
+__device__ __forceinline__ void sgb_reads(std::integer_sequence<int, I...>) {
+    ((METEORA_SGB(0x008, 1), METEORA_SGB(0x100, 1), sgb_mfma<MPR - 1>(), sgb_vmem<pieces_after_read(I, NPC, NR)>()), ...);
+}
+
+template <int MI, int NI>
 __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
-    constexpr int MI = 4, NI = 4, BM = 256, BN = 256;
+    constexpr int BM = MI * 64, BN = NI * 64;
     constexpr int PX = BM / 32, PW = BN / 32;   // pieces per wavefront per tile
-    static_assert(PX == MI + NI && PW == 8, "the phase schedules below are written for 8 + 8 pieces");
+    constexpr int NR = MI + NI;                 // fragment reads per k-step
+    static_assert(MI * NI >= NR, "a phase needs one MFMA per fragment read");
+    constexpr int PW1 = (PW + 2) / 3, PW2 = (PW - PW1 + 1) / 2, PW3 = PW - PW1 - PW2;   // W pieces per phase
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
     constexpr int kXElems = BM * kGemmBK, kWElems = BN * kGemmBK;
@@ -623,8 +654,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = 0.f;
 
-    const int nk_main = a.d_in / kGemmBK;
-    const int nk_ext = a.ext_k > 0 ? a.ext_stride / kGemmBK : 0;
+    // this workgroup's share of the contraction: main K tiles [kt0, kt0 + nk_main) and/or the extension
+    int kt0 = 0, nk_main = a.d_in / kGemmBK;
+    int nk_ext = a.ext_k > 0 ? a.ext_stride / kGemmBK : 0;
+    if (a.partial != nullptr) {
+        const int split = blockIdx.y;
+        if (split < a.splits) {
+            kt0 = split * a.tiles_per_split;
+            nk_main = max(0, min(a.tiles_per_split, nk_main - kt0));
+            nk_ext = 0;
+        } else {
+            nk_main = 0;
+        }
+    }
     const int nk = nk_main + nk_ext;
 
     const DmaOperand ox = dma_operand(a.x, a.T, a.d_in, m0, wave, lane);
@@ -637,22 +679,23 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
     // piece i of the x-like / W-like operand of local tile `it` (main tiles first, then the extension)
     auto request_x = [&](int it, int i, auto is_ext) {
         if constexpr (decltype(is_ext)::value) dma_piece(xslot(it), oh, it - nk_main, i, wave);
-        else dma_piece(xslot(it), ox, it, i, wave);
+        else dma_piece(xslot(it), ox, kt0 + it, i, wave);
     };
     auto request_w = [&](int it, int i, auto is_ext) {
         if constexpr (decltype(is_ext)::value) dma_piece(wslot(it), ob, it - nk_main, i, wave);
-        else dma_piece(wslot(it), ow, it, i, wave);
+        else dma_piece(wslot(it), ow, kt0 + it, i, wave);
     };
     auto request_tile = [&](int it) {
+        if (it < nk_main) {
 #pragma unroll
-        for (int i = 0; i < PX; ++i) {
-            if (it < nk_main) request_x(it, i, std::false_type{});
-            else request_x(it, i, std::true_type{});
-        }
+            for (int i = 0; i < PX; ++i) request_x(it, i, std::false_type{});
 #pragma unroll
-        for (int i = 0; i < PW; ++i) {
-            if (it < nk_main) request_w(it, i, std::false_type{});
-            else request_w(it, i, std::true_type{});
+            for (int i = 0; i < PW; ++i) request_w(it, i, std::false_type{});
+        } else {
+#pragma unroll
+            for (int i = 0; i < PX; ++i) request_x(it, i, std::true_type{});
+#pragma unroll
+            for (int i = 0; i < PW; ++i) request_w(it, i, std::true_type{});
         }
     };
 
@@ -676,29 +719,28 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
         using IsExt = std::integral_constant<bool, REQ == 1>;
         const bf16_t* xs = xslot(it);
         const bf16_t* ws = wslot(it);
-        // phases 1-3: 16 MFMAs of k-step ks-1, the 8 fragment reads of k-step ks one per MFMA, and W pieces
-        // [P0, P0 + NPC) of tile it+2 after reads 1, 3, 5 (program order = the order LDS accesses keep)
+        // phases 1-3: MI*NI MFMAs of k-step ks-1, the fragment reads of k-step ks one per MFMA from the start of
+        // the phase, and W pieces [P0, P0 + NPC) of tile it+2 spread between the reads (program order = the
+        // order the LDS accesses keep)
         auto phase = [&](Frags<MI, NI>& fnext, const Frags<MI, NI>& fcur, int ks, auto p0, auto npc) {
-            constexpr int P0 = decltype(p0)::value, NPC = decltype(npc)::value;
+            constexpr int P0 = decltype(p0)::value, NPC = REQ < 2 ? decltype(npc)::value : 0;
+            int issued = 0;
 #pragma unroll
-            for (int i = 0; i < MI + NI; ++i) {
+            for (int i = 0; i < NR; ++i) {
                 load_frag1<MI, NI>(fnext, xs, ws, wm, wn, lrow, khalf, ks, i);
-                if constexpr (REQ < 2)
-                    if ((i & 1) && (i >> 1) < NPC) request_w(it + 2, P0 + (i >> 1), IsExt{});
+                if constexpr (NPC > 0) {
+#pragma unroll
+                    for (int c = 0; c < pieces_after_read(i, NPC, NR); ++c) request_w(it + 2, P0 + issued++, IsExt{});
+                }
             }
             mma_frags<MI, NI>(acc, fcur);
-#pragma unroll
-            for (int i = 0; i < MI + NI; ++i) {
-                METEORA_SGB(0x008, 1);
-                METEORA_SGB(0x100, 1);
-                if (REQ < 2 && (i & 1) && (i >> 1) < NPC) METEORA_SGB(0x020, 1);
-            }
-            METEORA_SGB(0x008, MI * NI - (MI + NI));
+            sgb_reads<1, NPC, NR>(std::make_integer_sequence<int, NR>{});
+            sgb_mfma<MI * NI - NR>();
             __builtin_amdgcn_sched_barrier(0);
         };
-        phase(f1, f0, 1, std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{});
-        phase(f0, f1, 2, std::integral_constant<int, 3>{}, std::integral_constant<int, 3>{});
-        phase(f1, f0, 3, std::integral_constant<int, 6>{}, std::integral_constant<int, 2>{});
+        phase(f1, f0, 1, std::integral_constant<int, 0>{}, std::integral_constant<int, PW1>{});
+        phase(f0, f1, 2, std::integral_constant<int, PW1>{}, std::integral_constant<int, PW2>{});
+        phase(f1, f0, 3, std::integral_constant<int, PW1 + PW2>{}, std::integral_constant<int, PW3>{});
         // tile it+1 (x requested one tile ago, W before that) must have landed, and every wavefront's reads of
         // tile it must be complete; the W pieces of tile it+2 just issued may still be in flight
         // (a plain s_barrier: __syncthreads() carries a fence, for which the compiler waits for every load)
@@ -711,27 +753,24 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
         const bf16_t* xn = xslot(it + 1);
         const bf16_t* wnx = wslot(it + 1);
         if constexpr (REQ < 2) {
-            // first fragments of tile it+1, and the x pieces of tile it+2 into the x-slot just drained:
-            // one piece per two MFMAs
+            // first fragments of tile it+1, and the x pieces of tile it+2 into the x-slot just drained, spread
+            // over the phase: MPR MFMAs per read, a read's pieces after them
+            constexpr int MPR = MI * NI / NR;
+            int issued = 0;
 #pragma unroll
-            for (int i = 0; i < MI + NI; ++i) {
+            for (int i = 0; i < NR; ++i) {
                 load_frag1<MI, NI>(f0, xn, wnx, wm, wn, lrow, khalf, 0, i);
-                request_x(it + 2, i, IsExt{});
+#pragma unroll
+                for (int c = 0; c < pieces_after_read(i, PX, NR); ++c) request_x(it + 2, issued++, IsExt{});
             }
             mma_frags<MI, NI>(acc, f1);
-#pragma unroll
-            for (int i = 0; i < MI + NI; ++i) {
-                METEORA_SGB(0x008, 1);
-                METEORA_SGB(0x100, 1);
-                METEORA_SGB(0x008, 1);
-                METEORA_SGB(0x020, 1);
-            }
+            sgb_reads<MPR, PX, NR>(std::make_integer_sequence<int, NR>{});
+            sgb_mfma<MI * NI - NR * MPR>();
         } else {
             if (it + 1 < nk) load_frags<MI, NI>(f0, xn, wnx, wm, wn, lrow, khalf, 0);
             mma_frags<MI, NI>(acc, f1);
-#pragma unroll
-            for (int i = 0; i < MI + NI; ++i) { METEORA_SGB(0x008, 1); METEORA_SGB(0x100, 1); }
-            METEORA_SGB(0x008, MI * NI - (MI + NI));
+            sgb_reads<1, 0, NR>(std::make_integer_sequence<int, NR>{});
+            sgb_mfma<MI * NI - NR>();
         }
         __builtin_amdgcn_sched_barrier(0);
     };
