@@ -135,7 +135,9 @@ meteora_status meteora_linear_forward(const void* x, const void* W, const float*
  * Weight packing, done once when the adapters are loaded: the stacked adapter
  * tensors of Sec. 3.3 and the gate weight are static during inference, so their
  * kernel-side layouts (W_gate split into three bf16 terms in matrix-core operand
- * order, A in operand order, B transposed) need not be rebuilt for every batch.
+ * order, A in operand order, B transposed, and the gate terms with every column of
+ * every A_i as the rows of one matrix for the mid-sized-batch routing kernel) need
+ * not be rebuilt for every batch.
  *   meteora_packed_bytes   size of the packed blob for these shapes (0 if this dtype
  *                          uses no packed operands, e.g. METEORA_F32).  Host only.
  *   meteora_pack_weights   fills `packed` (device, 256-byte aligned, caller-owned) from
@@ -178,7 +180,10 @@ meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, 
  * Optional per-stage timing, for benchmarks.  Host only; off by default.
  * While enabled, meteora_lora_forward and meteora_linear_forward record
  * hipEvents on `stream` around each stage (prep, gate_logits, gate_topk,
- * bucket, shrink, gemm, expand) for up to 256 calls.  meteora_stage_timing_read waits
+ * bucket, shrink, gemm, expand) for up to 256 calls.  A stage that a batch size
+ * folds into another is not reported: for 64 < T <= 8192 (bf16) gate_logits covers
+ * the gate logits and the shrink, gate_topk the top-k, softmax and selection; for
+ * T <= 64 shrink covers top-k, softmax and shrink.  meteora_stage_timing_read waits
  * for those events, returns per stage the summed milliseconds and the number
  * of timed launches (arrays of meteora_stage_count() entries, host memory)
  * and the number of calls covered, and starts a new window.  Not thread-safe;
