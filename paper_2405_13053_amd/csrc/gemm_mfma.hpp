@@ -677,25 +677,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
     auto xslot = [&](int it) { return smem + (it & 1) * kXElems; };
     auto wslot = [&](int it) { return smem + 2 * kXElems + (it % 3) * kWElems; };
     // piece i of the x-like / W-like operand of local tile `it` (main tiles first, then the extension)
-    auto request_x = [&](int it, int i, auto is_ext) {
-        if constexpr (decltype(is_ext)::value) dma_piece(xslot(it), oh, it - nk_main, i, wave);
-        else dma_piece(xslot(it), ox, kt0 + it, i, wave);
+    auto request_x = [&](bf16_t* slot, int it, int i, auto is_ext) {
+        if constexpr (decltype(is_ext)::value) dma_piece(slot, oh, it - nk_main, i, wave);
+        else dma_piece(slot, ox, kt0 + it, i, wave);
     };
-    auto request_w = [&](int it, int i, auto is_ext) {
-        if constexpr (decltype(is_ext)::value) dma_piece(wslot(it), ob, it - nk_main, i, wave);
-        else dma_piece(wslot(it), ow, kt0 + it, i, wave);
+    auto request_w = [&](bf16_t* slot, int it, int i, auto is_ext) {
+        if constexpr (decltype(is_ext)::value) dma_piece(slot, ob, it - nk_main, i, wave);
+        else dma_piece(slot, ow, kt0 + it, i, wave);
     };
     auto request_tile = [&](int it) {
         if (it < nk_main) {
 #pragma unroll
-            for (int i = 0; i < PX; ++i) request_x(it, i, std::false_type{});
+            for (int i = 0; i < PX; ++i) request_x(xslot(it), it, i, std::false_type{});
 #pragma unroll
-            for (int i = 0; i < PW; ++i) request_w(it, i, std::false_type{});
+            for (int i = 0; i < PW; ++i) request_w(wslot(it), it, i, std::false_type{});
         } else {
 #pragma unroll
-            for (int i = 0; i < PX; ++i) request_x(it, i, std::true_type{});
+            for (int i = 0; i < PX; ++i) request_x(xslot(it), it, i, std::true_type{});
 #pragma unroll
-            for (int i = 0; i < PW; ++i) request_w(it, i, std::true_type{});
+            for (int i = 0; i < PW; ++i) request_w(wslot(it), it, i, std::true_type{});
         }
     };
 
@@ -714,11 +714,23 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
     }
 
     // REQ: 0 = tile it+2 is a main tile, 1 = it is an extension tile, 2 = there is none (last two tiles)
-    auto tile_step = [&](int it, auto req) {
-        constexpr int REQ = decltype(req)::value;
+    // PH: it % 6 when it is known at compile time (the unrolled main loop: every slot address is then a
+    // constant and no address arithmetic sits between two tiles), -1 otherwise
+    auto tile_step = [&](int it, auto req, auto ph) {
+        constexpr int REQ = decltype(req)::value, PH = decltype(ph)::value;
         using IsExt = std::integral_constant<bool, REQ == 1>;
-        const bf16_t* xs = xslot(it);
-        const bf16_t* ws = wslot(it);
+        auto xsl = [&](int d) {   // x-slot / W-slot of tile it + d
+            if constexpr (PH >= 0) return smem + ((PH + d) & 1) * kXElems;
+            else return xslot(it + d);
+        };
+        auto wsl = [&](int d) {
+            if constexpr (PH >= 0) return smem + 2 * kXElems + ((PH + d) % 3) * kWElems;
+            else return wslot(it + d);
+        };
+        const bf16_t* xs = xsl(0);
+        const bf16_t* ws = wsl(0);
+        bf16_t* const xreq = xsl(2);
+        bf16_t* const wreq = wsl(2);
         // phases 1-3: MI*NI MFMAs of k-step ks-1, the fragment reads of k-step ks one per MFMA from the start of
         // the phase, and W pieces [P0, P0 + NPC) of tile it+2 spread between the reads (program order = the
         // order the LDS accesses keep)
@@ -730,7 +742,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
                 load_frag1<MI, NI>(fnext, xs, ws, wm, wn, lrow, khalf, ks, i);
                 if constexpr (NPC > 0) {
 #pragma unroll
-                    for (int c = 0; c < pieces_after_read(i, NPC, NR); ++c) request_w(it + 2, P0 + issued++, IsExt{});
+                    for (int c = 0; c < pieces_after_read(i, NPC, NR); ++c) request_w(wreq, it + 2, P0 + issued++, IsExt{});
                 }
             }
             mma_frags<MI, NI>(acc, fcur);
@@ -750,18 +762,20 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
         }
-        const bf16_t* xn = xslot(it + 1);
-        const bf16_t* wnx = wslot(it + 1);
+        const bf16_t* xn = xsl(1);
+        const bf16_t* wnx = wsl(1);
         if constexpr (REQ < 2) {
             // first fragments of tile it+1, and the x pieces of tile it+2 into the x-slot just drained, spread
             // over the phase: MPR MFMAs per read, a read's pieces after them
             constexpr int MPR = MI * NI / NR;
             int issued = 0;
+            // read order: the next phase's first MFMAs use x block 0 with every W block, then x blocks 1..
 #pragma unroll
             for (int i = 0; i < NR; ++i) {
-                load_frag1<MI, NI>(f0, xn, wnx, wm, wn, lrow, khalf, 0, i);
+                const int fi = i == 0 ? 0 : (i <= NI ? MI + i - 1 : i - NI);
+                load_frag1<MI, NI>(f0, xn, wnx, wm, wn, lrow, khalf, 0, fi);
 #pragma unroll
-                for (int c = 0; c < pieces_after_read(i, PX, NR); ++c) request_x(it + 2, issued++, IsExt{});
+                for (int c = 0; c < pieces_after_read(i, PX, NR); ++c) request_x(xreq, it + 2, issued++, IsExt{});
             }
             mma_frags<MI, NI>(acc, f1);
             sgb_reads<MPR, PX, NR>(std::make_integer_sequence<int, NR>{});
@@ -774,10 +788,22 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
         }
         __builtin_amdgcn_sched_barrier(0);
     };
+    using Req0 = std::integral_constant<int, 0>;
+    using Rt = std::integral_constant<int, -1>;
     int it = 0;
-    for (; it + 2 < nk_main; ++it) tile_step(it, std::integral_constant<int, 0>{});
-    for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{});
-    for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{});
+    if constexpr (MI == 4 && NI == 4) {   // six tiles per trip: the period of the 2-slot and 3-slot rings
+        for (; it + 7 < nk_main; it += 6) {
+            tile_step(it, Req0{}, std::integral_constant<int, 0>{});
+            tile_step(it + 1, Req0{}, std::integral_constant<int, 1>{});
+            tile_step(it + 2, Req0{}, std::integral_constant<int, 2>{});
+            tile_step(it + 3, Req0{}, std::integral_constant<int, 3>{});
+            tile_step(it + 4, Req0{}, std::integral_constant<int, 4>{});
+            tile_step(it + 5, Req0{}, std::integral_constant<int, 5>{});
+        }
+    }
+    for (; it + 2 < nk_main; ++it) tile_step(it, Req0{}, Rt{});
+    for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{}, Rt{});
+    for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{}, Rt{});
 
     gemm_epilogue<MI, NI>(a, acc, smem_raw, m0, n0, wm, wn, wave, lane);
 }
