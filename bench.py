@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this same command (each counter scaled by what it reads for a plain 1 GiB copy kernel: 2.0 and 1.0);
 # the summary is profiles/linear_forward_config2_hbm_traffic.md.  Only the profiled workload has a value.
-MEASURED_GEMM_TRAFFIC_BYTES = {(2, 0): 108845.5 * 2.0 * 1024 + 41216.0 * 1024}
+MEASURED_GEMM_TRAFFIC_BYTES = {(2, 0): 106856.5 * 2.0 * 1024 + 37376.0 * 1024}
 
 
 def algorithmic(shape):
