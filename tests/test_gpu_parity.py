@@ -297,6 +297,45 @@ def test_dense_route_exact_ties_and_zero_gate():
             assert np.all(~(idx == 9).any(axis=1) | (idx == 5).any(axis=1))
 
 
+GRAPH_SHAPES = [
+    LS(33, 1024, 520, 28, 8, 2, 2.0, "bf16", "uniform", "graph-decode"),
+    LS(333, 1024, 520, 28, 8, 2, 2.0, "bf16", "zipf", "graph-dense-route"),
+    LS(400, 1024, 520, 28, 16, 2, 2.0, "bf16", "uniform", "graph-bucketed"),
+]
+
+
+@pytest.mark.parametrize("shape", GRAPH_SHAPES, ids=lambda s: s.name)
+def test_layer_call_replays_from_a_hip_graph(shape):
+    """The library allocates nothing and records no memset: a captured call replays bit-identically on new inputs."""
+    ops, dev = util.make_case(shape, seed=48, condition=False)
+    dt = util.torch_dtype(shape)
+    packed = m.pack_weights(dev["W_gate"], dev["A"], dev["B"])
+    ws = torch.empty(m.workspace_bytes(shape.T, shape.d_in, shape.d_out, shape.N, shape.r, shape.k, dt),
+                     dtype=torch.uint8, device="cuda")
+    x_in = dev["x"].clone()
+    out = torch.empty((shape.T, shape.d_out), dtype=dt, device="cuda")
+    args = (dev["W"], dev["W_gate"], dev["bias"], dev["A"], dev["B"], shape.k, shape.scale)
+    m.linear_forward(x_in, *args, out=out, ws=ws, packed=packed)   # first call sets the kernels' LDS attributes
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            m.linear_forward(x_in, *args, out=out, ws=ws, packed=packed)
+    torch.cuda.synchronize()
+    gen_t = torch.Generator(device="cuda").manual_seed(5)
+    for rep in range(3):
+        x_new = torch.randn(dev["x"].shape, generator=gen_t, device="cuda", dtype=torch.float32).to(dt)
+        ref = m.linear_forward(x_new, *args, packed=packed)           # eager, own output and workspace
+        torch.cuda.synchronize()
+        x_in.copy_(x_new)
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), f"replay {rep} differs from the eager call"
+
+
 def test_linear_forward_single_adapter_is_merged_gemm():
     """N=1,k=1: the layer is x(W + s*A*B) (Eq. 1)."""
     shape = LS(100, 256, 264, 1, 8, 1, 2.0, "f32")
