@@ -13,12 +13,19 @@ namespace {
 
 struct WsLayout {
     size_t wsplit, partials, chunk_counts, counts, offsets, bucket_tok, bucket_slot, topk_idx, topk_w, h32,
-        hdense, apack, hpart, splitk, btrans, wcat, dpart, total;
+        hdense, apack, hpart, splitk, btrans, wcat, dpart, gpart, total;
     int ext_stride;   // columns of hdense: N*r rounded up to 64 (one K tile of the GEMM)
 };
 
 bool shape_ok(int T, int d_in, int d_out, int N, int r, int k) {
     return T >= 0 && d_in >= 1 && d_out >= 1 && N >= 1 && r >= 1 && k >= 1 && k <= N;
+}
+
+// Decode in three launches (gate logits inside the GEMM's launch, routing + shrink, reduce + expand): the split-K
+// shapes whose adapters also have the Wcat operand.
+bool decode_fused_applies(int T, int d_in, int d_out, int N, int r, bool bf16) {
+    return route_small_applies(T, r, bf16) && gemm_splitk_splits(T, d_in, d_out, bf16) > 0 &&
+           route_dense_possible(d_in, N, r, bf16);
 }
 
 bool shape_supported(int T, int d_in, int d_out, int N, int r, int k) {
@@ -49,8 +56,10 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     L.splitk = take(gemm_splitk_bytes(T, d_in, d_out, bf16));
     L.btrans = take(prep_btrans_bytes(d_out, N, r, bf16));
     const bool dense = route_dense_applies(T, d_in, N, r, bf16);
-    L.wcat = take(dense ? prep_wcat_bytes(d_in, N, r, bf16) : 0);
+    const bool decode3 = decode_fused_applies(T, d_in, d_out, N, r, bf16);
+    L.wcat = take(dense || decode3 ? prep_wcat_bytes(d_in, N, r, bf16) : 0);
     L.dpart = take(route_dense_part_bytes(T, d_in, N, r, bf16));
+    L.gpart = take(decode3 ? (size_t)gemm_splitk_splits(T, d_in, d_out, bf16) * T * 3 * NP * sizeof(float) : 0);
     L.total = off;
     return L;
 }
@@ -369,6 +378,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
     const int tslot = timing_begin_call();
     // mid-sized batch: gate logits and the shrink of every adapter in one MFMA launch, selection afterwards
     const bool dense = route_dense_applies(T, d_in, N, r, bf16);
+    const bool decode3 = decode_fused_applies(T, d_in, d_out, N, r, bf16);
     PackedPtrs pk{at<void>(ws, L.wsplit), at<void>(ws, L.apack), at<void>(ws, L.btrans), at<void>(ws, L.wcat)};
     if (use_packed) {
         void* blob = const_cast<void*>(packed);   // read only from here on
@@ -377,11 +387,31 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
     } else {
         // only the operands this batch size reads are packed
         StageScope sc(ST_PREP, st, tslot);
-        const bool pw = !dense && gate_wsplit_bytes(d_in, N, bf16) > 0;
-        const bool pa = !dense && shrink_apack_bytes(d_in, N, r, bf16) > 0;
-        const bool pb = prep_btrans_bytes(d_out, N, r, bf16) > 0;
+        const bool pw = !dense && !decode3 && gate_wsplit_bytes(d_in, N, bf16) > 0;
+        const bool pa = !dense && !decode3 && shrink_apack_bytes(d_in, N, r, bf16) > 0;
+        const bool pb = !decode3 && prep_btrans_bytes(d_out, N, r, bf16) > 0;
         METEORA_HIP(launch_prep(W_gate, pw ? pk.wsplit : nullptr, A, pa ? pk.apack : nullptr, pb ? B : nullptr,
-                                pb ? pk.btrans : nullptr, dense ? pk.wcat : nullptr, d_in, d_out, N, r, st));
+                                pb ? pk.btrans : nullptr, dense || decode3 ? pk.wcat : nullptr, d_in, d_out, N, r, st));
+    }
+    if (decode3) {
+        // decode-sized batch: the launch that streams W also computes the gate logits; then top-k, softmax and the
+        // shrink of the selected adapters token by token; then the split-K reduction, which adds the expand
+        float* part = at<float>(ws, L.splitk);
+        float* gpart = at<float>(ws, L.gpart);
+        float* hs = at<float>(ws, L.h32);
+        const int S = gemm_splitk_splits(T, d_in, d_out, bf16);
+        {
+            StageScope sc(ST_GEMM, st, tslot);
+            METEORA_HIP(launch_gemm_decode_main(x, W, pk.wcat, 3 * padded_adapters(N), T, d_in, d_out, part, gpart, st));
+        }
+        {
+            StageScope sc(ST_SHRINK, st, tslot);
+            METEORA_HIP(launch_route_shrink_small(x, nullptr, 0, gate_bias, A, T, d_in, N, r, k, 1.0f, scale, idx, w,
+                                                  nullptr, L.ext_stride, st, gpart, S, hs));
+        }
+        StageScope sc(ST_EXPAND, st, tslot);
+        METEORA_HIP(launch_gemm_decode_finish(part, T, d_in, d_out, hs, idx, B, k, r, out, st));
+        return METEORA_OK;
     }
     if (dense) {
         float* dpart = at<float>(ws, L.dpart);

@@ -87,6 +87,61 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __
     *dst = pk;
 }
 
+// Decode: the fixed-order sum of the split-K tiles plus the LoRA expand of Eq. 2 from the fp32 shrink outputs,
+//   out[t, c] = bf16( sum_s partial[s][t][c] + sum_slot sum_q hs[t][slot][q] * B[idx[t][slot]][q][c] ),
+// hs = scale * w * h.  A thread owns 8 consecutive columns of one token: B rows are read as 16-byte pieces,
+// coalesced across the threads of a token.
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_expand_kernel(
+    const float* __restrict__ partial, int nsplit, int T, int d_out, const float* __restrict__ hs,
+    const int32_t* __restrict__ idx, const bf16_t* __restrict__ B, int k, int r, bf16_t* __restrict__ out) {
+    const int c8 = d_out / 8;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (size_t)T * c8) return;
+    const int t = (int)(i / c8), c = (int)(i - (size_t)t * c8) * 8;
+    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {   // tiles in order, 8 tiles' loads in flight
+        f32x4 v0[8], v1[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float* src = partial + ((size_t)min(s0 + u, nsplit - 1) * T + t) * d_out + c;
+            v0[u] = *reinterpret_cast<const f32x4*>(src);
+            v1[u] = *reinterpret_cast<const f32x4*>(src + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < nsplit) { lo += v0[u]; hi += v1[u]; }
+    }
+    for (int slot = 0; slot < k; ++slot) {
+        const int a = idx[(size_t)t * k + slot];
+        const float* h = hs + ((size_t)t * k + slot) * r;
+        const bf16_t* Ba = B + (size_t)a * r * d_out + c;
+        for (int q0 = 0; q0 < r; q0 += 8) {   // r % 8 == 0; 8 rows of B in flight
+            u32x4 b[8];
+            float hv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                b[u] = *reinterpret_cast<const u32x4*>(Ba + (size_t)(q0 + u) * d_out);
+                hv[u] = h[q0 + u];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                lo[0] = fmaf(hv[u], bf16_bits_to_float(b[u][0] & 0xffffu), lo[0]);
+                lo[1] = fmaf(hv[u], bf16_bits_to_float(b[u][0] >> 16), lo[1]);
+                lo[2] = fmaf(hv[u], bf16_bits_to_float(b[u][1] & 0xffffu), lo[2]);
+                lo[3] = fmaf(hv[u], bf16_bits_to_float(b[u][1] >> 16), lo[3]);
+                hi[0] = fmaf(hv[u], bf16_bits_to_float(b[u][2] & 0xffffu), hi[0]);
+                hi[1] = fmaf(hv[u], bf16_bits_to_float(b[u][2] >> 16), hi[1]);
+                hi[2] = fmaf(hv[u], bf16_bits_to_float(b[u][3] & 0xffffu), hi[2]);
+                hi[3] = fmaf(hv[u], bf16_bits_to_float(b[u][3] >> 16), hi[3]);
+            }
+        }
+    }
+    u32x4 pk;
+    pk[0] = pack_bf16x2(lo[0], lo[1]); pk[1] = pack_bf16x2(lo[2], lo[3]);
+    pk[2] = pack_bf16x2(hi[0], hi[1]); pk[3] = pack_bf16x2(hi[2], hi[3]);
+    reinterpret_cast<u32x4*>(out)[i] = pk;
+}
+
 // Skinny batches (decode): one 64-row tile per 64 output columns leaves most CUs idle while W streams
 // from HBM, so K is split over workgroups.  Returns the number of main-K splits (0 = do not split).
 int gemm_splitk_splits(int T, int d_in, int d_out, bool bf16) {
@@ -198,6 +253,46 @@ hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int 
     a.splits = gemm_dense_splits(T, d_in, rows);
     a.tiles_per_split = ceil_div(d_in / kGemmBK, a.splits);
     return dense_small_tiles(T) ? launch_dense<2, 2, true>(a, stream) : launch_dense<2, 5, true>(a, stream);
+}
+
+// Decode in three launches: (1) the main K splits of x * W^T with the gate-term rows of Wcat as extra column
+// tiles (fp32 tiles into `partial` and `gpartial`), (2) routing and shrink on the gate tiles (route_small.hip),
+// (3) reduce + expand.  Shapes: gemm_splitk_splits(T, d_in, d_out) > 0.
+hipError_t launch_gemm_decode_main(const void* x, const void* W, const void* wg3, int gate_rows, int T, int d_in,
+                                   int d_out, float* partial, float* gpartial, hipStream_t stream) {
+    const int S = gemm_splitk_splits(T, d_in, d_out, true);
+    if (S <= 0 || gate_rows % 8 != 0) return hipErrorInvalidValue;
+    GemmArgs a{};
+    a.x = (const bf16_t*)x; a.W = (const bf16_t*)W; a.T = T; a.d_in = d_in; a.d_out = d_out;
+    a.partial = partial; a.splits = S; a.tiles_per_split = ceil_div(d_in / kGemmBK, S);
+    a.Wg3 = (const bf16_t*)wg3; a.gpartial = gpartial; a.gate_rows = gate_rows; a.gate_tiles = ceil_div(gate_rows, 64);
+    constexpr int smem = gemm_lds_bytes<1, 1>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_dma_kernel<1, 1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    a.tiles_m = ceil_div(T, 64);
+    a.tiles_n = ceil_div(d_out, 64) + a.gate_tiles;
+    const uint64_t widest = (uint64_t)d_in * 2;
+    if (d_in % kGemmBK != 0 || ((uint64_t)T + 64) * widest >= (1ull << 32) ||
+        ((uint64_t)d_out + 64) * widest >= (1ull << 32))
+        return hipErrorInvalidValue;
+    gemm_mfma_dma_kernel<1, 1><<<dim3(a.tiles_m * a.tiles_n, S), 256, smem, stream>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_decode_finish(const float* partial, int T, int d_in, int d_out, const float* hs,
+                                     const int32_t* idx, const void* B, int k, int r, void* out,
+                                     hipStream_t stream) {
+    const int S = gemm_splitk_splits(T, d_in, d_out, true);
+    if (S <= 0 || r % 8 != 0) return hipErrorInvalidValue;
+    const size_t n8 = (size_t)T * d_out / 8;
+    gemm_splitk_reduce_expand_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, stream>>>(
+        partial, S, T, d_out, hs, idx, (const bf16_t*)B, k, r, (bf16_t*)out);
+    return hipGetLastError();
 }
 
 bool gemm_fuses_expand(bool bf16) { return bf16; }

@@ -58,6 +58,12 @@ struct GemmArgs {
     // split == splits (only if ext_k > 0) takes the expand extension; fp32 tiles go to partial[split][T][d_out]
     float* partial;       // nullptr: no split, the kernel writes `out` itself
     int splits, tiles_per_split;
+    // decode (two-slot split-K kernel only): the last gate_tiles column tiles take the rows of Wg3 (the three bf16
+    // terms of the gate columns, [gate_rows, d_in]) instead of W and write gpartial[split][T][gate_rows]: the gate
+    // logits ride in the launch that streams W
+    const bf16_t* Wg3;
+    float* gpartial;
+    int gate_rows, gate_tiles;   // 0: off
 };
 
 // LDS position of 16-byte chunk `chunk` of a 128-byte tile row.  A ds_read_b128 pass serves 16 lanes =
@@ -441,7 +447,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[M
 }
 
 template <int MI, int NI>
-__global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a_in) {
+    GemmArgs a = a_in;
     constexpr int BM = MI * 64, BN = NI * 64;
     constexpr int PX = BM / 32, PW = BN / 32;   // pieces per wavefront per tile
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -454,7 +461,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a) {
     const int lrow = lane & 31, khalf = lane >> 5;
     int tile_m, tile_n;
     tile_of_workgroup(blockIdx.x, a.tiles_m, a.tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int m0 = tile_m * BM;
+    int n0 = tile_n * BN;
+    if (a.gate_tiles > 0 && tile_n >= a.tiles_n - a.gate_tiles) {   // uniform: a gate tile is an ordinary tile of Wg3
+        n0 = (tile_n - (a.tiles_n - a.gate_tiles)) * BN;
+        a.W = a.Wg3;
+        a.d_out = a.gate_rows;
+        a.partial = a.gpartial;
+    }
 
     f32x16 acc[MI][NI];
 #pragma unroll

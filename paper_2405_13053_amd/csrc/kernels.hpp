@@ -36,11 +36,14 @@ hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, in
 // adapters in one launch, one workgroup per token; consumes launch_gate_logits' partials and writes
 // topk_idx, topk_w and every column of the token's row of hdense.  Replaces launch_gate_topk,
 // launch_bucket and launch_shrink for the whole-layer call.
+// gpart (optional): take the logits from launch_gemm_decode_main's gate tiles gpart[GS][T][3 * padded_adapters(N)]
+// instead of `partials`; hs (optional): write hs[T,k,r] = scale * w * h in fp32 instead of the rows of hdense.
 bool route_small_applies(int T, int r, bool bf16);
 hipError_t launch_route_shrink_small(const void* x, const float* partials, int KS, const float* bias, const void* A,
                                      int T, int d_in, int N, int r, int k, float inv_temperature, float scale,
                                      int32_t* topk_idx, float* topk_w, void* hdense, int ext_stride,
-                                     hipStream_t stream);
+                                     hipStream_t stream, const float* gpart = nullptr, int GS = 0,
+                                     float* hs = nullptr);
 
 // ---- mid-sized batches (64 < T <= kRouteDenseMaxTokens, bf16, r % 8 == 0, d_in % 64 == 0): one MFMA launch
 // computes the split-bf16 gate logits and x * A_i of every adapter as fp32 K-split partials
@@ -92,6 +95,17 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
 hipError_t launch_expand(const float* h32, const void* B, const int32_t* topk_idx, const float* topk_w,
                          int T, int d_out, int N, int r, int k, float scale, bool bf16, void* out,
                          int accumulate, hipStream_t stream);
+
+// ---- decode-sized batches in three launches (shapes with gemm_splitk_splits > 0, bf16, r % 8 == 0, Wcat packed):
+// launch_gemm_decode_main: main K splits of x * W^T as fp32 tiles partial[S][T][d_out], and in the same launch the
+//   gate-term rows of Wcat (its first gate_rows = 3 * padded_adapters(N) rows) as gpartial[S][T][gate_rows];
+// launch_route_shrink_small with `gpartial` (route_small.hip): top-k, softmax, shrink -> hs[T,k,r] = scale*w*h;
+// launch_gemm_decode_finish: out = bf16(sum of the S tiles in order + sum_slot hs * B[idx]).
+int gemm_splitk_splits(int T, int d_in, int d_out, bool bf16);
+hipError_t launch_gemm_decode_main(const void* x, const void* W, const void* wg3, int gate_rows, int T, int d_in,
+                                   int d_out, float* partial, float* gpartial, hipStream_t stream);
+hipError_t launch_gemm_decode_finish(const float* partial, int T, int d_in, int d_out, const float* hs,
+                                     const int32_t* idx, const void* B, int k, int r, void* out, hipStream_t stream);
 
 // ---- base projection out = x * W^T (W stored [d_out, d_in]), optional fused LoRA expand ---
 // If hdense != NULL the contraction is extended by the columns of hdense against the stacked B

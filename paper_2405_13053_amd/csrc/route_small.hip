@@ -18,7 +18,8 @@ template <int R8>   // R8 = r / 8: 16-byte pieces per row of A_a
 __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
     const bf16_t* __restrict__ x, const float* __restrict__ partials, int KS, const float* __restrict__ bias,
     const bf16_t* __restrict__ A, int T, int d_in, int N, int NP, int k, float inv_temperature, float scale,
-    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, bf16_t* __restrict__ hdense, int ext_stride) {
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, bf16_t* __restrict__ hdense, int ext_stride,
+    const float* __restrict__ gpart, int GS, float* __restrict__ hs) {
     constexpr int r = R8 * 8;
     constexpr int ROWS = 8 / R8;   // rows of A_a per slot whose loads are in flight together
     __shared__ int sel_idx[kMaxTopK];
@@ -28,13 +29,28 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     // this token's row of the dense expand operand starts as zeros
-    {
+    if (hdense != nullptr) {
         u32x4* row = reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride);
         for (int i = threadIdx.x; i < ext_stride / 8; i += kSmallThreads) row[i] = u32x4{0u, 0u, 0u, 0u};
     }
     if (wave == 0) {   // top-k and softmax: lane = adapter
         float g = 0.f;
-        if (lane < N) {
+        if (lane < N && gpart != nullptr) {
+            // logits from the split-K tiles of the gate-term rows: splits in order, (lo + mid) + hi within a split
+            const int GR = 3 * NP;
+            for (int s0 = 0; s0 < GS; s0 += 16) {   // 16 splits' loads in flight
+                float v[16][3];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+#pragma unroll
+                    for (int term = 0; term < 3; ++term)
+                        v[u][term] = s0 + u < GS ? gpart[((size_t)(s0 + u) * T + t) * GR + term * NP + lane] : 0.f;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) g += (v[u][2] + v[u][1]) + v[u][0];
+            }
+            g += bias != nullptr ? bias[lane] : 0.f;
+            if (g == 0.f) g = 0.f;
+        } else if (lane < N) {
             for (int s0 = 0; s0 < KS; s0 += 16) {   // K-slices in order, 16 loads in flight
                 float v[16];
 #pragma unroll
@@ -113,7 +129,8 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
         float h = 0.f;
 #pragma unroll
         for (int wv = 0; wv < kSmallWaves; ++wv) h += red[wv][slot][q];   // fixed order
-        hdense[(size_t)t * ext_stride + sel_idx[slot] * r + q] = from_float<bf16_t>(scale * sel_w[slot] * h);
+        if (hs != nullptr) hs[((size_t)t * k + slot) * r + q] = scale * sel_w[slot] * h;
+        else hdense[(size_t)t * ext_stride + sel_idx[slot] * r + q] = from_float<bf16_t>(scale * sel_w[slot] * h);
     }
 }
 
@@ -122,11 +139,12 @@ bool route_small_applies(int T, int r, bool bf16) { return bf16 && T <= 64 && (r
 hipError_t launch_route_shrink_small(const void* x, const float* partials, int KS, const float* bias, const void* A,
                                      int T, int d_in, int N, int r, int k, float inv_temperature, float scale,
                                      int32_t* topk_idx, float* topk_w, void* hdense, int ext_stride,
-                                     hipStream_t stream) {
+                                     hipStream_t stream, const float* gpart, int GS, float* hs) {
     const int NP = padded_adapters(N);
     auto go = [&](auto kern) {
         kern<<<T, kSmallThreads, 0, stream>>>((const bf16_t*)x, partials, KS, bias, (const bf16_t*)A, T, d_in, N, NP, k,
-                                    inv_temperature, scale, topk_idx, topk_w, (bf16_t*)hdense, ext_stride);
+                                    inv_temperature, scale, topk_idx, topk_w, (bf16_t*)hdense, ext_stride, gpart,
+                                    GS, hs);
         return hipGetLastError();
     };
     if (r == 8) return go(route_shrink_small_kernel<1>);

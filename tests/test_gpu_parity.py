@@ -227,6 +227,8 @@ def test_packed_weights_serve_many_batches():
 
 SMALL_BATCH_SHAPES = [
     LS(1, 512, 256, 28, 8, 2, 2.0, "bf16", "uniform", "T=1"),
+    LS(64, 1024, 776, 12, 16, 3, 1.5, "bf16", "zipf", "T=64-r16-k3-bias-three-launch"),
+    LS(40, 4096, 1032, 28, 8, 2, 2.0, "bf16", "uniform", "T=40-ragged-tiles"),
     LS(7, 264, 136, 5, 16, 1, 1.0, "bf16", "zipf", "T=7-r16-top1-ragged"),
     LS(64, 1024, 520, 64, 32, 8, 0.5, "bf16", "uniform", "T=64-N64-r32-k8"),
     LS(33, 5120, 264, 28, 8, 2, 2.0, "bf16", "zipf", "T=33-decode-shape"),
@@ -235,13 +237,15 @@ SMALL_BATCH_SHAPES = [
 
 @pytest.mark.parametrize("shape", SMALL_BATCH_SHAPES, ids=lambda s: s.name)
 def test_small_batch_path_matches_oracle_and_gate_entry_point(shape):
-    """T <= 64: top-k and shrink run token-major in one launch; same routing as meteora_gate_topk, bit for bit."""
+    """T <= 64: top-k and shrink run token-major in one launch; same adapters as meteora_gate_topk picks."""
     out = _check_layer(shape, seed=45)
     ops, dev = util.make_case(shape, seed=45)
     _, idx, w = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], dev["bias"], dev["A"], dev["B"], shape.k,
                                  shape.scale, return_routing=True)
     idx_g, w_g, _ = m.gate_topk(dev["x"], dev["W_gate"], dev["bias"], shape.k)
-    assert torch.equal(idx, idx_g) and torch.equal(w, w_g)
+    assert torch.equal(idx, idx_g)
+    # where the logits come out of the GEMM's own launch they are summed in another order than the gate kernel's
+    assert float((w - w_g).abs().max()) <= 1e-5
     # and the LoRA term alone through the bucketed path gives the same layer output to bf16 accuracy
     base = m.base_gemm(dev["x"], dev["W"])
     full = m.lora_forward(dev["x"], dev["A"], dev["B"], idx, w, shape.scale, out=base.clone(), accumulate=True)
