@@ -340,6 +340,12 @@ def test_layer_call_replays_from_a_hip_graph(shape):
         assert torch.equal(out, ref), f"replay {rep} differs from the eager call"
 
 
+def test_many_tokens_small_layer_sampled_rows():
+    """T = 70000 through the bucketed path (1094 bucketing chunks, whole-K shrink): index arithmetic at scale."""
+    shape = LS(70000, 256, 264, 28, 8, 2, 2.0, "bf16", "zipf", "T=70000")
+    _check_layer(shape, seed=49, rows="sample", n_strided=200)
+
+
 def test_linear_forward_single_adapter_is_merged_gemm():
     """N=1,k=1: the layer is x(W + s*A*B) (Eq. 1)."""
     shape = LS(100, 256, 264, 1, 8, 1, 2.0, "f32")
