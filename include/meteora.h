@@ -169,6 +169,41 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
                                              void* ws, size_t ws_bytes, meteora_stream stream);
 
 /*
+ * Several MeteoRA layers on the same input: the layers of a decoder block that share x (q/k/v, and
+ * gate/up; Sec. 4.1 embeds the adapters in all seven linear layers) each have their own base weight,
+ * gate and adapters but the same T, d_in, N, r, k and scale.  The result is that of one
+ * meteora_linear_forward_packed call per member (same routing; outputs equal to bf16 accuracy, the
+ * split-K sums may run in another order).  For decode-sized batches (T <= 64, bf16, packed weights,
+ * at most 4 members) the whole group runs in three launches instead of three per layer; otherwise the
+ * members run one after the other.
+ *   members  host array of G descriptors; every pointer in it is a device pointer with the meaning and
+ *            alignment it has in meteora_linear_forward_packed (packed may be NULL: that member is then
+ *            repacked into the workspace on every call, and the group runs member by member).
+ *   ws       at least meteora_group_workspace_bytes(d_out[0..G), ...) bytes, 256-byte aligned.
+ * Errors as for meteora_linear_forward_packed; G < 1 or G > 64 is METEORA_ERR_INVALID_ARG.
+ */
+typedef struct {
+    const void* W;            /* [d_out, d_in] */
+    const float* W_gate;      /* [d_in, N] */
+    const float* gate_bias;   /* [N] or NULL */
+    const void* A;            /* [N, d_in, r] */
+    const void* B;            /* [N, r, d_out] */
+    const void* packed;       /* blob of meteora_pack_weights for this member, or NULL */
+    size_t packed_bytes;
+    int d_out;
+    void* out;                /* [T, d_out] */
+    int32_t* topk_idx_out;    /* [T,k] or NULL */
+    float* topk_w_out;        /* [T,k] or NULL */
+} meteora_group_member;
+
+size_t meteora_group_workspace_bytes(const int* d_out /*host, [G]*/, int G, int T, int d_in, int N, int r, int k,
+                                     meteora_dtype dt);
+
+meteora_status meteora_linear_forward_group(const void* x, const meteora_group_member* members /*host*/, int G,
+                                            int T, int d_in, int N, int r, int k, float scale, meteora_dtype dt,
+                                            void* ws, size_t ws_bytes, meteora_stream stream);
+
+/*
  * Base projection alone, first term of Eq. 1 / Eq. 2: out = x * W
  * (W stored [d_out, d_in]).  Exposed so the dense contraction can be checked
  * and timed on its own.

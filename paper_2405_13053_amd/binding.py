@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional, Tuple
+from typing import Optional, Sequence, Tuple
 
 import torch
 
@@ -62,6 +62,10 @@ def load_library():
     lib.meteora_linear_forward_packed.restype = i
     lib.meteora_linear_forward_packed.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, i, vp, vp,
                                                   vp, vp, sz, vp]
+    lib.meteora_group_workspace_bytes.restype = sz
+    lib.meteora_group_workspace_bytes.argtypes = [vp, i, i, i, i, i, i, i]
+    lib.meteora_linear_forward_group.restype = i
+    lib.meteora_linear_forward_group.argtypes = [vp, vp, i, i, i, i, i, i, f, i, vp, sz, vp]
     lib.meteora_base_gemm.restype = i
     lib.meteora_base_gemm.argtypes = [vp, vp, i, i, i, i, vp, vp]
     lib.meteora_stage_count.restype = i
@@ -222,6 +226,58 @@ def linear_forward(x, W, W_gate, gate_bias, A, B, k: int, scale: float, out: Opt
     if st != 0:
         raise MeteoraError(st, "meteora_linear_forward")
     return (out, idx, w) if return_routing else out
+
+
+class GroupMember(ctypes.Structure):
+    """meteora_group_member of include/meteora.h."""
+    _fields_ = [("W", ctypes.c_void_p), ("W_gate", ctypes.c_void_p), ("gate_bias", ctypes.c_void_p),
+                ("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("packed", ctypes.c_void_p),
+                ("packed_bytes", ctypes.c_size_t), ("d_out", ctypes.c_int), ("out", ctypes.c_void_p),
+                ("topk_idx_out", ctypes.c_void_p), ("topk_w_out", ctypes.c_void_p)]
+
+
+def group_workspace_bytes(d_outs: Sequence[int], T: int, d_in: int, N: int, r: int, k: int, dtype) -> int:
+    """meteora_group_workspace_bytes."""
+    arr = (ctypes.c_int * len(d_outs))(*d_outs)
+    dt = BF16 if dtype in (torch.bfloat16, BF16, "bf16") else F32
+    return int(load_library().meteora_group_workspace_bytes(arr, len(d_outs), T, d_in, N, r, k, dt))
+
+
+def linear_forward_group(x, members, k: int, scale: float, ws: Optional[torch.Tensor] = None,
+                         return_routing: bool = False):
+    """meteora_linear_forward_group: layers that share x.  `members` is a sequence of dicts with W, W_gate,
+    gate_bias (or None), A, B, packed (or None) and optionally out; returns the list of outputs
+    (or of (out, idx, w) with return_routing)."""
+    T, d_in = x.shape
+    N, _, r = members[0]["A"].shape
+    _chk(x, "x")
+    arr = (GroupMember * len(members))()
+    keep, res = [], []
+    for g, mb in enumerate(members):
+        W, Wg, bias, A, B, packed = mb["W"], mb["W_gate"], mb.get("gate_bias"), mb["A"], mb["B"], mb.get("packed")
+        d_out = W.shape[0]
+        _chk(W, "W", x.dtype, (d_out, d_in)); _chk(Wg, "W_gate", torch.float32, (d_in, N))
+        _chk(bias, "gate_bias", torch.float32, (N,))
+        _chk(A, "A", x.dtype, (N, d_in, r)); _chk(B, "B", x.dtype, (N, r, d_out)); _chk(packed, "packed", torch.uint8)
+        out = mb.get("out")
+        if out is None:
+            out = torch.empty((T, d_out), dtype=x.dtype, device=x.device)
+        _chk(out, "out", x.dtype, (T, d_out))
+        idx = w = None
+        if return_routing:
+            idx = torch.empty((T, k), dtype=torch.int32, device=x.device)
+            w = torch.empty((T, k), dtype=torch.float32, device=x.device)
+        ptr = lambda t: None if t is None else t.data_ptr()
+        arr[g] = GroupMember(ptr(W), ptr(Wg), ptr(bias), ptr(A), ptr(B), ptr(packed),
+                             packed.numel() if packed is not None else 0, d_out, ptr(out), ptr(idx), ptr(w))
+        keep.append((out, idx, w))
+        res.append((out, idx, w) if return_routing else out)
+    ws = _ws(ws, group_workspace_bytes([mb["W"].shape[0] for mb in members], T, d_in, N, r, k, x.dtype), x.device)
+    st = load_library().meteora_linear_forward_group(_p(x), arr, len(members), T, d_in, N, r, k, float(scale), _dt(x),
+                                                     _p(ws), ws.numel(), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_linear_forward_group")
+    return res
 
 
 def base_gemm(x, W, out: Optional[torch.Tensor] = None):

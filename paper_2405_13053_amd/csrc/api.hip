@@ -396,21 +396,20 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
     if (decode3) {
         // decode-sized batch: the launch that streams W also computes the gate logits; then top-k, softmax and the
         // shrink of the selected adapters token by token; then the split-K reduction, which adds the expand
-        float* part = at<float>(ws, L.splitk);
-        float* gpart = at<float>(ws, L.gpart);
-        float* hs = at<float>(ws, L.h32);
-        const int S = gemm_splitk_splits(T, d_in, d_out, bf16);
+        const DecodeMember mem{W, pk.wcat, gate_bias, A, B, d_out, at<float>(ws, L.splitk), at<float>(ws, L.gpart),
+                               at<float>(ws, L.h32), idx, w, out};
+        const int gate_rows = 3 * padded_adapters(N);
+        const int S = gemm_group_splits(T, d_in, &d_out, 1, gate_rows);
         {
             StageScope sc(ST_GEMM, st, tslot);
-            METEORA_HIP(launch_gemm_decode_main(x, W, pk.wcat, 3 * padded_adapters(N), T, d_in, d_out, part, gpart, st));
+            METEORA_HIP(launch_gemm_decode_main(x, &mem, 1, gate_rows, S, T, d_in, st));
         }
         {
             StageScope sc(ST_SHRINK, st, tslot);
-            METEORA_HIP(launch_route_shrink_small(x, nullptr, 0, gate_bias, A, T, d_in, N, r, k, 1.0f, scale, idx, w,
-                                                  nullptr, L.ext_stride, st, gpart, S, hs));
+            METEORA_HIP(launch_route_shrink_small_group(x, &mem, 1, S, T, d_in, N, r, k, 1.0f, scale, st));
         }
         StageScope sc(ST_EXPAND, st, tslot);
-        METEORA_HIP(launch_gemm_decode_finish(part, T, d_in, d_out, hs, idx, B, k, r, out, st));
+        METEORA_HIP(launch_gemm_decode_finish(&mem, 1, S, T, k, r, st));
         return METEORA_OK;
     }
     if (dense) {
@@ -453,6 +452,123 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
     }
     return run_lora(x, W, A, B, idx, w, T, d_in, d_out, N, r, k, scale, bf16, out, 0, ws, L, pk, st, tslot, true);
 }
+
+}  // extern "C"
+
+// ---- a group of layers that share x ----------------------------------------------------------------------------
+namespace {
+
+// Fused form: decode-sized batch, every member on the three-launch path with packed weights.
+bool group_fused(const meteora_group_member* m, int G, int T, int d_in, int N, int r, bool bf16) {
+    if (G < 2 || G > kMaxDecodeGroup) return false;
+    for (int g = 0; g < G; ++g)
+        if (!m[g].packed || !decode_fused_applies(T, d_in, m[g].d_out, N, r, bf16)) return false;
+    return true;
+}
+
+struct GroupLayout { size_t partial[kMaxDecodeGroup], gpart[kMaxDecodeGroup], hs[kMaxDecodeGroup], idx[kMaxDecodeGroup],
+                            w[kMaxDecodeGroup], total; int S; };
+
+GroupLayout group_layout(const int* d_out, int G, int T, int d_in, int N, int r, int k) {
+    GroupLayout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const int gate_rows = 3 * padded_adapters(N);
+    L.S = gemm_group_splits(T, d_in, d_out, G, gate_rows);
+    for (int g = 0; g < G; ++g) {
+        L.partial[g] = take((size_t)L.S * T * d_out[g] * sizeof(float));
+        L.gpart[g] = take((size_t)L.S * T * gate_rows * sizeof(float));
+        L.hs[g] = take((size_t)T * k * r * sizeof(float));
+        L.idx[g] = take((size_t)T * k * sizeof(int32_t));
+        L.w[g] = take((size_t)T * k * sizeof(float));
+    }
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+
+extern "C" size_t meteora_group_workspace_bytes(const int* d_out, int G, int T, int d_in, int N, int r, int k,
+                                                meteora_dtype dt) {
+    if (!d_out || G < 1 || G > 64) return 0;
+    if (dt != METEORA_F32 && dt != METEORA_BF16) return 0;
+    const bool bf16 = dt == METEORA_BF16;
+    size_t need = 0;
+    bool fused = G >= 2 && G <= kMaxDecodeGroup;
+    for (int g = 0; g < G; ++g) {
+        const size_t one = meteora_workspace_bytes(T, d_in, d_out[g], N, r, k, dt);
+        if (one == 0) return 0;
+        need = one > need ? one : need;
+        fused = fused && decode_fused_applies(T, d_in, d_out[g], N, r, bf16);
+    }
+    if (fused) {
+        const size_t f = group_layout(d_out, G, T, d_in, N, r, k).total + 256;
+        need = f > need ? f : need;
+    }
+    return need;
+}
+
+extern "C" meteora_status meteora_linear_forward_group(const void* x, const meteora_group_member* members, int G, int T,
+                                                       int d_in, int N, int r, int k, float scale, meteora_dtype dt,
+                                                       void* ws, size_t ws_bytes, meteora_stream stream) {
+    if (!members || G < 1 || G > 64) return METEORA_ERR_INVALID_ARG;
+    if (dt != METEORA_F32 && dt != METEORA_BF16) return METEORA_ERR_UNSUPPORTED;
+    const bool bf16 = dt == METEORA_BF16;
+    int d_outs[64];
+    for (int g = 0; g < G; ++g) {
+        const meteora_group_member& m = members[g];
+        if (!m.W || !m.W_gate) return METEORA_ERR_INVALID_ARG;
+        const meteora_status s = check_lora_args(x, m.A, m.B, T, d_in, m.d_out, N, r, k, scale, dt, m.out);
+        if (s != METEORA_OK) return s;
+        if (!aligned16(m.W) || !aligned16(m.W_gate) || (m.gate_bias && !aligned4(m.gate_bias)) ||
+            (m.topk_idx_out && !aligned16(m.topk_idx_out)) || (m.topk_w_out && !aligned16(m.topk_w_out)))
+            return METEORA_ERR_UNSUPPORTED;
+        if (m.packed && (!aligned256(m.packed) ||
+                         m.packed_bytes < pack_layout(d_in, m.d_out, N, r, bf16).total))
+            return METEORA_ERR_WORKSPACE;
+        d_outs[g] = m.d_out;
+    }
+    if (!ws || !aligned256(ws) || ws_bytes < meteora_group_workspace_bytes(d_outs, G, T, d_in, N, r, k, dt))
+        return METEORA_ERR_WORKSPACE;
+    if (T == 0) return METEORA_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (!group_fused(members, G, T, d_in, N, r, bf16)) {
+        // the same result one layer after the other (they share the workspace, which the stream order allows)
+        for (int g = 0; g < G; ++g) {
+            const meteora_group_member& m = members[g];
+            const meteora_status s = meteora_linear_forward_packed(
+                x, m.W, m.W_gate, m.gate_bias, m.A, m.B, m.packed, m.packed_bytes, T, d_in, m.d_out, N, r, k, scale, dt,
+                m.out, m.topk_idx_out, m.topk_w_out, ws, ws_bytes, stream);
+            if (s != METEORA_OK) return s;
+        }
+        return METEORA_OK;
+    }
+    const GroupLayout L = group_layout(d_outs, G, T, d_in, N, r, k);
+    DecodeMember mem[kMaxDecodeGroup];
+    for (int g = 0; g < G; ++g) {
+        const meteora_group_member& m = members[g];
+        const PackLayout P = pack_layout(d_in, m.d_out, N, r, bf16);
+        mem[g] = DecodeMember{m.W, at<void>(const_cast<void*>(m.packed), P.wcat), m.gate_bias, m.A, m.B, m.d_out,
+                              at<float>(ws, L.partial[g]), at<float>(ws, L.gpart[g]), at<float>(ws, L.hs[g]),
+                              m.topk_idx_out ? m.topk_idx_out : at<int32_t>(ws, L.idx[g]),
+                              m.topk_w_out ? m.topk_w_out : at<float>(ws, L.w[g]), m.out};
+    }
+    const int gate_rows = 3 * padded_adapters(N);
+    const int tslot = timing_begin_call();
+    {
+        StageScope sc(ST_GEMM, st, tslot);
+        METEORA_HIP(launch_gemm_decode_main(x, mem, G, gate_rows, L.S, T, d_in, st));
+    }
+    {
+        StageScope sc(ST_SHRINK, st, tslot);
+        METEORA_HIP(launch_route_shrink_small_group(x, mem, G, L.S, T, d_in, N, r, k, 1.0f, scale, st));
+    }
+    StageScope sc(ST_EXPAND, st, tslot);
+    METEORA_HIP(launch_gemm_decode_finish(mem, G, L.S, T, k, r, st));
+    return METEORA_OK;
+}
+
+extern "C" {
 
 meteora_status meteora_linear_forward(const void* x, const void* W, const float* W_gate, const float* gate_bias,
                                       const void* A, const void* B, int T, int d_in, int d_out, int N, int r,

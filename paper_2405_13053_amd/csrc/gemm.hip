@@ -91,11 +91,31 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __
 //   out[t, c] = bf16( sum_s partial[s][t][c] + sum_slot sum_q hs[t][slot][q] * B[idx[t][slot]][q][c] ),
 // hs = scale * w * h.  A thread owns 8 consecutive columns of one token: B rows are read as 16-byte pieces,
 // coalesced across the threads of a token.
-__global__ __launch_bounds__(256) void gemm_splitk_reduce_expand_kernel(
-    const float* __restrict__ partial, int nsplit, int T, int d_out, const float* __restrict__ hs,
-    const int32_t* __restrict__ idx, const bf16_t* __restrict__ B, int k, int r, bf16_t* __restrict__ out) {
+struct ReduceExpandArgs {
+    struct Member {
+        const float* partial;   // [S][T][d_out]
+        const float* hs;        // [T,k,r]
+        const int32_t* idx;     // [T,k]
+        const bf16_t* B;        // [N,r,d_out]
+        bf16_t* out;            // [T,d_out]
+        int d_out, block0;      // first workgroup of this member
+    } m[kMaxDecodeGroup];
+    int G;
+};
+
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_expand_kernel(const ReduceExpandArgs ra, int nsplit, int T,
+                                                                        int k, int r) {
+    int g = 0;
+    for (int i = 1; i < ra.G; ++i)
+        if ((int)blockIdx.x >= ra.m[i].block0) g = i;   // uniform
+    const float* __restrict__ partial = ra.m[g].partial;
+    const float* __restrict__ hs = ra.m[g].hs;
+    const int32_t* __restrict__ idx = ra.m[g].idx;
+    const bf16_t* __restrict__ B = ra.m[g].B;
+    bf16_t* __restrict__ out = ra.m[g].out;
+    const int d_out = ra.m[g].d_out;
     const int c8 = d_out / 8;
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t i = (size_t)(blockIdx.x - ra.m[g].block0) * 256 + threadIdx.x;
     if (i >= (size_t)T * c8) return;
     const int t = (int)(i / c8), c = (int)(i - (size_t)t * c8) * 8;
     f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
@@ -257,15 +277,38 @@ hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int 
 
 // Decode in three launches: (1) the main K splits of x * W^T with the gate-term rows of Wcat as extra column
 // tiles (fp32 tiles into `partial` and `gpartial`), (2) routing and shrink on the gate tiles (route_small.hip),
-// (3) reduce + expand.  Shapes: gemm_splitk_splits(T, d_in, d_out) > 0.
-hipError_t launch_gemm_decode_main(const void* x, const void* W, const void* wg3, int gate_rows, int T, int d_in,
-                                   int d_out, float* partial, float* gpartial, hipStream_t stream) {
-    const int S = gemm_splitk_splits(T, d_in, d_out, true);
-    if (S <= 0 || gate_rows % 8 != 0) return hipErrorInvalidValue;
+// (3) reduce + expand.  A group of G layers that share x runs through the same three launches: the column tiles
+// of all their W and gate terms form one grid, all with the same number S of K splits.
+int gemm_group_splits(int T, int d_in, const int* d_out, int G, int gate_rows) {
+    if (T < 1 || T > 64 || d_in % kGemmBK != 0) return 0;
+    const int nk = d_in / kGemmBK;
+    if (nk < 8) return 0;
+    int tiles = 0;
+    for (int g = 0; g < G; ++g) tiles += ceil_div(d_out[g], 64) + ceil_div(gate_rows, 64);
+    if (G == 1) return gemm_splitk_splits(T, d_in, d_out[0], true);   // same split as the single-layer call
+    int S = ceil_div(768, tiles);
+    if (S > nk / 4) S = nk / 4;
+    return S < 1 ? 1 : S;
+}
+
+hipError_t launch_gemm_decode_main(const void* x, const DecodeMember* mem, int G, int gate_rows, int S, int T,
+                                   int d_in, hipStream_t stream) {
+    if (S <= 0 || gate_rows % 8 != 0 || G < 1 || 2 * G > GemmArgs::kMaxSegments) return hipErrorInvalidValue;
     GemmArgs a{};
-    a.x = (const bf16_t*)x; a.W = (const bf16_t*)W; a.T = T; a.d_in = d_in; a.d_out = d_out;
-    a.partial = partial; a.splits = S; a.tiles_per_split = ceil_div(d_in / kGemmBK, S);
-    a.Wg3 = (const bf16_t*)wg3; a.gpartial = gpartial; a.gate_rows = gate_rows; a.gate_tiles = ceil_div(gate_rows, 64);
+    a.x = (const bf16_t*)x; a.T = T; a.d_in = d_in;
+    a.splits = S; a.tiles_per_split = ceil_div(d_in / kGemmBK, S);
+    const uint64_t widest = (uint64_t)d_in * 2;
+    if (d_in % kGemmBK != 0 || ((uint64_t)T + 64) * widest >= (1ull << 32)) return hipErrorInvalidValue;
+    int tile0 = 0;
+    for (int g = 0; g < G; ++g) {
+        if (((uint64_t)mem[g].d_out + 64) * widest >= (1ull << 32)) return hipErrorInvalidValue;
+        a.seg[2 * g] = {(const bf16_t*)mem[g].W, mem[g].partial, mem[g].d_out, tile0};
+        tile0 += ceil_div(mem[g].d_out, 64);
+        a.seg[2 * g + 1] = {(const bf16_t*)mem[g].wg3, mem[g].gpartial, gate_rows, tile0};
+        tile0 += ceil_div(gate_rows, 64);
+    }
+    a.nseg = 2 * G;
+    a.W = a.seg[0].W; a.d_out = a.seg[0].rows; a.partial = a.seg[0].partial;   // replaced per workgroup
     constexpr int smem = gemm_lds_bytes<1, 1>();
     static bool attr_set = false;
     if (!attr_set) {
@@ -275,23 +318,23 @@ hipError_t launch_gemm_decode_main(const void* x, const void* W, const void* wg3
         attr_set = true;
     }
     a.tiles_m = ceil_div(T, 64);
-    a.tiles_n = ceil_div(d_out, 64) + a.gate_tiles;
-    const uint64_t widest = (uint64_t)d_in * 2;
-    if (d_in % kGemmBK != 0 || ((uint64_t)T + 64) * widest >= (1ull << 32) ||
-        ((uint64_t)d_out + 64) * widest >= (1ull << 32))
-        return hipErrorInvalidValue;
+    a.tiles_n = tile0;
     gemm_mfma_dma_kernel<1, 1><<<dim3(a.tiles_m * a.tiles_n, S), 256, smem, stream>>>(a);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_decode_finish(const float* partial, int T, int d_in, int d_out, const float* hs,
-                                     const int32_t* idx, const void* B, int k, int r, void* out,
+hipError_t launch_gemm_decode_finish(const DecodeMember* mem, int G, int S, int T, int k, int r,
                                      hipStream_t stream) {
-    const int S = gemm_splitk_splits(T, d_in, d_out, true);
-    if (S <= 0 || r % 8 != 0) return hipErrorInvalidValue;
-    const size_t n8 = (size_t)T * d_out / 8;
-    gemm_splitk_reduce_expand_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, stream>>>(
-        partial, S, T, d_out, hs, idx, (const bf16_t*)B, k, r, (bf16_t*)out);
+    if (S <= 0 || r % 8 != 0 || G < 1 || G > kMaxDecodeGroup) return hipErrorInvalidValue;
+    ReduceExpandArgs ra{};
+    unsigned blocks = 0;
+    for (int g = 0; g < G; ++g) {
+        ra.m[g] = {mem[g].partial, mem[g].hs, mem[g].idx, (const bf16_t*)mem[g].B, (bf16_t*)mem[g].out, mem[g].d_out,
+                   (int)blocks};
+        blocks += (unsigned)(((size_t)T * mem[g].d_out / 8 + 255) / 256);
+    }
+    ra.G = G;
+    gemm_splitk_reduce_expand_kernel<<<blocks, 256, 0, stream>>>(ra, S, T, k, r);
     return hipGetLastError();
 }
 

@@ -58,12 +58,18 @@ struct GemmArgs {
     // split == splits (only if ext_k > 0) takes the expand extension; fp32 tiles go to partial[split][T][d_out]
     float* partial;       // nullptr: no split, the kernel writes `out` itself
     int splits, tiles_per_split;
-    // decode (two-slot split-K kernel only): the last gate_tiles column tiles take the rows of Wg3 (the three bf16
-    // terms of the gate columns, [gate_rows, d_in]) instead of W and write gpartial[split][T][gate_rows]: the gate
-    // logits ride in the launch that streams W
-    const bf16_t* Wg3;
-    float* gpartial;
-    int gate_rows, gate_tiles;   // 0: off
+    // decode (two-slot split-K kernel only): the column tiles of one launch may belong to several row-major
+    // matrices that share x (the base weights of the layers of a group, and for each layer the gate-term rows of
+    // its Wcat, so the gate logits ride in the launch that streams W).  Segment e owns column tiles
+    // [seg[e].tile0, seg[e+1].tile0) and writes fp32 tiles seg[e].partial[split][T][seg[e].rows].  nseg = 0: off.
+    struct Segment {
+        const bf16_t* W;   // [rows, d_in]
+        float* partial;
+        int rows, tile0;
+    };
+    static constexpr int kMaxSegments = 8;
+    Segment seg[kMaxSegments];
+    int nseg;
 };
 
 // LDS position of 16-byte chunk `chunk` of a 128-byte tile row.  A ds_read_b128 pass serves 16 lanes =
@@ -463,11 +469,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma_kernel(const GemmArgs a_in)
     tile_of_workgroup(blockIdx.x, a.tiles_m, a.tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM;
     int n0 = tile_n * BN;
-    if (a.gate_tiles > 0 && tile_n >= a.tiles_n - a.gate_tiles) {   // uniform: a gate tile is an ordinary tile of Wg3
-        n0 = (tile_n - (a.tiles_n - a.gate_tiles)) * BN;
-        a.W = a.Wg3;
-        a.d_out = a.gate_rows;
-        a.partial = a.gpartial;
+    if (a.nseg > 0) {   // uniform: the tile is an ordinary tile of its segment's matrix
+        int e = 0;
+        for (int i = 1; i < a.nseg; ++i)
+            if (tile_n >= a_in.seg[i].tile0) e = i;
+        n0 = (tile_n - a_in.seg[e].tile0) * BN;
+        a.W = a_in.seg[e].W;
+        a.d_out = a_in.seg[e].rows;
+        a.partial = a_in.seg[e].partial;
     }
 
     f32x16 acc[MI][NI];

@@ -96,16 +96,35 @@ hipError_t launch_expand(const float* h32, const void* B, const int32_t* topk_id
                          int T, int d_out, int N, int r, int k, float scale, bool bf16, void* out,
                          int accumulate, hipStream_t stream);
 
-// ---- decode-sized batches in three launches (shapes with gemm_splitk_splits > 0, bf16, r % 8 == 0, Wcat packed):
-// launch_gemm_decode_main: main K splits of x * W^T as fp32 tiles partial[S][T][d_out], and in the same launch the
-//   gate-term rows of Wcat (its first gate_rows = 3 * padded_adapters(N) rows) as gpartial[S][T][gate_rows];
-// launch_route_shrink_small with `gpartial` (route_small.hip): top-k, softmax, shrink -> hs[T,k,r] = scale*w*h;
-// launch_gemm_decode_finish: out = bf16(sum of the S tiles in order + sum_slot hs * B[idx]).
+// ---- decode-sized batches in three launches (T <= 64, bf16, r % 8 == 0, Wcat packed), for one layer or for a
+// group of up to kMaxDecodeGroup layers that share x (q/k/v, gate/up):
+// launch_gemm_decode_main: the main K splits of x * W_g^T as fp32 tiles partial_g[S][T][d_out_g], and in the same
+//   launch the gate-term rows of each Wcat_g (its first gate_rows = 3 * padded_adapters(N) rows) as
+//   gpartial_g[S][T][gate_rows]; S = gemm_group_splits(...) for every member;
+// launch_route_shrink_small_group (route_small.hip): top-k, softmax, shrink -> idx_g, w_g, hs_g[T,k,r] = scale*w*h;
+// launch_gemm_decode_finish: out_g = bf16(sum of the S tiles in order + sum_slot hs_g * B_g[idx_g]).
+constexpr int kMaxDecodeGroup = 4;
+struct DecodeMember {
+    const void* W;        // [d_out, d_in]
+    const void* wg3;      // gate-term rows of Wcat
+    const float* bias;    // gate bias or NULL
+    const void* A;        // [N, d_in, r]
+    const void* B;        // [N, r, d_out]
+    int d_out;
+    float* partial;       // [S][T][d_out]
+    float* gpartial;      // [S][T][gate_rows]
+    float* hs;            // [T,k,r]
+    int32_t* idx;         // [T,k]
+    float* w;             // [T,k]
+    void* out;            // [T,d_out]
+};
 int gemm_splitk_splits(int T, int d_in, int d_out, bool bf16);
-hipError_t launch_gemm_decode_main(const void* x, const void* W, const void* wg3, int gate_rows, int T, int d_in,
-                                   int d_out, float* partial, float* gpartial, hipStream_t stream);
-hipError_t launch_gemm_decode_finish(const float* partial, int T, int d_in, int d_out, const float* hs,
-                                     const int32_t* idx, const void* B, int k, int r, void* out, hipStream_t stream);
+int gemm_group_splits(int T, int d_in, const int* d_out, int G, int gate_rows);   // 0: the shapes are not split
+hipError_t launch_gemm_decode_main(const void* x, const DecodeMember* mem, int G, int gate_rows, int S, int T,
+                                   int d_in, hipStream_t stream);
+hipError_t launch_route_shrink_small_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
+                                           int r, int k, float inv_temperature, float scale, hipStream_t stream);
+hipError_t launch_gemm_decode_finish(const DecodeMember* mem, int G, int S, int T, int k, int r, hipStream_t stream);
 
 // ---- base projection out = x * W^T (W stored [d_out, d_in]), optional fused LoRA expand ---
 // If hdense != NULL the contraction is extended by the columns of hdense against the stacked B

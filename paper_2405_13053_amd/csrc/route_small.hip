@@ -14,18 +14,43 @@ namespace meteora {
 constexpr int kSmallThreads = 1024;   // 16 wavefronts per token: the shrink is latency-bound, so many short loops
 constexpr int kSmallWaves = kSmallThreads / 64;
 
+// A group of layers that share x (same T, d_in, N, r, k): workgroup b serves token b % T of member b / T.
+struct RouteGroup {
+    struct Member {
+        const float* gpart;
+        const float* bias;
+        const bf16_t* A;
+        int32_t* idx;
+        float* w;
+        float* hs;
+    } m[kMaxDecodeGroup];
+    int G;   // 0: the kernel's own pointer arguments describe the one layer
+};
+
 template <int R8>   // R8 = r / 8: 16-byte pieces per row of A_a
 __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
-    const bf16_t* __restrict__ x, const float* __restrict__ partials, int KS, const float* __restrict__ bias,
-    const bf16_t* __restrict__ A, int T, int d_in, int N, int NP, int k, float inv_temperature, float scale,
-    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, bf16_t* __restrict__ hdense, int ext_stride,
-    const float* __restrict__ gpart, int GS, float* __restrict__ hs) {
+    const bf16_t* __restrict__ x, const float* __restrict__ partials, int KS, const float* bias_in,
+    const bf16_t* A_in, int T, int d_in, int N, int NP, int k, float inv_temperature, float scale,
+    int32_t* idx_in, float* w_in, bf16_t* __restrict__ hdense, int ext_stride,
+    const float* gpart_in, int GS, float* hs_in, const RouteGroup rg) {
     constexpr int r = R8 * 8;
     constexpr int ROWS = 8 / R8;   // rows of A_a per slot whose loads are in flight together
     __shared__ int sel_idx[kMaxTopK];
     __shared__ float sel_w[kMaxTopK];
     __shared__ float red[kSmallWaves][kMaxTopK][r];
-    const int t = blockIdx.x;
+    int t = blockIdx.x;
+    const float* __restrict__ bias = bias_in;
+    const bf16_t* __restrict__ A = A_in;
+    int32_t* __restrict__ topk_idx = idx_in;
+    float* __restrict__ topk_w = w_in;
+    const float* __restrict__ gpart = gpart_in;
+    float* __restrict__ hs = hs_in;
+    if (rg.G > 0) {   // uniform
+        const int g = blockIdx.x / T;
+        t = blockIdx.x - g * T;
+        bias = rg.m[g].bias; A = rg.m[g].A; topk_idx = rg.m[g].idx; topk_w = rg.m[g].w;
+        gpart = rg.m[g].gpart; hs = rg.m[g].hs;
+    }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     // this token's row of the dense expand operand starts as zeros
@@ -144,7 +169,27 @@ hipError_t launch_route_shrink_small(const void* x, const float* partials, int K
     auto go = [&](auto kern) {
         kern<<<T, kSmallThreads, 0, stream>>>((const bf16_t*)x, partials, KS, bias, (const bf16_t*)A, T, d_in, N, NP, k,
                                     inv_temperature, scale, topk_idx, topk_w, (bf16_t*)hdense, ext_stride, gpart,
-                                    GS, hs);
+                                    GS, hs, RouteGroup{});
+        return hipGetLastError();
+    };
+    if (r == 8) return go(route_shrink_small_kernel<1>);
+    if (r == 16) return go(route_shrink_small_kernel<2>);
+    if (r == 32) return go(route_shrink_small_kernel<4>);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_route_shrink_small_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
+                                           int r, int k, float inv_temperature, float scale, hipStream_t stream) {
+    if (G < 1 || G > kMaxDecodeGroup) return hipErrorInvalidValue;
+    const int NP = padded_adapters(N);
+    RouteGroup rg{};
+    for (int g = 0; g < G; ++g)
+        rg.m[g] = {mem[g].gpartial, mem[g].bias, (const bf16_t*)mem[g].A, mem[g].idx, mem[g].w, mem[g].hs};
+    rg.G = G;
+    auto go = [&](auto kern) {
+        kern<<<G * T, kSmallThreads, 0, stream>>>((const bf16_t*)x, nullptr, 0, nullptr, nullptr, T, d_in, N, NP, k,
+                                                  inv_temperature, scale, nullptr, nullptr, nullptr, 0, nullptr, S,
+                                                  nullptr, rg);
         return hipGetLastError();
     };
     if (r == 8) return go(route_shrink_small_kernel<1>);

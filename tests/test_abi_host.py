@@ -24,7 +24,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = sorted(set(re.findall(r"\b(meteora_[a-z_0-9]+)\s*\(", hdr)))
     assert {"meteora_gate_topk", "meteora_bucket_tokens", "meteora_lora_forward", "meteora_linear_forward",
             "meteora_base_gemm", "meteora_workspace_bytes", "meteora_packed_bytes", "meteora_pack_weights",
-            "meteora_linear_forward_packed"} <= set(names)
+            "meteora_linear_forward_packed", "meteora_linear_forward_group",
+            "meteora_group_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in meteora.h but not exported"
 
@@ -148,6 +149,39 @@ def test_pack_weights_validation(lib):
     assert linp(W=None) == INVALID
     assert linp(wsb=1024) == WORKSPACE
     assert linp(T=0) == OK
+
+
+def test_group_validation(lib):
+    """Grouped entry point: sizes and argument checks on the host (no launch on any error path)."""
+    from paper_2405_13053_amd.binding import GroupMember
+    d_outs = (ctypes.c_int * 3)(4096, 1024, 1024)
+    one = [lib.meteora_workspace_bytes(64, 4096, d, 28, 8, 2, BF16) for d in (4096, 1024, 1024)]
+    need = lib.meteora_group_workspace_bytes(d_outs, 3, 64, 4096, 28, 8, 2, BF16)
+    assert need >= max(one)                                # members may also run one after the other in it
+    assert lib.meteora_group_workspace_bytes(d_outs, 0, 64, 4096, 28, 8, 2, BF16) == 0
+    assert lib.meteora_group_workspace_bytes(None, 3, 64, 4096, 28, 8, 2, BF16) == 0
+    assert lib.meteora_group_workspace_bytes(d_outs, 3, 64, 4096, 65, 8, 2, BF16) == 0   # unsupported member
+
+    def member(W=P.value, Wg=P.value, A=P.value, B=P.value, pk=None, pkb=0, d_out=256, out=P.value):
+        return GroupMember(W, Wg, None, A, B, pk, pkb, d_out, out, None, None)
+
+    def call(ms, T=64, ws=WS, wsb=BIG, G=None, x=P):
+        arr = (GroupMember * len(ms))(*ms)
+        return lib.meteora_linear_forward_group(x, arr, len(ms) if G is None else G, T, 256, 4, 8, 2, 2.0, BF16, ws,
+                                                wsb, None)
+
+    two = [member(), member(d_out=264)]
+    assert call(two, T=0) == OK
+    assert call(two, G=0) == INVALID
+    assert call(two, x=None) == INVALID
+    assert call([member(), member(W=None)]) == INVALID
+    assert call([member(), member(out=None)]) == INVALID
+    assert call([member(), member(d_out=7)]) == UNSUPPORTED
+    assert call([member(), member(A=ODD.value)]) == UNSUPPORTED
+    assert call([member(), member(pk=WS.value, pkb=64)]) == WORKSPACE
+    assert call(two, wsb=1024) == WORKSPACE
+    assert call(two, ws=None) == WORKSPACE
+    assert lib.meteora_linear_forward_group(P, None, 2, 64, 256, 4, 8, 2, 2.0, BF16, WS, BIG, None) == INVALID
 
 
 def test_base_gemm_validation(lib):

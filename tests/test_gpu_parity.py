@@ -8,6 +8,7 @@ import pytest
 import torch
 
 import oracle
+from oracle import margin
 import paper_2405_13053_amd as m
 from gen import inputs as gen
 from tests import util
@@ -344,6 +345,53 @@ def test_many_tokens_small_layer_sampled_rows():
     """T = 70000 through the bucketed path (1094 bucketing chunks, whole-K shrink): index arithmetic at scale."""
     shape = LS(70000, 256, 264, 28, 8, 2, 2.0, "bf16", "zipf", "T=70000")
     _check_layer(shape, seed=49, rows="sample", n_strided=200)
+
+
+# ------------------------------------------------------------------ layers that share x (q/k/v, gate/up)
+def _group_case(T, d_in, d_outs, N, r, k, routing, seed):
+    shapes = [LS(T, d_in, d, N, r, k, 2.0, "bf16", routing, f"member{g}") for g, d in enumerate(d_outs)]
+    ops0, dev0 = util.make_case(shapes[0], seed, 0)
+    members, all_ops = [], []
+    for g, sh in enumerate(shapes):
+        ops = gen.make_layer(sh, seed, g)
+        ops["x"] = ops0["x"]                      # the members share the (margin-conditioned) input of member 0
+        dev = {n: util.to_dev(ops[n], torch.bfloat16) for n in ("W", "A", "B")}
+        dev["W_gate"] = util.to_dev(ops["W_gate"], torch.float32)
+        dev["gate_bias"] = util.to_dev(ops["bias"], torch.float32)
+        all_ops.append(ops)
+        members.append(dev)
+    # conditioning was done for member 0's gate only: drop the rows that are near-tied for any other member
+    keep = np.ones(T, dtype=bool)
+    for ops in all_ops[1:]:
+        bad = margin.small_margin_rows(oracle.gate_logits(ops["x"], ops["W_gate"], ops["bias"]), k, 1e-3)
+        keep[bad] = False
+    return shapes, all_ops, members, dev0["x"], np.nonzero(keep)[0]
+
+
+@pytest.mark.parametrize("T,d_in,d_outs,N,r,k,routing,packed", [
+    (33, 1024, (520, 136, 136), 28, 8, 2, "uniform", True),      # q/k/v-like, three launches for the group
+    (64, 4096, (1032, 1032), 12, 16, 3, "zipf", True),           # gate/up-like, r = 16, bias
+    (8, 512, (256, 264, 136, 72), 28, 8, 2, "uniform", True),    # four members
+    (33, 1024, (520, 136), 28, 8, 2, "uniform", False),          # not packed: member by member
+    (300, 512, (256, 264), 28, 8, 2, "uniform", True),           # not decode-sized: member by member
+], ids=["qkv", "gate-up-r16", "four", "unpacked", "T=300"])
+def test_group_call_matches_oracle_and_single_calls(T, d_in, d_outs, N, r, k, routing, packed):
+    shapes, all_ops, members, x, rows = _group_case(T, d_in, d_outs, N, r, k, routing, seed=50)
+    for mb in members:
+        mb["packed"] = m.pack_weights(mb["W_gate"], mb["A"], mb["B"]) if packed else None
+    res = m.linear_forward_group(x, members, k, 2.0, return_routing=True)
+    torch.cuda.synchronize()
+    for sh, ops, mb, (out, idx, w) in zip(shapes, all_ops, members, res):
+        ref = oracle.linear_forward(ops["x"], ops["W"], ops["W_gate"], ops["bias"], ops["A"], ops["B"], k, 2.0)
+        assert np.array_equal(_np(idx)[rows], ref["idx"][rows]), f"{sh.name}: routing differs from the oracle"
+        np.testing.assert_allclose(_np(w)[rows], ref["w"][rows], rtol=0, atol=1e-5)
+        y = out.to(torch.float64).cpu().numpy()
+        err = float(np.abs(y[rows] - ref["y"][rows]).max() / np.abs(ref["y"][rows]).max())
+        assert err <= util.tol(sh), f"{sh.name}: rel err {err:.3e}"
+        single, idx1, w1 = m.linear_forward(x, mb["W"], mb["W_gate"], mb["gate_bias"], mb["A"], mb["B"], k, 2.0,
+                                            return_routing=True, packed=mb["packed"])
+        assert torch.equal(idx[torch.from_numpy(rows).cuda()], idx1[torch.from_numpy(rows).cuda()])
+        assert util.rel_max_err(out, single.to(torch.float64).cpu().numpy()) <= 2 * util.tol(sh)
 
 
 def test_linear_forward_single_adapter_is_merged_gemm():
