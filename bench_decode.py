@@ -8,9 +8,10 @@ and 28 rank-8 adapters each (seeded synthetic values; attention, norms and the r
 not modelled, every layer gets an input of its own shape), so the 14 GB of base weights stream from
 HBM once per step as in real decoding.  It reports the step eagerly enqueued (224 calls of
 meteora_linear_forward_packed) and replayed from ONE captured HIP graph, which removes the host-side
-launch cost that dominates at this size.  Prints one JSON line.
+launch cost when it dominates.  --group sends the layers of a block that share an input (q/k/v, gate/up)
+through meteora_linear_forward_group, which runs each group in three launches.  Prints one JSON line.
 
-    python bench_decode.py [--tokens 64] [--blocks 32] [--steps 20] [--warmup 3]
+    python bench_decode.py [--tokens 64] [--blocks 32] [--steps 20] [--warmup 3] [--group]
 """
 import argparse
 import json
@@ -36,6 +37,8 @@ def main():
     ap.add_argument("--adapters", type=int, default=28)
     ap.add_argument("--rank", type=int, default=8)
     ap.add_argument("--topk", type=int, default=2)
+    ap.add_argument("--group", action="store_true",
+                    help="run the layers that share an input (q/k/v, gate/up) through meteora_linear_forward_group")
     args = ap.parse_args()
 
     import torch
@@ -52,7 +55,9 @@ def main():
     xs = {d_in: randn((T, d_in), 1.0) for d_in in (D, FFN)}
     calls, weight_bytes = [], 0
     ws_bytes = 0
+    groups = []   # per block: [q, k, v], [o], [gate, up], [down]
     for b in range(args.blocks):
+        block = []
         for name, d_in, d_out in LAYERS:
             W = randn((d_out, d_in), d_in ** -0.5)
             Wg = randn((d_in, N), d_in ** -0.5, torch.float32)
@@ -61,14 +66,24 @@ def main():
             packed = m.pack_weights(Wg, A, B)
             out = torch.empty((T, d_out), dtype=dt, device="cuda")
             calls.append((xs[d_in], W, Wg, A, B, packed, out))
+            block.append({"W": W, "W_gate": Wg, "gate_bias": None, "A": A, "B": B, "packed": packed, "out": out})
             weight_bytes += W.numel() * 2 + A.numel() * 2 + B.numel() * 2 + Wg.numel() * 4
             ws_bytes = max(ws_bytes, m.workspace_bytes(T, d_in, d_out, N, r, k, dt))
+        for members, d_in in ((block[0:3], D), (block[3:4], D), (block[4:6], D), (block[6:7], FFN)):
+            groups.append((xs[d_in], members))
+            ws_bytes = max(ws_bytes, m.group_workspace_bytes([mb["W"].shape[0] for mb in members], T, d_in, N, r, k, dt))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")   # the calls of a step run one after the other
     torch.cuda.synchronize()
 
-    def step():
+    def step_single():
         for x, W, Wg, A, B, packed, out in calls:
             m.linear_forward(x, W, Wg, None, A, B, k, s, out=out, ws=ws, packed=packed)
+
+    def step_group():
+        for x, members in groups:
+            m.linear_forward_group(x, members, k, s, ws=ws)
+
+    step = step_group if args.group else step_single
 
     def timed(fn):
         for _ in range(args.warmup):
@@ -107,7 +122,9 @@ def main():
         "metric": "decode step over all MeteoRA linears of a Llama3-8B-shaped model (tokens/s of the batch)",
         "config": {"workload": f"{args.blocks} blocks x 7 layers = {n_layers} MeteoRA layers per step, T={T} tokens, "
                                f"N={N}, r={r}, top-{k}, bf16, distinct weights per layer",
-                   "weights_streamed_per_step_GB": round(weight_bytes / 1e9, 2)},
+                   "weights_streamed_per_step_GB": round(weight_bytes / 1e9, 2),
+                   "calls": "meteora_linear_forward_group on [q,k,v], [o], [gate,up], [down]" if args.group
+                            else "meteora_linear_forward_packed per layer"},
         "eager": {"ms_per_step": eager_s * 1e3, "us_per_layer": eager_s * 1e6 / n_layers,
                   "tokens_per_s": T / eager_s, "host_enqueue_ms_per_step": enqueue_s * 1e3},
         "hip_graph": {"ms_per_step": graph_s * 1e3, "us_per_layer": graph_s * 1e6 / n_layers,
