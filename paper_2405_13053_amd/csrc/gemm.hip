@@ -168,7 +168,7 @@ int gemm_splitk_splits(int T, int d_in, int d_out, bool bf16) {
     if (!bf16 || T < 1 || T > 64 || d_in % kGemmBK != 0) return 0;
     const int tiles = ceil_div(T, 64) * ceil_div(d_out, 64), nk = d_in / kGemmBK;
     if (tiles >= 512 || nk < 8) return 0;
-    int S = ceil_div(768, tiles);
+    int S = ceil_div(512, tiles);   // about two workgroups per CU (measured: 384 to 1536 tried)
     if (S > nk / 4) S = nk / 4;
     return S >= 2 ? S : 0;
 }
@@ -286,7 +286,7 @@ int gemm_group_splits(int T, int d_in, const int* d_out, int G, int gate_rows) {
     int tiles = 0;
     for (int g = 0; g < G; ++g) tiles += ceil_div(d_out[g], 64) + ceil_div(gate_rows, 64);
     if (G == 1) return gemm_splitk_splits(T, d_in, d_out[0], true);   // same split as the single-layer call
-    int S = ceil_div(768, tiles);
+    int S = ceil_div(512, tiles);   // about two workgroups per CU (measured: 384 to 1536 tried)
     if (S > nk / 4) S = nk / 4;
     return S < 1 ? 1 : S;
 }
