@@ -136,15 +136,37 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
                         acc1[q + 1] = fmaf(xv[u], bf16_bits_to_float(v1[u][c][e] >> 16), acc1[q + 1]);
                     }
         }
-        // wavefront sums (fixed butterfly); the wavefronts are added through LDS below
+        // Wavefront sums of the 2r values a lane holds, in a fixed order.  A plain butterfly per value would cost
+        // 6 cross-lane exchanges for each of them (the 16 wavefronts of the workgroup queue on the CU's one
+        // exchange path: measured 3 us of a 12 us kernel).  Instead every halving step also halves the values a
+        // lane carries: lanes whose bit `off` is clear keep the lower half and take the partner's lower half,
+        // the others the upper halves; when one value per lane is left, plain steps finish the sum.  2r-1 (+1 or
+        // 2) exchanges instead of 12r.  Lane l ends up with value index = its bits 5, 4, ... read as a number.
+        float v[2 * r];
 #pragma unroll
-        for (int q = 0; q < r; ++q) {
-            float s0 = acc0[q], s1 = acc1[q];
+        for (int q = 0; q < r; ++q) { v[q] = acc0[q]; v[r + q] = acc1[q]; }
+        int cnt = 2 * r, off = 32;
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) { s0 += __shfl_xor(s0, off); s1 += __shfl_xor(s1, off); }
-            if (lane == 0) {
-                red[wave][slot0][q] = s0;
-                if (two) red[wave][slot0 + 1][q] = s1;
+        for (; cnt > 1 && off >= 1; cnt >>= 1, off >>= 1) {
+            const bool upper = (lane & off) != 0;
+#pragma unroll
+            for (int i = 0; i < cnt / 2; ++i) {
+                const float give = upper ? v[i] : v[i + cnt / 2];
+                const float keep = upper ? v[i + cnt / 2] : v[i];
+                v[i] = keep + __shfl_xor(give, off);
+            }
+        }
+#pragma unroll
+        for (; off >= 1; off >>= 1) v[0] += __shfl_xor(v[0], off);   // lanes that still hold the same value index
+        {
+            // halving steps done: log2(2r), capped at 6; the value index is the top bits of the lane number
+            constexpr int kSteps = (2 * r >= 64) ? 6 : (2 * r == 32 ? 5 : 4);
+            const int vi = lane >> (6 - kSteps);
+            if ((lane & ((1 << (6 - kSteps)) - 1)) == 0) {
+                if (2 * r <= 64) {
+                    const int slot = vi / r, q = vi - slot * r;
+                    if (slot == 0 || two) red[wave][slot0 + slot][q] = v[0];
+                }
             }
         }
     }
