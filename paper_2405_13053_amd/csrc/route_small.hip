@@ -38,6 +38,8 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
     __shared__ int sel_idx[kMaxTopK];
     __shared__ float sel_w[kMaxTopK];
     __shared__ float red[kSmallWaves][kMaxTopK][r];
+    __shared__ float gsum[2][kSmallWaves][kMaxAdapters];   // per-split logit terms, double-buffered over rounds
+    float glog = 0.f;
     int t = blockIdx.x;
     const float* __restrict__ bias = bias_in;
     const bf16_t* __restrict__ A = A_in;
@@ -58,22 +60,30 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
         u32x4* row = reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride);
         for (int i = threadIdx.x; i < ext_stride / 8; i += kSmallThreads) row[i] = u32x4{0u, 0u, 0u, 0u};
     }
+    // Logits from the split-K tiles of the gate-term rows: wavefront w fetches split w, w + 16, ... (every wavefront
+    // has its loads out at once), (lo + mid) + hi within a split; wavefront 0 then adds the splits in order.
+    if (gpart != nullptr) {
+        const int GR = 3 * NP;
+        for (int s0 = 0; s0 < GS; s0 += kSmallWaves) {
+            const int sp = s0 + wave;
+            float v = 0.f;
+            if (sp < GS && lane < N) {
+                const float* src = gpart + ((size_t)sp * T + t) * GR + lane;
+                const float hi = src[0], mid = src[NP], lo = src[2 * NP];
+                v = (lo + mid) + hi;
+            }
+            if (lane < kMaxAdapters) gsum[s0 / kSmallWaves & 1][wave][lane] = v;
+            __syncthreads();
+            if (wave == 0) {
+                const int n = min(kSmallWaves, GS - s0);
+                for (int u = 0; u < n; ++u) glog += gsum[s0 / kSmallWaves & 1][u][lane];
+            }
+        }
+    }
     if (wave == 0) {   // top-k and softmax: lane = adapter
         float g = 0.f;
         if (lane < N && gpart != nullptr) {
-            // logits from the split-K tiles of the gate-term rows: splits in order, (lo + mid) + hi within a split
-            const int GR = 3 * NP;
-            for (int s0 = 0; s0 < GS; s0 += 16) {   // 16 splits' loads in flight
-                float v[16][3];
-#pragma unroll
-                for (int u = 0; u < 16; ++u)
-#pragma unroll
-                    for (int term = 0; term < 3; ++term)
-                        v[u][term] = s0 + u < GS ? gpart[((size_t)(s0 + u) * T + t) * GR + term * NP + lane] : 0.f;
-#pragma unroll
-                for (int u = 0; u < 16; ++u) g += (v[u][2] + v[u][1]) + v[u][0];
-            }
-            g += bias != nullptr ? bias[lane] : 0.f;
+            g = glog + (bias != nullptr ? bias[lane] : 0.f);
             if (g == 0.f) g = 0.f;
         } else if (lane < N) {
             for (int s0 = 0; s0 < KS; s0 += 16) {   // K-slices in order, 16 loads in flight
