@@ -54,20 +54,19 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
     }
 
     {   // totals over all chunks and over the chunks before this one; wave w takes chunks w, w+4, ...
-        // (8 independent loads per step: the loop is bound by load latency, not by bandwidth)
+        // (32 independent loads per step, from clamped addresses so that no branch separates them: the loop is
+        // bound by load latency, not by bandwidth, and 16384 tokens are 256 chunks = two steps per wavefront)
         int tot = 0, bef = 0;
         if (lane < N) {
-            for (int cc0 = wave; cc0 < nchunks; cc0 += 32) {
-                int v[8];
+            for (int cc0 = wave; cc0 < nchunks; cc0 += 128) {
+                int v[32];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < 32; ++u) v[u] = chunk_counts[(size_t)min(cc0 + 4 * u, nchunks - 1) * N + lane];
+#pragma unroll
+                for (int u = 0; u < 32; ++u) {
                     const int cc = cc0 + 4 * u;
-                    v[u] = cc < nchunks ? chunk_counts[(size_t)cc * N + lane] : 0;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    tot += v[u];
-                    if (cc0 + 4 * u < c) bef += v[u];
+                    if (cc < nchunks) tot += v[u];
+                    if (cc < c) bef += v[u];
                 }
             }
         }

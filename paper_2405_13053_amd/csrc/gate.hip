@@ -72,19 +72,20 @@ __global__ __launch_bounds__(kTopkWaves * 64) void gate_topk_kernel(
 #pragma unroll
     for (int i = 0; i < G; ++i) { g[i] = 0.f; tok[i] = t0 + i * TPP + sub; }
     if (col < N) {
-        // fixed order over K-slices; 8 slices' loads are issued together (the loop is latency-bound),
-        // a missing slice adds +0.f, which leaves the sum unchanged
-        for (int s0 = 0; s0 < KS; s0 += 8) {
-            float v[8][G];
+        // fixed order over K-slices; 16 slices' loads are issued together, from clamped addresses so that no
+        // branch separates them (the loop is latency-bound); a slice past the end is not added
+        for (int s0 = 0; s0 < KS; s0 += 16) {
+            float v[16][G];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 16; ++u)
 #pragma unroll
                 for (int i = 0; i < G; ++i)
-                    v[u][i] = s0 + u < KS ? partials[((size_t)(s0 + u) * T + min(tok[i], T - 1)) * NP + col] : 0.f;
+                    v[u][i] = partials[((size_t)min(s0 + u, KS - 1) * T + min(tok[i], T - 1)) * NP + col];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 16; ++u)
 #pragma unroll
-                for (int i = 0; i < G; ++i) g[i] += v[u][i];
+                for (int i = 0; i < G; ++i)
+                    if (s0 + u < KS) g[i] += v[u][i];
         }
         const float b = bias != nullptr ? bias[col] : 0.f;
 #pragma unroll
