@@ -81,7 +81,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-                 "(the layer shards by tokens with no exchange step, see DESIGN.md)")
+                 "(the layer shards by tokens with no exchange step between the GPUs)")
 
     import numpy as np
     import torch
