@@ -262,6 +262,7 @@ DENSE_ROUTE_SHAPES = [
     LS(700, 512, 256, 7, 32, 7, 1.0, "bf16", "uniform", "T=700-r32-k=N"),
     LS(4097, 256, 136, 28, 8, 2, 2.0, "bf16", "uniform", "T=4097-wide-tiles"),
     LS(5000, 832, 264, 14, 16, 3, 2.0, "bf16", "zipf", "T=5000-r16-wide-tiles"),
+    LS(260, 384, 136, 28, 8, 8, 1.0, "bf16", "uniform", "T=260-k8"),
 ]
 
 
@@ -374,7 +375,8 @@ def _group_case(T, d_in, d_outs, N, r, k, routing, seed):
     (8, 512, (256, 264, 136, 72), 28, 8, 2, "uniform", True),    # four members
     (33, 1024, (520, 136), 28, 8, 2, "uniform", False),          # not packed: member by member
     (300, 512, (256, 264), 28, 8, 2, "uniform", True),           # not decode-sized: member by member
-], ids=["qkv", "gate-up-r16", "four", "unpacked", "T=300"])
+    (16, 512, (264,), 28, 8, 2, "zipf", True),                   # a group of one is the single-layer call
+], ids=["qkv", "gate-up-r16", "four", "unpacked", "T=300", "one"])
 def test_group_call_matches_oracle_and_single_calls(T, d_in, d_outs, N, r, k, routing, packed):
     shapes, all_ops, members, x, rows = _group_case(T, d_in, d_outs, N, r, k, routing, seed=50)
     for mb in members:
