@@ -246,9 +246,8 @@ int gemm_dense_splits(int T, int d_in, int rows) {
     return S < 1 ? 1 : S;
 }
 
-template <int MI, int NI, bool W3>
-static hipError_t launch_dense(GemmArgs a, hipStream_t stream) {
-    static_assert(W3, "the dense products use the three-deep W ring");
+template <int MI, int NI>
+static hipError_t launch_dense(GemmArgs a, hipStream_t stream) {   // three-deep W ring, fp32 split-K tiles
     constexpr int smem = gemm_w3_lds_bytes<MI, NI>();
     auto kern = &gemm_mfma_w3_kernel<MI, NI>;
     static bool attr_set = false;
@@ -272,7 +271,7 @@ hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int 
     a.partial = partial;
     a.splits = gemm_dense_splits(T, d_in, rows);
     a.tiles_per_split = ceil_div(d_in / kGemmBK, a.splits);
-    return dense_small_tiles(T) ? launch_dense<2, 2, true>(a, stream) : launch_dense<2, 5, true>(a, stream);
+    return dense_small_tiles(T) ? launch_dense<2, 2>(a, stream) : launch_dense<2, 5>(a, stream);
 }
 
 // Decode in three launches: (1) the main K splits of x * W^T with the gate-term rows of Wcat as extra column

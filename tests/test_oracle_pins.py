@@ -258,3 +258,95 @@ def test_margin_conditioning_removes_near_ties():
     o2 = gen.make_layer(shape, seed, only=("x", "W_gate"))
     margin.condition_margins(shape, seed, 0, o2["x"], o2["W_gate"], None, 1e-3)
     assert np.array_equal(o["x"], o2["x"])
+
+
+# ------------------------------------------------- gate gradients (Sec. 3.2, Eq. 4)
+def _loss_of_gate(ops, W_gate, bias, dy, idx, k, scale, labels, beta):
+    """The scalar that the gate gradients differentiate, built from the forward definitions only:
+    <dy, o> with o from Eq. 2 (selection idx held fixed, weights from Eq. 3 on the k selected logits in
+    double) plus beta * sum_t cross-entropy(softmax over all N logits, label_t)."""
+    x64 = ops["x"].astype(np.float64)
+    g = x64 @ W_gate + bias
+    gs = np.take_along_axis(g, idx.astype(np.int64), axis=1)
+    e = np.exp(gs - gs.max(axis=1, keepdims=True))
+    w = e / e.sum(axis=1, keepdims=True)
+    y = oracle.base(ops["x"], ops["W"]) + oracle.lora_delta(ops["x"], ops["A"], ops["B"], idx, w, scale)
+    loss = float((dy * y).sum())
+    if beta:
+        lse = np.log(np.exp(g - g.max(axis=1, keepdims=True)).sum(axis=1)) + g.max(axis=1)
+        loss += beta * float((lse - g[np.arange(g.shape[0]), labels]).sum())
+    return loss
+
+
+def _backward_case(seed, k, T=6, d_in=10, d_out=14, N=5, r=3):
+    from oracle import gate_backward as gb
+    shape, ops = _rand_layer(seed, T=T, d_in=d_in, d_out=d_out, N=N, r=r, k=k)
+    rng = np.random.default_rng(seed + 100)
+    dy = rng.standard_normal((T, d_out))
+    labels = rng.integers(0, N, size=T)
+    bias = rng.standard_normal(N).astype(np.float32) * np.float32(0.3)
+    return gb, shape, ops, dy, labels, bias
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 5])
+@pytest.mark.parametrize("beta", [0.0, 0.7])
+def test_gate_backward_matches_finite_differences_of_the_forward(k, beta):
+    gb, shape, ops, dy, labels, bias = _backward_case(31 + k, k)
+    res = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], k, shape.scale, labels, beta)
+    # the selection must not change under the probes below: every gap among ranks 1..k+1 is far above them
+    g = oracle.gate_logits(ops["x"], ops["W_gate"], bias)
+    top = -np.sort(-g, axis=1)[:, :min(k + 1, g.shape[1])]
+    assert (top[:, :-1] - top[:, 1:]).min() > 1e-3
+    Wg64, b64 = ops["W_gate"].astype(np.float64), bias.astype(np.float64)
+    eps = 1e-6
+    rng = np.random.default_rng(5)
+    for _ in range(12):
+        i, n = int(rng.integers(0, Wg64.shape[0])), int(rng.integers(0, Wg64.shape[1]))
+        Wp, Wm = Wg64.copy(), Wg64.copy()
+        Wp[i, n] += eps
+        Wm[i, n] -= eps
+        fd = (_loss_of_gate(ops, Wp, b64, dy, res["idx"], k, shape.scale, labels, beta) -
+              _loss_of_gate(ops, Wm, b64, dy, res["idx"], k, shape.scale, labels, beta)) / (2 * eps)
+        assert abs(fd - res["dW_gate"][i, n]) <= 1e-5 * max(1.0, abs(fd)), (i, n, fd, res["dW_gate"][i, n])
+    for n in range(b64.size):
+        bp, bm = b64.copy(), b64.copy()
+        bp[n] += eps
+        bm[n] -= eps
+        fd = (_loss_of_gate(ops, Wg64, bp, dy, res["idx"], k, shape.scale, labels, beta) -
+              _loss_of_gate(ops, Wg64, bm, dy, res["idx"], k, shape.scale, labels, beta)) / (2 * eps)
+        assert abs(fd - res["dbias"][n]) <= 1e-5 * max(1.0, abs(fd)), (n, fd, res["dbias"][n])
+
+
+def test_gate_backward_top1_has_no_language_model_part():
+    """App. "Top-1 strategy": with k = 1 the weight is the constant 1, the output does not depend on the gate,
+    so only the classification loss reaches it; with beta = 0 every gradient is exactly zero."""
+    gb, shape, ops, dy, labels, bias = _backward_case(41, 1)
+    res = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], 1, shape.scale, labels, 0.0)
+    assert not res["dW_gate"].any() and not res["dbias"].any()
+    res = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], 1, shape.scale, labels, 0.5)
+    g = oracle.gate_logits(ops["x"], ops["W_gate"], bias).astype(np.float32).astype(np.float64)
+    p = np.exp(g - g.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    p[np.arange(len(labels)), labels] -= 1.0
+    np.testing.assert_allclose(res["d_logits"], 0.5 * p, rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("k", [2, 4])
+def test_gate_backward_invariants(k):
+    """Both softmaxes are shift invariant, so each token's logit gradient sums to zero; unselected adapters get
+    only the classification part; dW_gate is the outer-product sum of x and d_logits."""
+    gb, shape, ops, dy, labels, bias = _backward_case(51 + k, k)
+    res = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], k, shape.scale, labels, 0.3)
+    assert np.abs(res["d_logits"].sum(axis=1)).max() < 1e-12
+    assert np.abs(res["dbias"].sum()) < 1e-12
+    lm_only = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], k, shape.scale, None, 0.0)
+    sel = np.zeros_like(lm_only["d_logits"], dtype=bool)
+    np.put_along_axis(sel, lm_only["idx"].astype(np.int64), True, axis=1)
+    assert not lm_only["d_logits"][~sel].any()
+    acc = np.zeros_like(res["dW_gate"])
+    for t in range(ops["x"].shape[0]):
+        acc += np.outer(ops["x"][t].astype(np.float64), res["d_logits"][t])
+    np.testing.assert_allclose(res["dW_gate"], acc, rtol=1e-12, atol=1e-12)
+    # scaling dy scales the language-model part linearly
+    twice = gb.gate_backward(ops["x"], 2 * dy, ops["W_gate"], bias, ops["A"], ops["B"], k, shape.scale, None, 0.0)
+    np.testing.assert_allclose(twice["dW_gate"], 2 * lm_only["dW_gate"], rtol=1e-12, atol=1e-12)
