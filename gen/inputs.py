@@ -32,7 +32,7 @@ from typing import Dict, Optional
 
 import numpy as np
 
-_TAGS = {"x": 1, "W": 2, "W_gate": 3, "A": 4, "B": 5}
+_TAGS = {"x": 1, "W": 2, "W_gate": 3, "A": 4, "B": 5, "dy": 6, "labels": 7}
 
 
 @dataclasses.dataclass(frozen=True)
@@ -117,6 +117,18 @@ def redraw_rows(x: np.ndarray, rows: np.ndarray, shape: LayerShape, seed: int,
         g = _stream(seed, _TAGS["x"] | (int(t) + 1) << 8, layer, redraw=attempt)
         v = g.standard_normal(size=(shape.d_in,), dtype=np.float32)
         x[t, :] = round_to_bf16(v) if shape.dtype == "bf16" else v
+
+
+def make_training_signals(shape: LayerShape, seed: int, layer: int = 0):
+    """Inputs of a gate-training step on this layer (Sec. 3.2): the upstream gradient dy[T, d_out] ~ N(0, 1/d_out)
+    in the storage dtype, and per-token task labels: tokens come in runs of 16 with one task each (a sample of
+    the balanced training set is one task's), every 11th run unlabelled (-1)."""
+    dy = _normal(seed, _TAGS["dy"], layer, (shape.T, shape.d_out), 1.0 / math.sqrt(shape.d_out), shape.dtype)
+    runs = (shape.T + 15) // 16
+    per_run = _stream(seed, _TAGS["labels"], layer).integers(0, shape.N, size=runs, dtype=np.int32)
+    per_run[10::11] = -1
+    labels = np.repeat(per_run, 16)[:shape.T].astype(np.int32)
+    return dy, labels
 
 
 # --------------------------------------------------------------------------

@@ -204,6 +204,37 @@ meteora_status meteora_linear_forward_group(const void* x, const meteora_group_m
                                             void* ws, size_t ws_bytes, meteora_stream stream);
 
 /*
+ * Gradients of the gate of one module for its training (Sec. 3.2, Eq. 4; App. "Top-k strategy"): W, A and B
+ * stay fixed, the loss reaches W_gate and gate_bias
+ *   - through the output: dy[T,d_out] = dL_lm/do (storage type dt).  With v_j = scale * (x*A_a)*B_a,
+ *     a = topk_idx[t,j]:  dL/dw_j = <dy[t], v_j>,  dL/dg_a = w_j * (dL/dw_j - sum_i w_i * dL/dw_i)
+ *     (softmax of Eq. 3 over the k selected; the selection itself carries no gradient; zero for k = 1);
+ *   - through the LoRA-classification loss of the module, beta * sum_t CE(softmax over all N logits of token
+ *     t, labels[t]):  dL/dg_n += beta * (softmax(g)_n - [n == labels[t]]).  labels[t] outside [0, N) gives
+ *     token t no classification part; labels == NULL or beta == 0 leaves the term out.
+ * Outputs (fp32, overwritten):  d_logits[T,N] (may be NULL),  dW_gate[d_in,N] = x^T * d_logits,
+ * dbias[N] = sum_t d_logits[t] (may be NULL).
+ * The logits are recomputed from x and the packed weights exactly as the forward call for 64 < T <= 8192
+ * computes them.  topk_idx / topk_w (both or neither): the routing the forward call returned, to be used
+ * as it is; NULL ranks again from the recomputed logits (the same routing as that forward path's).
+ * `packed` is the blob of meteora_pack_weights for these adapters; B is the stacked [N,r,d_out] tensor.
+ * Limits: dt == METEORA_BF16, N <= 32, r % 8 == 0, d_in % 64 == 0, d_out % 64 == 0, 3*32 + N*r <= 320,
+ * T <= 65536; otherwise METEORA_ERR_UNSUPPORTED (meteora_gate_backward_workspace_bytes returns 0).
+ * All pointers but the host-side scalars are device memory; ws as for the other entry points.
+ */
+size_t meteora_gate_backward_workspace_bytes(int T, int d_in, int d_out, int N, int r, int k, meteora_dtype dt);
+
+meteora_status meteora_gate_backward(const void* x /*[T,d_in]*/, const void* dy /*[T,d_out]*/,
+                                     const float* gate_bias /*[N] or NULL*/, const void* B /*[N,r,d_out]*/,
+                                     const void* packed, size_t packed_bytes,
+                                     const int32_t* topk_idx /*[T,k] or NULL*/, const float* topk_w /*[T,k] or NULL*/,
+                                     const int32_t* labels /*[T] or NULL*/, float beta,
+                                     int T, int d_in, int d_out, int N, int r, int k, float scale, meteora_dtype dt,
+                                     float* dW_gate /*[d_in,N]*/, float* dbias /*[N] or NULL*/,
+                                     float* d_logits /*[T,N] or NULL*/,
+                                     void* ws, size_t ws_bytes, meteora_stream stream);
+
+/*
  * Base projection alone, first term of Eq. 1 / Eq. 2: out = x * W
  * (W stored [d_out, d_in]).  Exposed so the dense contraction can be checked
  * and timed on its own.

@@ -17,6 +17,7 @@ input x[T,d_in] the joint loss of Eq. 4 reaches the gate parameters along two ro
     all N gate logits and the token's task label,
         l = logsumexp(g) - g_label,        dl/dg_n = softmax(g)_n - [n == label].
     Eq. 4 sums l over tokens and modules (no mean); a caller who wants a mean folds 1/T into beta.
+    A label outside [0, N) marks a token that has no task label: it gets no classification part.
     (Reading: the paper does not print l; "cross-entropy loss for LoRA classification" is taken as the
     N-way cross entropy on the raw logits.)
 
@@ -53,7 +54,7 @@ def gate_backward(x, dy, W_gate, bias, A, B, k: int, scale: float, labels=None, 
         mean = float(np.dot(w[t], dw))
         for j in range(k):
             d_logits[t, idx[t, j]] += w[t, j] * (dw[j] - mean)
-        if labels is not None and beta != 0.0:
+        if labels is not None and beta != 0.0 and 0 <= int(labels[t]) < N:   # other values: token without a label
             gt = g32[t].astype(np.float64)
             p = np.exp(gt - gt.max())
             p /= p.sum()

@@ -66,6 +66,11 @@ def load_library():
     lib.meteora_group_workspace_bytes.argtypes = [vp, i, i, i, i, i, i, i]
     lib.meteora_linear_forward_group.restype = i
     lib.meteora_linear_forward_group.argtypes = [vp, vp, i, i, i, i, i, i, f, i, vp, sz, vp]
+    lib.meteora_gate_backward_workspace_bytes.restype = sz
+    lib.meteora_gate_backward_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    lib.meteora_gate_backward.restype = i
+    lib.meteora_gate_backward.argtypes = [vp, vp, vp, vp, vp, sz, vp, vp, vp, f, i, i, i, i, i, i, f, i, vp, vp, vp,
+                                          vp, sz, vp]
     lib.meteora_base_gemm.restype = i
     lib.meteora_base_gemm.argtypes = [vp, vp, i, i, i, i, vp, vp]
     lib.meteora_stage_count.restype = i
@@ -278,6 +283,37 @@ def linear_forward_group(x, members, k: int, scale: float, ws: Optional[torch.Te
     if st != 0:
         raise MeteoraError(st, "meteora_linear_forward_group")
     return res
+
+
+def gate_backward_workspace_bytes(T, d_in, d_out, N, r, k, dtype) -> int:
+    dt = BF16 if dtype in (torch.bfloat16, BF16, "bf16") else F32
+    return int(load_library().meteora_gate_backward_workspace_bytes(T, d_in, d_out, N, r, k, dt))
+
+
+def gate_backward(x, dy, gate_bias, B, packed, k: int, scale: float, labels=None, beta: float = 0.0,
+                  topk_idx=None, topk_w=None, want_dbias: bool = True, want_d_logits: bool = False,
+                  ws: Optional[torch.Tensor] = None):
+    """meteora_gate_backward: (dW_gate[d_in,N], dbias[N] or None, d_logits[T,N] or None), all fp32."""
+    T, d_in = x.shape
+    N, r, d_out = B.shape
+    _chk(x, "x"); _chk(dy, "dy", x.dtype, (T, d_out)); _chk(gate_bias, "gate_bias", torch.float32, (N,))
+    _chk(B, "B", x.dtype, (N, r, d_out)); _chk(packed, "packed", torch.uint8)
+    _chk(labels, "labels", torch.int32, (T,))
+    _chk(topk_idx, "topk_idx", torch.int32, (T, k)); _chk(topk_w, "topk_w", torch.float32, (T, k))
+    need = gate_backward_workspace_bytes(T, d_in, d_out, N, r, k, x.dtype)
+    if need == 0 and T > 0:
+        raise MeteoraError(2, "meteora_gate_backward_workspace_bytes")
+    ws = _ws(ws, need, x.device)
+    dW = torch.empty((d_in, N), dtype=torch.float32, device=x.device)
+    db = torch.empty((N,), dtype=torch.float32, device=x.device) if want_dbias else None
+    dl = torch.empty((T, N), dtype=torch.float32, device=x.device) if want_d_logits else None
+    st = load_library().meteora_gate_backward(_p(x), _p(dy), _p(gate_bias), _p(B), _p(packed),
+                                              0 if packed is None else packed.numel(), _p(topk_idx), _p(topk_w),
+                                              _p(labels), float(beta), T, d_in, d_out, N, r, k, float(scale),
+                                              _dt(x), _p(dW), _p(db), _p(dl), _p(ws), ws.numel(), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_gate_backward")
+    return dW, db, dl
 
 
 def base_gemm(x, W, out: Optional[torch.Tensor] = None):

@@ -578,4 +578,39 @@ meteora_status meteora_linear_forward(const void* x, const void* W, const float*
                                          dt, out, topk_idx_out, topk_w_out, ws, ws_bytes, stream);
 }
 
+size_t meteora_gate_backward_workspace_bytes(int T, int d_in, int d_out, int N, int r, int k, meteora_dtype dt) {
+    if (!shape_ok(T, d_in, d_out, N, r, k) || !shape_supported(T, d_in, d_out, N, r, k) || T < 1) return 0;
+    if (!gate_backward_applies(T, d_in, d_out, N, r, dt == METEORA_BF16)) return 0;
+    return gate_backward_layout(T, d_in, d_out, N, r).total;
+}
+
+meteora_status meteora_gate_backward(const void* x, const void* dy, const float* gate_bias, const void* B,
+                                     const void* packed, size_t packed_bytes, const int32_t* topk_idx,
+                                     const float* topk_w, const int32_t* labels, float beta, int T, int d_in,
+                                     int d_out, int N, int r, int k, float scale, meteora_dtype dt, float* dW_gate,
+                                     float* dbias, float* d_logits, void* ws, size_t ws_bytes,
+                                     meteora_stream stream) {
+    if (!x || !dy || !B || !packed || !dW_gate || (topk_idx == nullptr) != (topk_w == nullptr))
+        return METEORA_ERR_INVALID_ARG;
+    if (!shape_ok(T, d_in, d_out, N, r, k) || !isfinite(scale) || !isfinite(beta)) return METEORA_ERR_INVALID_ARG;
+    if (dt != METEORA_BF16 && dt != METEORA_F32) return METEORA_ERR_INVALID_ARG;
+    if (T == 0) return METEORA_OK;
+    const bool bf16 = dt == METEORA_BF16;
+    if (!shape_supported(T, d_in, d_out, N, r, k) || !gate_backward_applies(T, d_in, d_out, N, r, bf16))
+        return METEORA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(B) || !aligned16(dW_gate) || (gate_bias && !aligned4(gate_bias)) ||
+        (dbias && !aligned4(dbias)) || (d_logits && !aligned4(d_logits)) || (labels && !aligned4(labels)) ||
+        (topk_idx && (!aligned4(topk_idx) || !aligned4(topk_w))))
+        return METEORA_ERR_UNSUPPORTED;
+    const PackLayout P = pack_layout(d_in, d_out, N, r, bf16);
+    if (!aligned256(packed) || packed_bytes < P.total) return METEORA_ERR_WORKSPACE;
+    const GateBackwardLayout L = gate_backward_layout(T, d_in, d_out, N, r);
+    if (!ws || !aligned256(ws) || ws_bytes < L.total) return METEORA_ERR_WORKSPACE;
+    const void* wcat = static_cast<const char*>(packed) + P.wcat;
+    const hipError_t e = launch_gate_backward(x, dy, wcat, B, gate_bias, topk_idx, topk_w, labels, beta, T, d_in, d_out,
+                                              N, r, k, scale, dW_gate, dbias, d_logits, static_cast<char*>(ws),
+                                              static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? METEORA_OK : METEORA_ERR_HIP;
+}
+
 }  // extern "C"

@@ -12,6 +12,7 @@
 #include "common.hpp"
 #include "kernels.hpp"
 #include "topk_key.hpp"
+#include "dense_logits.hpp"
 
 namespace meteora {
 
@@ -36,35 +37,11 @@ __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
     const int col = lane & (NP - 1), sub = lane / NP;
     const int t0 = blockIdx.x * kSelTokens;
 
-    // ---- logits: splits in order, within a split (lo + mid) + hi; 4 splits' loads in flight ----
     float g[G];
     int lt[G];   // token index inside the workgroup
 #pragma unroll
-    for (int i = 0; i < G; ++i) { g[i] = 0.f; lt[i] = wave * kSelTokensPerWave + i * TPP + sub; }
-    if (col < N) {
-        for (int s0 = 0; s0 < S; s0 += 4) {
-            float v[4][3][G];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int term = 0; term < 3; ++term)
-#pragma unroll
-                    for (int i = 0; i < G; ++i) {
-                        const int t = min(t0 + lt[i], T - 1);
-                        v[u][term][i] = s0 + u < S ? part[((size_t)(s0 + u) * T + t) * CR + term * NP + col] : 0.f;
-                    }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int i = 0; i < G; ++i) g[i] += (v[u][2][i] + v[u][1][i]) + v[u][0][i];
-        }
-        const float b = bias != nullptr ? bias[col] : 0.f;
-#pragma unroll
-        for (int i = 0; i < G; ++i) {
-            g[i] += b;
-            if (g[i] == 0.f) g[i] = 0.f;   // -0 -> +0 so equal logits have equal keys
-        }
-    }
+    for (int i = 0; i < G; ++i) lt[i] = wave * kSelTokensPerWave + i * TPP + sub;
+    dense_logits<NP, G>(part, S, CR, bias, T, N, t0, lt, col, g);
     int sel_i[G];
     float sel_w[G];
     wave_topk_softmax<NP, G>(g, lane, N, k, inv_temperature, sel_i, sel_w);

@@ -184,6 +184,36 @@ def test_group_validation(lib):
     assert lib.meteora_linear_forward_group(P, None, 2, 64, 256, 4, 8, 2, 2.0, BF16, WS, BIG, None) == INVALID
 
 
+def test_gate_backward_validation(lib):
+    """Gate gradients: sizes and argument checks on the host (no launch on any error path)."""
+    need = lib.meteora_gate_backward_workspace_bytes(4096, 4096, 4096, 28, 8, 2, BF16)
+    assert need > 0
+    # the two K-split partial arrays, the padded logit gradients and the slice partials of dW_gate all fit
+    assert need >= 4096 * 320 * 4 + 4096 * 224 * 4 + 4096 * 32 * 4 + 4096 * 32 * 4
+    assert lib.meteora_gate_backward_workspace_bytes(4096, 4096, 4096, 28, 8, 2, F32) == 0
+    assert lib.meteora_gate_backward_workspace_bytes(4096, 4096, 4100, 28, 8, 2, BF16) == 0   # d_out % 64
+    assert lib.meteora_gate_backward_workspace_bytes(4096, 4096, 4096, 28, 12, 2, BF16) == 0  # r % 8
+    assert lib.meteora_gate_backward_workspace_bytes(4096, 4096, 4096, 40, 8, 2, BF16) == 0   # N > 32
+    assert lib.meteora_gate_backward_workspace_bytes(70000, 4096, 4096, 28, 8, 2, BF16) == 0  # T > 65536
+    pkb = lib.meteora_packed_bytes(256, 256, 4, 8, BF16)
+
+    def call(x=P, dy=P, B=P, pk=WS, pkb=pkb, idx=None, w=None, T=64, d_out=256, N=4, r=8, k=2, scale=2.0, beta=0.0,
+             dt=BF16, dW=P, ws=WS, wsb=BIG):
+        return lib.meteora_gate_backward(x, dy, None, B, pk, pkb, idx, w, None, beta, T, 256, d_out, N, r, k, scale, dt,
+                                         dW, None, None, ws, wsb, None)
+
+    assert call(T=0) == OK
+    assert call(x=None) == INVALID and call(dy=None) == INVALID and call(B=None) == INVALID
+    assert call(pk=None) == INVALID and call(dW=None) == INVALID
+    assert call(idx=P) == INVALID                          # routing: both arrays or neither
+    assert call(k=5) == INVALID and call(scale=float("nan")) == INVALID and call(beta=float("inf")) == INVALID
+    assert call(dt=F32) == UNSUPPORTED
+    assert call(d_out=264) == UNSUPPORTED and call(r=4) == UNSUPPORTED and call(N=40, k=2) == UNSUPPORTED
+    assert call(x=ODD) == UNSUPPORTED
+    assert call(pkb=64) == WORKSPACE
+    assert call(ws=None) == WORKSPACE and call(wsb=1024) == WORKSPACE
+
+
 def test_base_gemm_validation(lib):
     f = lambda x=P, W=P, T=64, di=256, do=256, dt=BF16, out=P: lib.meteora_base_gemm(x, W, T, di, do, dt, out, None)
     assert f(x=None) == INVALID and f(W=None) == INVALID and f(out=None) == INVALID

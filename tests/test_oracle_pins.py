@@ -350,3 +350,15 @@ def test_gate_backward_invariants(k):
     # scaling dy scales the language-model part linearly
     twice = gb.gate_backward(ops["x"], 2 * dy, ops["W_gate"], bias, ops["A"], ops["B"], k, shape.scale, None, 0.0)
     np.testing.assert_allclose(twice["dW_gate"], 2 * lm_only["dW_gate"], rtol=1e-12, atol=1e-12)
+
+
+def test_gate_backward_unlabelled_tokens_have_no_classification_part():
+    gb, shape, ops, dy, labels, bias = _backward_case(61, 2)
+    lab = labels.copy()
+    lab[1], lab[4] = -1, 99
+    res = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], 2, shape.scale, lab, 0.4)
+    lm = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], 2, shape.scale, None, 0.0)
+    full = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], 2, shape.scale, labels, 0.4)
+    for t in range(len(lab)):
+        want = lm if t in (1, 4) else full
+        np.testing.assert_array_equal(res["d_logits"][t], want["d_logits"][t])
