@@ -218,6 +218,10 @@ meteora_status meteora_linear_forward_group(const void* x, const meteora_group_m
  * computes them.  topk_idx / topk_w (both or neither): the routing the forward call returned, to be used
  * as it is; NULL ranks again from the recomputed logits (the same routing as that forward path's).
  * `packed` is the blob of meteora_pack_weights for these adapters; B is the stacked [N,r,d_out] tensor.
+ * forward_ws (optional): the workspace in which meteora_linear_forward(_packed) ran on this same x, these
+ * adapters and the same T, d_in, d_out, N, r, k, dt, not written to since.  For 64 < T <= 8192 that call leaves
+ * its products of x with the packed gate and A operands there and they are read instead of being computed
+ * again (one launch less); for other T the argument is ignored.  The caller vouches for the contents.
  * Limits: dt == METEORA_BF16, N <= 32, r % 8 == 0, d_in % 64 == 0, d_out % 64 == 0, 3*32 + N*r <= 320,
  * T <= 65536; otherwise METEORA_ERR_UNSUPPORTED (meteora_gate_backward_workspace_bytes returns 0).
  * All pointers but the host-side scalars are device memory; ws as for the other entry points.
@@ -232,6 +236,7 @@ meteora_status meteora_gate_backward(const void* x /*[T,d_in]*/, const void* dy 
                                      int T, int d_in, int d_out, int N, int r, int k, float scale, meteora_dtype dt,
                                      float* dW_gate /*[d_in,N]*/, float* dbias /*[N] or NULL*/,
                                      float* d_logits /*[T,N] or NULL*/,
+                                     const void* forward_ws /*or NULL*/, size_t forward_ws_bytes,
                                      void* ws, size_t ws_bytes, meteora_stream stream);
 
 /*

@@ -588,8 +588,8 @@ meteora_status meteora_gate_backward(const void* x, const void* dy, const float*
                                      const void* packed, size_t packed_bytes, const int32_t* topk_idx,
                                      const float* topk_w, const int32_t* labels, float beta, int T, int d_in,
                                      int d_out, int N, int r, int k, float scale, meteora_dtype dt, float* dW_gate,
-                                     float* dbias, float* d_logits, void* ws, size_t ws_bytes,
-                                     meteora_stream stream) {
+                                     float* dbias, float* d_logits, const void* forward_ws, size_t forward_ws_bytes,
+                                     void* ws, size_t ws_bytes, meteora_stream stream) {
     if (!x || !dy || !B || !packed || !dW_gate || (topk_idx == nullptr) != (topk_w == nullptr))
         return METEORA_ERR_INVALID_ARG;
     if (!shape_ok(T, d_in, d_out, N, r, k) || !isfinite(scale) || !isfinite(beta)) return METEORA_ERR_INVALID_ARG;
@@ -607,8 +607,15 @@ meteora_status meteora_gate_backward(const void* x, const void* dy, const float*
     const GateBackwardLayout L = gate_backward_layout(T, d_in, d_out, N, r);
     if (!ws || !aligned256(ws) || ws_bytes < L.total) return METEORA_ERR_WORKSPACE;
     const void* wcat = static_cast<const char*>(packed) + P.wcat;
+    // the forward call of a mid-sized batch leaves x * Wcat^T in its workspace: take it instead of computing it again
+    const float* part_x = nullptr;
+    if (forward_ws != nullptr && route_dense_applies(T, d_in, N, r, bf16)) {
+        const WsLayout F = ws_layout(T, d_in, d_out, N, r, k, bf16);
+        if (!aligned256(forward_ws) || forward_ws_bytes < F.total) return METEORA_ERR_WORKSPACE;
+        part_x = reinterpret_cast<const float*>(static_cast<const char*>(forward_ws) + F.dpart);
+    }
     const hipError_t e = launch_gate_backward(x, dy, wcat, B, gate_bias, topk_idx, topk_w, labels, beta, T, d_in, d_out,
-                                              N, r, k, scale, dW_gate, dbias, d_logits, static_cast<char*>(ws),
+                                              N, r, k, scale, dW_gate, dbias, d_logits, part_x, static_cast<char*>(ws),
                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? METEORA_OK : METEORA_ERR_HIP;
 }

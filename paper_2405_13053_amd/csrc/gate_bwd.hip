@@ -12,9 +12,9 @@
 // x * Wcat^T gives the logits and x A_i of EVERY adapter (the forward's own first launch, so the logits and with
 // them the top-k are bit-identical to that path's), dy * Bflat^T with Bflat = B viewed as [N*r, d_out] gives
 // B_i dy of every adapter; both as fp32 K-split partials.  gate_bwd_dlogits_kernel (this file) turns them
-// into d_logits per token, gate_bwd_wgrad_kernel accumulates x^T d_logits over token slices with plain fp32
-// FMAs (a [d_in, T] x [T, 32] product whose x operand is not K-contiguous; 1 GFLOP at T = d_in = 4096, below
-// what re-tiling x for MFMA would cost), and gate_bwd_reduce_kernel adds the slices in order.
+// into d_logits per token, gate_bwd_wgrad_kernel accumulates x^T d_logits over token slices with fp32 MFMAs
+// (a [d_in, T] x [T, 32] product whose x operand is not K-contiguous), and gate_bwd_reduce_kernel adds the
+// slices in order.
 #include "common.hpp"
 #include "kernels.hpp"
 #include "topk_key.hpp"
@@ -160,69 +160,81 @@ __global__ __launch_bounds__(kBwdThreads) void gate_bwd_dlogits_kernel(const Dlo
 }
 
 // ---- dW_gate partials: wpart[slice][c][32] = sum over the slice's tokens of x[t][c] * dg[t][:] ----
-// A workgroup takes 128 columns of x (a lane two adjacent ones) and one token slice; its four wavefronts take
-// eight adapters each.  dg of 64 tokens at a time sits in LDS (read as broadcasts); x streams with eight
-// tokens' loads in flight.  Workgroups of column tile 0 also add up dg itself for the bias gradient.
+// The contraction runs over tokens, and x[T, d_in] is not token-contiguous, so the bf16 MFMA operand layout
+// (eight consecutive K values per lane) would need a transposed copy of x.  The fp32 MFMA 32x32x2 takes ONE K
+// value per lane: lane l holds A[m = l % 32][k = l / 32] and B[k = l / 32][n = l % 32].  With m = adapter,
+// n = column of x and k = token, both operands are plain coalesced loads (dg[t][m], x[t][c0 + n]) and the
+// product keeps full fp32 accuracy.  A wavefront owns 32 columns and the whole token slice in one 32x32
+// accumulator; a workgroup's four wavefronts take 128 adjacent columns (256-byte row segments of x).
+// Two chunks of kWgChunk tokens are in flight per wavefront.  Workgroups of column tile 0 also add up dg for
+// dbias.
 constexpr int kWgCols = 128;
 constexpr int kWgChunk = 64;
 
-__global__ __launch_bounds__(256) void gate_bwd_wgrad_kernel(const bf16_t* __restrict__ x, const float* __restrict__ dg,
+__global__ __launch_bounds__(256) void gate_bwd_wgrad_kernel(const uint16_t* __restrict__ x, const float* __restrict__ dg,
                                                               int T, int d_in, int slice_tokens,
                                                               float* __restrict__ wpart, float* __restrict__ bpart) {
-    __shared__ __attribute__((aligned(16))) float s_dg[kWgChunk][kBwdNP];
+    constexpr int U = kWgChunk / 2;                          // MFMAs per chunk: two tokens each
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = blockIdx.x * kWgCols + 2 * lane;
-    const int cc = min(c, d_in - 2);                         // d_in is even; clamped lanes do not store
+    const int n = lane & 31, kh = lane >> 5;
+    const int c = blockIdx.x * kWgCols + wave * 32 + n;
+    const int cc = min(c, d_in - 1);                         // clamped lanes do not store
     const int slice = blockIdx.y;
     const int t_begin = slice * slice_tokens, t_end = min(T, t_begin + slice_tokens);
-    float acc0[8], acc1[8];
+    f32x16 acc;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { acc0[j] = 0.f; acc1[j] = 0.f; }
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
     float bsum = 0.f;
-    for (int tc = t_begin; tc < t_end; tc += kWgChunk) {
-        __syncthreads();
-        {   // 64 x 32 floats: a thread copies 8 of them; rows past the slice are zero
-            const int row = threadIdx.x >> 2, q = (threadIdx.x & 3) * 8;
-            f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
-            if (tc + row < t_end) {
-                const float* p = dg + (size_t)(tc + row) * kBwdNP + q;
-                v0 = *reinterpret_cast<const f32x4*>(p);
-                v1 = *reinterpret_cast<const f32x4*>(p + 4);
+    uint16_t xv[2][U];
+    float dv[2][U];
+    // lane part of the addresses; the token part is uniform, so a full chunk's loads need no per-lane arithmetic
+    const int lane_x = kh * d_in + cc;
+    auto load_chunk = [&](int buf, int t0) {
+        if (t0 + kWgChunk <= t_end) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                xv[buf][u] = x[(size_t)(t0 + 2 * u) * d_in + lane_x];
+                dv[buf][u] = dg[(size_t)(t0 + 2 * u) * kBwdNP + lane];
             }
-            *reinterpret_cast<f32x4*>(&s_dg[row][q]) = v0;
-            *reinterpret_cast<f32x4*>(&s_dg[row][q + 4]) = v1;
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int t = t0 + 2 * u + kh;
+                const int tc = min(t, T - 1);
+                xv[buf][u] = x[(size_t)tc * d_in + cc];
+                const float d = dg[(size_t)tc * kBwdNP + n];
+                dv[buf][u] = t < t_end ? d : 0.f;            // tokens past the slice contribute nothing
+            }
         }
-        __syncthreads();
-        if (blockIdx.x == 0 && threadIdx.x < kBwdNP)
-            for (int tt = 0; tt < kWgChunk; ++tt) bsum += s_dg[tt][threadIdx.x];
-        for (int tt0 = 0; tt0 < kWgChunk; tt0 += 8) {
-            uint32_t xv[8];
+    };
+    auto mma_chunk = [&](int buf) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int t = min(tc + tt0 + u, T - 1);      // rows past the slice meet zero dg
-                xv[u] = *reinterpret_cast<const uint32_t*>(x + (size_t)t * d_in + cc);
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const float x0 = bf16_bits_to_float(xv[u] & 0xffffu), x1 = bf16_bits_to_float(xv[u] >> 16);
-                const f32x4 d0 = *reinterpret_cast<const f32x4*>(&s_dg[tt0 + u][wave * 8]);
-                const f32x4 d1 = *reinterpret_cast<const f32x4*>(&s_dg[tt0 + u][wave * 8 + 4]);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    acc0[j] += x0 * d0[j]; acc0[4 + j] += x0 * d1[j];
-                    acc1[j] += x1 * d0[j]; acc1[4 + j] += x1 * d1[j];
-                }
-            }
+        for (int u = 0; u < U; ++u) {
+            const float xf = bf16_bits_to_float(xv[buf][u]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(dv[buf][u], xf, acc, 0, 0, 0);
+            bsum += dv[buf][u];
+        }
+    };
+    load_chunk(0, t_begin);
+    for (int t0 = t_begin; t0 < t_end; t0 += 2 * kWgChunk) {
+        if (t0 + kWgChunk < t_end) load_chunk(1, t0 + kWgChunk);
+        mma_chunk(0);
+        if (t0 + kWgChunk < t_end) {
+            if (t0 + 2 * kWgChunk < t_end) load_chunk(0, t0 + 2 * kWgChunk);
+            mma_chunk(1);
         }
     }
+    // accumulator entry i of lane l: adapter 8*(i/4) + 4*(l/32) + i%4, column l%32
     if (c < d_in) {
-        float* p = wpart + ((size_t)slice * d_in + c) * kBwdNP + wave * 8;
-        *reinterpret_cast<f32x4*>(p) = f32x4{acc0[0], acc0[1], acc0[2], acc0[3]};
-        *reinterpret_cast<f32x4*>(p + 4) = f32x4{acc0[4], acc0[5], acc0[6], acc0[7]};
-        *reinterpret_cast<f32x4*>(p + kBwdNP) = f32x4{acc1[0], acc1[1], acc1[2], acc1[3]};
-        *reinterpret_cast<f32x4*>(p + kBwdNP + 4) = f32x4{acc1[4], acc1[5], acc1[6], acc1[7]};
+        float* p = wpart + ((size_t)slice * d_in + c) * kBwdNP + kh * 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<f32x4*>(p + q * 8) = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
     }
-    if (blockIdx.x == 0 && threadIdx.x < kBwdNP) bpart[slice * kBwdNP + threadIdx.x] = bsum;
+    if (blockIdx.x == 0 && wave == 0) {
+        bsum += __shfl_xor(bsum, 32);
+        if (kh == 0) bpart[slice * kBwdNP + n] = bsum;
+    }
 }
 
 // dW_gate[c][n] = sum of the slices in order (thread per (c, padded n)); the last workgroup does dbias.
@@ -263,7 +275,7 @@ bool gate_backward_applies(int T, int d_in, int d_out, int N, int r, bool bf16) 
 
 static int wgrad_slices(int T, int d_in) {
     const int col_tiles = ceil_div(d_in, kWgCols);
-    int slices = ceil_div(1024, col_tiles);                   // about four workgroups per CU
+    int slices = ceil_div(512, col_tiles);   // two workgroups per CU (measured: 256 to 2048 workgroups tried)
     const int most = ceil_div(T, kWgChunk);
     if (slices > most) slices = most;
     return slices < 1 ? 1 : slices;
@@ -290,17 +302,18 @@ GateBackwardLayout gate_backward_layout(int T, int d_in, int d_out, int N, int r
 hipError_t launch_gate_backward(const void* x, const void* dy, const void* wcat, const void* B, const float* bias,
                                 const int32_t* idx_in, const float* w_in, const int32_t* labels, float beta, int T,
                                 int d_in, int d_out, int N, int r, int k, float scale, float* dW_gate, float* dbias,
-                                float* d_logits, char* ws, hipStream_t stream) {
+                                float* d_logits, const float* part_x_given, char* ws, hipStream_t stream) {
     if (!gate_backward_applies(T, d_in, d_out, N, r, true) || k < 1 || k > kMaxTopK || k > N)
         return hipErrorInvalidValue;
     const GateBackwardLayout L = gate_backward_layout(T, d_in, d_out, N, r);
     const int CR = prep_wcat_rows(N, r), NR = N * r;
-    float* part_x = reinterpret_cast<float*>(ws + L.part_x);
+    const float* part_x = part_x_given != nullptr ? part_x_given : reinterpret_cast<float*>(ws + L.part_x);
     float* part_dy = reinterpret_cast<float*>(ws + L.part_dy);
     float* dg = reinterpret_cast<float*>(ws + L.dg);
     float* wpart = reinterpret_cast<float*>(ws + L.wpart);
     float* bpart = reinterpret_cast<float*>(ws + L.bpart);
-    hipError_t e = launch_gemm_dense_splitk(x, wcat, T, d_in, CR, part_x, stream);
+    hipError_t e = hipSuccess;
+    if (part_x_given == nullptr) e = launch_gemm_dense_splitk(x, wcat, T, d_in, CR, reinterpret_cast<float*>(ws + L.part_x), stream);
     if (e != hipSuccess) return e;
     e = launch_gemm_dense_splitk(dy, B, T, d_out, NR, part_dy, stream);
     if (e != hipSuccess) return e;
@@ -314,7 +327,7 @@ hipError_t launch_gate_backward(const void* x, const void* dy, const void* wcat,
     const int slice_tokens = wgrad_slice_tokens(T, d_in);
     const int slices = ceil_div(T, slice_tokens);
     gate_bwd_wgrad_kernel<<<dim3(ceil_div(d_in, kWgCols), slices), 256, 0, stream>>>(
-        (const bf16_t*)x, dg, T, d_in, slice_tokens, wpart, bpart);
+        (const uint16_t*)x, dg, T, d_in, slice_tokens, wpart, bpart);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const int blocks = (int)ceil_div64((int64_t)d_in * kBwdNP, 256) + 1;
     gate_bwd_reduce_kernel<<<blocks, 256, 0, stream>>>(wpart, bpart, slices, d_in, N, dW_gate, dbias);

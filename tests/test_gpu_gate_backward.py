@@ -86,6 +86,30 @@ def test_gate_backward_takes_the_forward_routing():
     assert not torch.equal(c[2], d[2])
 
 
+@pytest.mark.parametrize("T", [300, 40])
+def test_gate_backward_reads_the_forward_products(T):
+    """With the forward call's workspace the products of x are not computed again: same bits as without it
+    (T = 300: taken from the workspace; T = 40: that forward path leaves none, the argument is ignored)."""
+    shape = LS(T, 256, 192, 12, 8, 3, 2.0, "bf16", "zipf", "forward-ws")
+    ops, dev, dy, labels = _case(shape, seed=73)
+    ws = torch.empty(m.workspace_bytes(T, shape.d_in, shape.d_out, shape.N, shape.r, shape.k, torch.bfloat16),
+                     dtype=torch.uint8, device="cuda")
+    _, idx, w = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], dev["bias"], dev["A"], dev["B"], shape.k,
+                                 shape.scale, return_routing=True, packed=dev["packed"], ws=ws)
+    a = m.gate_backward(dev["x"], dev["dy"], dev["bias"], dev["B"], dev["packed"], shape.k, shape.scale,
+                        labels=dev["labels"], beta=0.3, topk_idx=idx, topk_w=w, want_d_logits=True)
+    b = m.gate_backward(dev["x"], dev["dy"], dev["bias"], dev["B"], dev["packed"], shape.k, shape.scale,
+                        labels=dev["labels"], beta=0.3, topk_idx=idx, topk_w=w, want_d_logits=True, forward_ws=ws)
+    torch.cuda.synchronize()
+    for u, v in zip(a, b):
+        assert torch.equal(u, v)
+    if T > 64:   # and it is really read: a cleared workspace changes the result
+        ws.zero_()
+        c = m.gate_backward(dev["x"], dev["dy"], dev["bias"], dev["B"], dev["packed"], shape.k, shape.scale,
+                            labels=dev["labels"], beta=0.3, topk_idx=idx, topk_w=w, want_d_logits=True, forward_ws=ws)
+        assert not torch.equal(c[0], a[0])
+
+
 def test_gate_backward_full_size_sampled():
     """Config 2's layer (T = 4096, 4096 -> 4096, N = 28, r = 8, top-2): d_logits on sampled tokens against the
     oracle, dW_gate and dbias through properties that hold at any size: dbias = column sums of d_logits,
