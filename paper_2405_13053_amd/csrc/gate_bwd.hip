@@ -15,6 +15,7 @@
 // into d_logits per token, gate_bwd_wgrad_kernel accumulates x^T d_logits over token slices with fp32 MFMAs
 // (a [d_in, T] x [T, 32] product whose x operand is not K-contiguous), and gate_bwd_reduce_kernel adds the
 // slices in order.
+#include <type_traits>
 #include "common.hpp"
 #include "kernels.hpp"
 #include "topk_key.hpp"
@@ -163,78 +164,112 @@ __global__ __launch_bounds__(kBwdThreads) void gate_bwd_dlogits_kernel(const Dlo
 // The contraction runs over tokens, and x[T, d_in] is not token-contiguous, so the bf16 MFMA operand layout
 // (eight consecutive K values per lane) would need a transposed copy of x.  The fp32 MFMA 32x32x2 takes ONE K
 // value per lane: lane l holds A[m = l % 32][k = l / 32] and B[k = l / 32][n = l % 32].  With m = adapter,
-// n = column of x and k = token, both operands are plain coalesced loads (dg[t][m], x[t][c0 + n]) and the
-// product keeps full fp32 accuracy.  A wavefront owns 32 columns and the whole token slice in one 32x32
-// accumulator; a workgroup's four wavefronts take 128 adjacent columns (256-byte row segments of x).
-// Two chunks of kWgChunk tokens are in flight per wavefront.  Workgroups of column tile 0 also add up dg for
-// dbias.
+// k = token and n = column slot, both operands are plain coalesced loads and the product keeps full fp32
+// accuracy.  The kernel is bound by the number of vector loads it issues (a CU takes a 4-byte-per-lane load
+// every ~6 cycles, a 2-, 8- or 16-byte one every 15 to 29), so a lane loads one dword of x, two adjacent
+// columns, per token pair and feeds two MFMAs with column slots c0 + 2n and c0 + 2n + 1: one x load and one dg
+// load per two MFMAs.  A wavefront covers 64 columns; the four wavefronts of a workgroup are 2 column halves
+// x 2 token halves of a 128-column slice, the token halves added through LDS in a fixed order.
+// Workgroups of column tile 0 also add up dg for dbias.
 constexpr int kWgCols = 128;
-constexpr int kWgChunk = 64;
+constexpr int kWgRing = 16;      // token pairs whose loads are in flight per wavefront
+constexpr int kWgChunk = 2 * kWgRing;
 
-__global__ __launch_bounds__(256) void gate_bwd_wgrad_kernel(const uint16_t* __restrict__ x, const float* __restrict__ dg,
-                                                              int T, int d_in, int slice_tokens,
-                                                              float* __restrict__ wpart, float* __restrict__ bpart) {
-    constexpr int U = kWgChunk / 2;                          // MFMAs per chunk: two tokens each
+__global__ __launch_bounds__(256, 2) void gate_bwd_wgrad_kernel(const uint16_t* __restrict__ x,
+                                                                 const float* __restrict__ dg, int T, int d_in,
+                                                                 int slice_tokens, float* __restrict__ wpart,
+                                                                 float* __restrict__ bpart) {
+    constexpr int R = kWgRing;
+    __shared__ float red[2][32][64];                         // [column half][acc entry][lane] of the second token half
+    __shared__ float s_b[kBwdNP];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, kh = lane >> 5;
-    const int c = blockIdx.x * kWgCols + wave * 32 + n;
-    const int cc = min(c, d_in - 1);                         // clamped lanes do not store
+    const int chalf = wave & 1, thalf = wave >> 1;
+    const int c = blockIdx.x * kWgCols + chalf * 64 + 2 * n; // d_in is even: both columns inside or both outside
+    const int cc = min(c, d_in - 2);
     const int slice = blockIdx.y;
-    const int t_begin = slice * slice_tokens, t_end = min(T, t_begin + slice_tokens);
-    f32x16 acc;
+    const int s_begin = slice * slice_tokens, s_end = min(T, s_begin + slice_tokens);
+    const int half_tokens = slice_tokens / 2;                // a multiple of kWgChunk
+    const int t_begin = s_begin + thalf * half_tokens, t_end = min(s_end, t_begin + half_tokens);
+    f32x16 acc0, acc1;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int i = 0; i < 16; ++i) { acc0[i] = 0.f; acc1[i] = 0.f; }
     float bsum = 0.f;
-    uint16_t xv[2][U];
-    float dv[2][U];
-    // lane part of the addresses; the token part is uniform, so a full chunk's loads need no per-lane arithmetic
-    const int lane_x = kh * d_in + cc;
-    auto load_chunk = [&](int buf, int t0) {
-        if (t0 + kWgChunk <= t_end) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                xv[buf][u] = x[(size_t)(t0 + 2 * u) * d_in + lane_x];
-                dv[buf][u] = dg[(size_t)(t0 + 2 * u) * kBwdNP + lane];
-            }
+    uint32_t xv[R];
+    float dv[R];
+    const uint32_t* xw = reinterpret_cast<const uint32_t*>(x);
+    // lane part of the addresses (in dwords); the token part is uniform, so a full pair needs no per-lane arithmetic
+    const int lane_x = (kh * d_in + cc) >> 1;
+    const int row_dwords = d_in >> 1;
+    // pair p of this wavefront = tokens t_begin + 2p (lanes 0..31) and t_begin + 2p + 1 (lanes 32..63)
+    auto load_pair = [&](int slot, int pair, bool inside) {
+        const int t0 = t_begin + 2 * pair;
+        if (inside) {                                        // both tokens lie in [t_begin, t_end)
+            xv[slot] = xw[(size_t)t0 * row_dwords + lane_x];
+            dv[slot] = dg[(size_t)t0 * kBwdNP + lane];
         } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = t0 + 2 * u + kh;
-                const int tc = min(t, T - 1);
-                xv[buf][u] = x[(size_t)tc * d_in + cc];
-                const float d = dg[(size_t)tc * kBwdNP + n];
-                dv[buf][u] = t < t_end ? d : 0.f;            // tokens past the slice contribute nothing
-            }
+            const int t = t0 + kh;
+            const int tc = min(t, T - 1);
+            xv[slot] = xw[((size_t)tc * d_in + cc) >> 1];
+            const float d = dg[(size_t)tc * kBwdNP + n];
+            dv[slot] = t < t_end ? d : 0.f;                  // tokens past the range contribute nothing
         }
     };
-    auto mma_chunk = [&](int buf) {
+    const int pairs = (max(t_end - t_begin, 0) + 1) / 2;
+    // The loads of R pairs are in flight; each step consumes one pair (two MFMAs) and then requests the pair R
+    // steps ahead into the same registers, so the load unit and the matrix cores work side by side instead of in
+    // bursts.  The scheduling barriers keep the compiler from gathering the loads of a round at its top.
+    // The operands of a step are converted one step ahead, while the matrix cores run the step before (a conversion
+    // placed right in front of its MFMA holds the MFMA back by about 20 cycles).
+    float cur_d = 0.f, cur_a0 = 0.f, cur_a1 = 0.f;
+    auto convert = [&](int slot) {
+        cur_d = dv[slot];
+        cur_a0 = __uint_as_float(xv[slot] << 16);
+        cur_a1 = __uint_as_float(xv[slot] & 0xffff0000u);
+    };
+    auto round = [&](auto mode, int p) {                     // mode 0: refill inside, 1: refill at the ragged end, 2: none
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float xf = bf16_bits_to_float(xv[buf][u]);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(dv[buf][u], xf, acc, 0, 0, 0);
-            bsum += dv[buf][u];
+        for (int u = 0; u < R; ++u) {
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(cur_d, cur_a0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(cur_d, cur_a1, acc1, 0, 0, 0);
+            bsum += cur_d;
+            if constexpr (decltype(mode)::value != 2) load_pair(u, p + R + u, decltype(mode)::value == 0);
+            convert((u + 1) % R);                            // slot 0 at the end of a round: refilled at its first step
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
-    load_chunk(0, t_begin);
-    for (int t0 = t_begin; t0 < t_end; t0 += 2 * kWgChunk) {
-        if (t0 + kWgChunk < t_end) load_chunk(1, t0 + kWgChunk);
-        mma_chunk(0);
-        if (t0 + kWgChunk < t_end) {
-            if (t0 + 2 * kWgChunk < t_end) load_chunk(0, t0 + 2 * kWgChunk);
-            mma_chunk(1);
+    if (pairs > 0) {
+#pragma unroll
+        for (int u = 0; u < R; ++u) load_pair(u, u, false);
+        convert(0);
+        for (int p = 0; p < pairs; p += R) {
+            if (t_begin + 2 * (p + 2 * R) <= t_end) round(std::integral_constant<int, 0>{}, p);
+            else if (p + R < pairs) round(std::integral_constant<int, 1>{}, p);
+            else round(std::integral_constant<int, 2>{}, p);
         }
     }
-    // accumulator entry i of lane l: adapter 8*(i/4) + 4*(l/32) + i%4, column l%32
+    // ---- second token half into LDS, first half adds it ----
+    bsum += __shfl_xor(bsum, 32);
+    if (thalf == 1) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { red[chalf][i][lane] = acc0[i]; red[chalf][16 + i][lane] = acc1[i]; }
+        if (chalf == 0 && kh == 0) s_b[n] = bsum;
+    }
+    __syncthreads();
+    if (thalf == 1) return;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc0[i] += red[chalf][i][lane]; acc1[i] += red[chalf][16 + i][lane]; }
+    // accumulator entry i of lane l: adapter 8*(i/4) + 4*(l/32) + i%4, column slot l%32
     if (c < d_in) {
         float* p = wpart + ((size_t)slice * d_in + c) * kBwdNP + kh * 4;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            *reinterpret_cast<f32x4*>(p + q * 8) = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        for (int q = 0; q < 4; ++q) {
+            *reinterpret_cast<f32x4*>(p + q * 8) = f32x4{acc0[4 * q], acc0[4 * q + 1], acc0[4 * q + 2], acc0[4 * q + 3]};
+            *reinterpret_cast<f32x4*>(p + kBwdNP + q * 8) =
+                f32x4{acc1[4 * q], acc1[4 * q + 1], acc1[4 * q + 2], acc1[4 * q + 3]};
+        }
     }
-    if (blockIdx.x == 0 && wave == 0) {
-        bsum += __shfl_xor(bsum, 32);
-        if (kh == 0) bpart[slice * kBwdNP + n] = bsum;
-    }
+    if (blockIdx.x == 0 && chalf == 0 && kh == 0) bpart[slice * kBwdNP + n] = bsum + s_b[n];
 }
 
 // dW_gate[c][n] = sum of the slices in order (thread per (c, padded n)); the last workgroup does dbias.
@@ -276,12 +311,13 @@ bool gate_backward_applies(int T, int d_in, int d_out, int N, int r, bool bf16) 
 static int wgrad_slices(int T, int d_in) {
     const int col_tiles = ceil_div(d_in, kWgCols);
     int slices = ceil_div(512, col_tiles);   // two workgroups per CU (measured: 256 to 2048 workgroups tried)
-    const int most = ceil_div(T, kWgChunk);
+    const int most = ceil_div(T, 2 * kWgChunk);
     if (slices > most) slices = most;
     return slices < 1 ? 1 : slices;
 }
-static int wgrad_slice_tokens(int T, int d_in) {
-    return ceil_div(ceil_div(T, wgrad_slices(T, d_in)), kWgChunk) * kWgChunk;
+static int wgrad_slice_tokens(int T, int d_in) {   // a multiple of one chunk per token half
+    constexpr int step = 2 * kWgChunk;
+    return ceil_div(ceil_div(T, wgrad_slices(T, d_in)), step) * step;
 }
 
 GateBackwardLayout gate_backward_layout(int T, int d_in, int d_out, int N, int r) {
