@@ -22,6 +22,11 @@ input x[T,d_in] the joint loss of Eq. 4 reaches the gate parameters along two ro
     N-way cross entropy on the raw logits.)
 
 From d_logits[T,N] = dL/dg:  dW_gate = x^T d_logits,  dbias = sum_t d_logits[t].
+
+The gradient with respect to the module's input (what the modules in front of this one need for their own
+gates) collects the three roads x takes: the base projection, the selected adapters, and the gate,
+    dx = dy W  +  scale * sum_j w_j ((dy B_{a_j}^T) A_{a_j}^T)  +  d_logits W_gate^T
+with W stored [d_out, d_in] (o = x W^T in storage terms).
 """
 from __future__ import annotations
 
@@ -30,8 +35,9 @@ import numpy as np
 from . import gate_logits, topk_softmax
 
 
-def gate_backward(x, dy, W_gate, bias, A, B, k: int, scale: float, labels=None, beta: float = 0.0):
-    """Returns dict(dW_gate[d_in,N], dbias[N], d_logits[T,N], idx[T,k], w[T,k]), all float64 but idx."""
+def gate_backward(x, dy, W_gate, bias, A, B, k: int, scale: float, labels=None, beta: float = 0.0, W=None):
+    """Returns dict(dW_gate[d_in,N], dbias[N], d_logits[T,N], idx[T,k], w[T,k]), all float64 but idx;
+    with W[d_out,d_in] given also dx[T,d_in]."""
     x = np.asarray(x, dtype=np.float64)
     dy = np.asarray(dy, dtype=np.float64)
     A = np.asarray(A, dtype=np.float64)
@@ -60,4 +66,14 @@ def gate_backward(x, dy, W_gate, bias, A, B, k: int, scale: float, labels=None, 
             p /= p.sum()
             p[int(labels[t])] -= 1.0
             d_logits[t] += beta * p
-    return {"dW_gate": x.T @ d_logits, "dbias": d_logits.sum(axis=0), "d_logits": d_logits, "idx": idx, "w": w}
+    res = {"dW_gate": x.T @ d_logits, "dbias": d_logits.sum(axis=0), "d_logits": d_logits, "idx": idx, "w": w}
+    if W is not None:
+        W = np.asarray(W, dtype=np.float64)
+        assert W.shape == (d_out, d_in)
+        dx = dy @ W + d_logits @ np.asarray(W_gate, dtype=np.float64).T
+        for t in range(T):
+            for j in range(k):
+                a = idx[t, j]
+                dx[t] += scale * w[t, j] * ((dy[t] @ B[a].T) @ A[a].T)
+        res["dx"] = dx
+    return res

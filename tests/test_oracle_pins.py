@@ -261,16 +261,24 @@ def test_margin_conditioning_removes_near_ties():
 
 
 # ------------------------------------------------- gate gradients (Sec. 3.2, Eq. 4)
-def _loss_of_gate(ops, W_gate, bias, dy, idx, k, scale, labels, beta):
+def _loss_of_gate(ops, W_gate, bias, dy, idx, k, scale, labels, beta, x=None):
     """The scalar that the gate gradients differentiate, built from the forward definitions only:
     <dy, o> with o from Eq. 2 (selection idx held fixed, weights from Eq. 3 on the k selected logits in
     double) plus beta * sum_t cross-entropy(softmax over all N logits, label_t)."""
-    x64 = ops["x"].astype(np.float64)
+    xx = ops["x"] if x is None else x
+    x64 = xx.astype(np.float64)
     g = x64 @ W_gate + bias
     gs = np.take_along_axis(g, idx.astype(np.int64), axis=1)
     e = np.exp(gs - gs.max(axis=1, keepdims=True))
     w = e / e.sum(axis=1, keepdims=True)
-    y = oracle.base(ops["x"], ops["W"]) + oracle.lora_delta(ops["x"], ops["A"], ops["B"], idx, w, scale)
+    if x is None:
+        y = oracle.base(ops["x"], ops["W"]) + oracle.lora_delta(ops["x"], ops["A"], ops["B"], idx, w, scale)
+    else:   # the C oracle takes float32 inputs; a probe of x needs double: Eq. 2 written out with numpy here
+        y = x64 @ ops["W"].astype(np.float64).T
+        for t in range(x64.shape[0]):
+            for j in range(k):
+                a = idx[t, j]
+                y[t] += scale * w[t, j] * ((x64[t] @ ops["A"][a].astype(np.float64)) @ ops["B"][a].astype(np.float64))
     loss = float((dy * y).sum())
     if beta:
         lse = np.log(np.exp(g - g.max(axis=1, keepdims=True)).sum(axis=1)) + g.max(axis=1)
@@ -362,3 +370,31 @@ def test_gate_backward_unlabelled_tokens_have_no_classification_part():
     for t in range(len(lab)):
         want = lm if t in (1, 4) else full
         np.testing.assert_array_equal(res["d_logits"][t], want["d_logits"][t])
+
+
+@pytest.mark.parametrize("k", [1, 2, 4])
+def test_gate_backward_dx_matches_finite_differences_of_the_forward(k):
+    """dx collects the base projection, the selected adapters and the gate: central differences of the same
+    loss with respect to entries of x (in double; Eq. 2 in numpy agrees with the C oracle at the unperturbed x)."""
+    gb, shape, ops, dy, labels, bias = _backward_case(71 + k, k)
+    beta = 0.6
+    res = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], k, shape.scale, labels, beta,
+                           W=ops["W"])
+    Wg64, b64 = ops["W_gate"].astype(np.float64), bias.astype(np.float64)
+    x64 = ops["x"].astype(np.float64)
+    base = _loss_of_gate(ops, Wg64, b64, dy, res["idx"], k, shape.scale, labels, beta)
+    twin = _loss_of_gate(ops, Wg64, b64, dy, res["idx"], k, shape.scale, labels, beta, x=x64)
+    assert abs(base - twin) <= 1e-9 * max(1.0, abs(base))
+    eps = 1e-6
+    rng = np.random.default_rng(9)
+    for _ in range(16):
+        t, i = int(rng.integers(0, x64.shape[0])), int(rng.integers(0, x64.shape[1]))
+        xp, xm = x64.copy(), x64.copy()
+        xp[t, i] += eps
+        xm[t, i] -= eps
+        fd = (_loss_of_gate(ops, Wg64, b64, dy, res["idx"], k, shape.scale, labels, beta, x=xp) -
+              _loss_of_gate(ops, Wg64, b64, dy, res["idx"], k, shape.scale, labels, beta, x=xm)) / (2 * eps)
+        assert abs(fd - res["dx"][t, i]) <= 1e-5 * max(1.0, abs(fd)), (t, i, fd, res["dx"][t, i])
+    # without adapters' weight and gate (scale 0, beta 0) dx is the base projection's: dy W
+    plain = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], k, 0.0, None, 0.0, W=ops["W"])
+    np.testing.assert_allclose(plain["dx"], dy @ ops["W"].astype(np.float64), rtol=1e-12, atol=1e-12)
