@@ -3,7 +3,8 @@
 Workload: the layer of bench.py's headline configuration (T = 4096 tokens, 4096 -> 4096, N = 28 adapters of
 rank 8, top-2, bf16, seeded synthetic values), with an upstream gradient dy and per-token task labels from
 gen.inputs.make_training_signals.  Times meteora_gate_backward alone and together with the forward call whose
-routing and products of x it reuses, with HIP events on the launch stream, inputs resident in HBM.  Prints one JSON line; the
+routing and products of x it reuses, without and with the module's input gradient dx (one more GEMM of the
+forward's size), with HIP events on the launch stream, inputs resident in HBM.  Prints one JSON line; the
 oracle's rate on a bounded token sample is reported beside it (a baseline, not a target).
 
     python bench_backward.py [--steps 200] [--warmup 20] [--no-cpu-baseline]
@@ -48,9 +49,12 @@ def main():
     ws_b = torch.empty(m.gate_backward_workspace_bytes(s.T, s.d_in, s.d_out, s.N, s.r, s.k, bf), dtype=torch.uint8,
                        device="cuda")
 
-    def backward(idx=None, w=None, forward_ws=None):
+    W_t = dev["W"].t().contiguous()   # the frozen base weight in the orientation the input gradient streams
+
+    def backward(idx=None, w=None, forward_ws=None, dx=False):
         return m.gate_backward(dev["x"], dyd, None, dev["B"], packed, s.k, s.scale, labels=lab, beta=args.beta,
-                               topk_idx=idx, topk_w=w, ws=ws_b, forward_ws=forward_ws)
+                               topk_idx=idx, topk_w=w, ws=ws_b, forward_ws=forward_ws, A=dev["A"], W_gate=Wg,
+                               W_t=W_t, want_dx=dx)
 
     def forward():
         return m.linear_forward(dev["x"], dev["W"], Wg, None, dev["A"], dev["B"], s.k, s.scale, out=out, ws=ws_f,
@@ -59,6 +63,10 @@ def main():
     def both():
         _, idx, w = forward()
         backward(idx, w, ws_f)   # the forward call's products of x are read, not computed again
+
+    def both_dx():
+        _, idx, w = forward()
+        backward(idx, w, ws_f, dx=True)
 
     def timed(fn):
         for _ in range(args.warmup):
@@ -76,6 +84,8 @@ def main():
     t_fwd = timed(forward)
     t_bwd = timed(backward)
     t_both = timed(both)
+    t_bwd_dx = timed(lambda: backward(dx=True))
+    t_both_dx = timed(both_dx)
 
     # HBM bytes one backward call has to move: x twice (products, x^T d_logits), dy, Wcat, B, the fp32 K-split
     # partials written and read back (all of the gate columns, the selected adapters' r columns), the padded
@@ -91,8 +101,11 @@ def main():
         "backward": {"us_per_call": t_bwd * 1e6, "tokens_per_s": T / t_bwd,
                      "input_GB/s": algorithmic / t_bwd / 1e9, "input_bytes": algorithmic,
                      "workspace_bytes": need},
+        "backward_with_dx": {"us_per_call": t_bwd_dx * 1e6, "tokens_per_s": T / t_bwd_dx,
+                             "PFLOP/s_of_dx_gemm_equivalent": 2.0 * T * d_in * d_out / t_bwd_dx / 1e15},
         "forward": {"us_per_call": t_fwd * 1e6},
         "forward_plus_backward": {"us_per_call": t_both * 1e6, "tokens_per_s": T / t_both},
+        "forward_plus_backward_with_dx": {"us_per_call": t_both_dx * 1e6, "tokens_per_s": T / t_both_dx},
         "steps": args.steps, "warmup": args.warmup, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
     }
     if not args.no_cpu_baseline:

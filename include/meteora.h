@@ -217,6 +217,11 @@ meteora_status meteora_linear_forward_group(const void* x, const meteora_group_m
  * The logits are recomputed from x and the packed weights exactly as the forward call for 64 < T <= 8192
  * computes them.  topk_idx / topk_w (both or neither): the routing the forward call returned, to be used
  * as it is; NULL ranks again from the recomputed logits (the same routing as that forward path's).
+ * dx[T,d_in] (storage type dt, optional): the gradient with respect to the module's input, for the modules
+ * in front of this one:  dx = dy*W + scale * sum_j w_j * ((dy*B_a^T)*A_a^T) + d_logits*W_gate^T  (base projection,
+ * selected adapters, gate).  It needs A[N,d_in,r], W_gate[d_in,N] and W_t = the base weight TRANSPOSED, stored
+ * [d_in,d_out] (the frozen base weight is kept in both orientations by a caller that trains); with dx == NULL
+ * these three may be NULL.  The gate term is computed from two-term bf16 splits (about 2^-16 of its size).
  * `packed` is the blob of meteora_pack_weights for these adapters; B is the stacked [N,r,d_out] tensor.
  * forward_ws (optional): the workspace in which meteora_linear_forward(_packed) ran on this same x, these
  * adapters and the same T, d_in, d_out, N, r, k, dt, not written to since.  For 64 < T <= 8192 that call leaves
@@ -236,6 +241,8 @@ meteora_status meteora_gate_backward(const void* x /*[T,d_in]*/, const void* dy 
                                      int T, int d_in, int d_out, int N, int r, int k, float scale, meteora_dtype dt,
                                      float* dW_gate /*[d_in,N]*/, float* dbias /*[N] or NULL*/,
                                      float* d_logits /*[T,N] or NULL*/,
+                                     const void* A /*[N,d_in,r] or NULL*/, const float* W_gate /*[d_in,N] or NULL*/,
+                                     const void* W_t /*[d_in,d_out] or NULL*/, void* dx /*[T,d_in] or NULL*/,
                                      const void* forward_ws /*or NULL*/, size_t forward_ws_bytes,
                                      void* ws, size_t ws_bytes, meteora_stream stream);
 

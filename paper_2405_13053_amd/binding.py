@@ -70,7 +70,7 @@ def load_library():
     lib.meteora_gate_backward_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
     lib.meteora_gate_backward.restype = i
     lib.meteora_gate_backward.argtypes = [vp, vp, vp, vp, vp, sz, vp, vp, vp, f, i, i, i, i, i, i, f, i, vp, vp, vp,
-                                          vp, sz, vp, sz, vp]
+                                          vp, vp, vp, vp, vp, sz, vp, sz, vp]
     lib.meteora_base_gemm.restype = i
     lib.meteora_base_gemm.argtypes = [vp, vp, i, i, i, i, vp, vp]
     lib.meteora_stage_count.restype = i
@@ -292,8 +292,10 @@ def gate_backward_workspace_bytes(T, d_in, d_out, N, r, k, dtype) -> int:
 
 def gate_backward(x, dy, gate_bias, B, packed, k: int, scale: float, labels=None, beta: float = 0.0,
                   topk_idx=None, topk_w=None, want_dbias: bool = True, want_d_logits: bool = False,
-                  ws: Optional[torch.Tensor] = None, forward_ws: Optional[torch.Tensor] = None):
-    """meteora_gate_backward: (dW_gate[d_in,N], dbias[N] or None, d_logits[T,N] or None), all fp32."""
+                  ws: Optional[torch.Tensor] = None, forward_ws: Optional[torch.Tensor] = None,
+                  A=None, W_gate=None, W_t=None, want_dx: bool = False):
+    """meteora_gate_backward: (dW_gate[d_in,N], dbias[N] or None, d_logits[T,N] or None), all fp32; with
+    want_dx (needs A, W_gate and W_t = W transposed, [d_in,d_out]) a fourth entry dx[T,d_in] in x's dtype."""
     T, d_in = x.shape
     N, r, d_out = B.shape
     _chk(x, "x"); _chk(dy, "dy", x.dtype, (T, d_out)); _chk(gate_bias, "gate_bias", torch.float32, (N,))
@@ -301,6 +303,13 @@ def gate_backward(x, dy, gate_bias, B, packed, k: int, scale: float, labels=None
     _chk(labels, "labels", torch.int32, (T,))
     _chk(topk_idx, "topk_idx", torch.int32, (T, k)); _chk(topk_w, "topk_w", torch.float32, (T, k))
     _chk(forward_ws, "forward_ws", torch.uint8)
+    dxo = None
+    if want_dx:
+        _chk(A, "A", x.dtype, (N, d_in, r)); _chk(W_gate, "W_gate", torch.float32, (d_in, N))
+        _chk(W_t, "W_t", x.dtype, (d_in, d_out))
+        if A is None or W_gate is None or W_t is None:
+            raise ValueError("want_dx needs A, W_gate and W_t")
+        dxo = torch.empty((T, d_in), dtype=x.dtype, device=x.device)
     need = gate_backward_workspace_bytes(T, d_in, d_out, N, r, k, x.dtype)
     if need == 0 and T > 0:
         raise MeteoraError(2, "meteora_gate_backward_workspace_bytes")
@@ -311,12 +320,14 @@ def gate_backward(x, dy, gate_bias, B, packed, k: int, scale: float, labels=None
     st = load_library().meteora_gate_backward(_p(x), _p(dy), _p(gate_bias), _p(B), _p(packed),
                                               0 if packed is None else packed.numel(), _p(topk_idx), _p(topk_w),
                                               _p(labels), float(beta), T, d_in, d_out, N, r, k, float(scale),
-                                              _dt(x), _p(dW), _p(db), _p(dl), _p(forward_ws),
+                                              _dt(x), _p(dW), _p(db), _p(dl), _p(A if want_dx else None),
+                                              _p(W_gate if want_dx else None), _p(W_t if want_dx else None),
+                                              _p(dxo), _p(forward_ws),
                                               0 if forward_ws is None else forward_ws.numel(), _p(ws), ws.numel(),
                                               _stream())
     if st != 0:
         raise MeteoraError(st, "meteora_gate_backward")
-    return dW, db, dl
+    return (dW, db, dl, dxo) if want_dx else (dW, db, dl)
 
 
 def base_gemm(x, W, out: Optional[torch.Tensor] = None):

@@ -588,10 +588,12 @@ meteora_status meteora_gate_backward(const void* x, const void* dy, const float*
                                      const void* packed, size_t packed_bytes, const int32_t* topk_idx,
                                      const float* topk_w, const int32_t* labels, float beta, int T, int d_in,
                                      int d_out, int N, int r, int k, float scale, meteora_dtype dt, float* dW_gate,
-                                     float* dbias, float* d_logits, const void* forward_ws, size_t forward_ws_bytes,
+                                     float* dbias, float* d_logits, const void* A, const float* W_gate,
+                                     const void* W_t, void* dx, const void* forward_ws, size_t forward_ws_bytes,
                                      void* ws, size_t ws_bytes, meteora_stream stream) {
     if (!x || !dy || !B || !packed || !dW_gate || (topk_idx == nullptr) != (topk_w == nullptr))
         return METEORA_ERR_INVALID_ARG;
+    if (dx != nullptr && (!A || !W_gate || !W_t)) return METEORA_ERR_INVALID_ARG;
     if (!shape_ok(T, d_in, d_out, N, r, k) || !isfinite(scale) || !isfinite(beta)) return METEORA_ERR_INVALID_ARG;
     if (dt != METEORA_BF16 && dt != METEORA_F32) return METEORA_ERR_INVALID_ARG;
     if (T == 0) return METEORA_OK;
@@ -600,7 +602,8 @@ meteora_status meteora_gate_backward(const void* x, const void* dy, const float*
         return METEORA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(dy) || !aligned16(B) || !aligned16(dW_gate) || (gate_bias && !aligned4(gate_bias)) ||
         (dbias && !aligned4(dbias)) || (d_logits && !aligned4(d_logits)) || (labels && !aligned4(labels)) ||
-        (topk_idx && (!aligned4(topk_idx) || !aligned4(topk_w))))
+        (topk_idx && (!aligned4(topk_idx) || !aligned4(topk_w))) ||
+        (dx && (!aligned16(dx) || !aligned16(A) || !aligned16(W_gate) || !aligned16(W_t))))
         return METEORA_ERR_UNSUPPORTED;
     const PackLayout P = pack_layout(d_in, d_out, N, r, bf16);
     if (!aligned256(packed) || packed_bytes < P.total) return METEORA_ERR_WORKSPACE;
@@ -615,7 +618,8 @@ meteora_status meteora_gate_backward(const void* x, const void* dy, const float*
         part_x = reinterpret_cast<const float*>(static_cast<const char*>(forward_ws) + F.dpart);
     }
     const hipError_t e = launch_gate_backward(x, dy, wcat, B, gate_bias, topk_idx, topk_w, labels, beta, T, d_in, d_out,
-                                              N, r, k, scale, dW_gate, dbias, d_logits, part_x, static_cast<char*>(ws),
+                                              N, r, k, scale, dW_gate, dbias, d_logits, part_x, A, W_gate, W_t, dx,
+                                              static_cast<char*>(ws),
                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? METEORA_OK : METEORA_ERR_HIP;
 }

@@ -15,6 +15,14 @@
 // into d_logits per token, gate_bwd_wgrad_kernel accumulates x^T d_logits over token slices with fp32 MFMAs
 // (a [d_in, T] x [T, 32] product whose x operand is not K-contiguous), and gate_bwd_reduce_kernel adds the
 // slices in order.
+//
+// Input gradient (optional): dx = dy W + scale * sum_j w_j (B_{a_j} dy) A_{a_j}^T + d_logits W_gate^T is the
+// forward's fused GEMM with the roles swapped: dy times W^T's storage (the caller's transposed copy
+// W_t[d_in, d_out]) with the K loop continued over an extension operand hx[T, E] against Xt[d_in, E]:
+//   columns a*r + q:        hx = scale * w * (B_a dy)_q for the selected adapters, else 0;   Xt[c] = A[a][c][q]
+//   next 3 blocks of 32:    hx = hi(d_logits) | hi(d_logits) | lo(d_logits);  Xt[c] = hi(W_gate[c]) | lo(W_gate[c]) | hi(W_gate[c])
+// (two-term bf16 splits, the lo * lo product dropped: the gate term to about 2^-16 of its size).
+// gate_bwd_dlogits_kernel writes hx, gate_bwd_pack_kernel writes Xt (W_gate changes with every optimizer step).
 #include <type_traits>
 #include "common.hpp"
 #include "kernels.hpp"
@@ -37,6 +45,8 @@ struct DlogitsArgs {
     const int32_t* labels;   // [T] or NULL
     float* dg;               // [T][32], columns >= N zero
     float* d_logits;         // [T,N] or NULL
+    bf16_t* hx;              // [T][ext] extension operand of the input-gradient GEMM, or NULL
+    int ext;                 // columns of hx: N*r + 96 rounded up to 64
     int S1, S2, CR, NR, T, N, r, k;
     float scale, beta;
 };
@@ -50,6 +60,7 @@ __global__ __launch_bounds__(kBwdThreads) void gate_bwd_dlogits_kernel(const Dlo
     __shared__ float s_w[kBwdTokens][kMaxTopK];
     __shared__ float s_dot[kBwdTokens][kMaxTopK][kChunks];
     __shared__ float s_dg[kBwdTokens][NP];
+    extern __shared__ __attribute__((aligned(16))) float s_u[];   // [kBwdTokens][k][r]: B_a dy, only when hx is written
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & (NP - 1), sub = lane / NP;
     const int t0 = blockIdx.x * kBwdTokens;
@@ -132,6 +143,11 @@ __global__ __launch_bounds__(kBwdThreads) void gate_bwd_dlogits_kernel(const Dlo
 #pragma unroll
         for (int q = 0; q < 4; ++q) d += h1[q] * u1[q];
         s_dot[tl][s][c] = d;
+        if (a.hx != nullptr) {
+            float* su = s_u + ((size_t)tl * k + s) * r + c * 8;
+            *reinterpret_cast<f32x4*>(su) = u0;
+            *reinterpret_cast<f32x4*>(su + 4) = u1;
+        }
     }
     __syncthreads();
 
@@ -158,6 +174,69 @@ __global__ __launch_bounds__(kBwdThreads) void gate_bwd_dlogits_kernel(const Dlo
         a.dg[(size_t)t * NP + col] = v;
         if (a.d_logits != nullptr && col < N) a.d_logits[(size_t)t * N + col] = v;
     }
+    if (a.hx == nullptr) return;
+
+    // ---- rows of hx: a thread owns 8 columns of one token ----
+    const int C8 = a.ext / 8, NR = N * r;
+    for (int e = threadIdx.x; e < kBwdTokens * C8; e += kBwdThreads) {
+        const int tl = e / C8, c0 = (e - tl * C8) * 8;
+        const int t = t0 + tl;
+        if (t >= T) continue;
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = 0.f;
+        if (c0 < NR) {                                       // the adapter part: scale * w * (B_a dy)
+            const int ad = c0 / r;
+            for (int sl = 0; sl < k; ++sl)
+                if (s_idx[tl][sl] == ad) {
+                    const float sw = a.scale * s_w[tl][sl];
+                    const float* su = s_u + ((size_t)tl * k + sl) * r + (c0 - ad * r);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = sw * su[i];
+                }
+        } else if (c0 < NR + 3 * NP) {                       // the gate part: hi | hi | lo of d_logits
+            const int term = (c0 - NR) / NP, n0 = (c0 - NR) - term * NP;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float d = s_dg[tl][n0 + i];            // columns >= N are not written above and hold 0 or the
+                const float dz = n0 + i < N ? d : 0.f;       // classification part of a padding lane: masked here
+                const float hi = static_cast<float>(static_cast<bf16_t>(dz));
+                v[i] = term == 2 ? dz - hi : hi;
+            }
+        }
+        u32x4 pk;
+        pk[0] = pack_bf16x2(v[0], v[1]); pk[1] = pack_bf16x2(v[2], v[3]);
+        pk[2] = pack_bf16x2(v[4], v[5]); pk[3] = pack_bf16x2(v[6], v[7]);
+        *reinterpret_cast<u32x4*>(a.hx + (size_t)t * a.ext + c0) = pk;
+    }
+}
+
+// Xt[c][ext] for the input-gradient GEMM: A[a][c][:] at columns a*r.., then hi | lo | hi of W_gate[c][:] in blocks
+// of 32 columns, zero elsewhere.  A thread owns 8 columns of one row c.
+__global__ __launch_bounds__(256) void gate_bwd_pack_kernel(const uint16_t* __restrict__ A,
+                                                             const float* __restrict__ W_gate, int d_in, int N, int r,
+                                                             int ext, uint16_t* __restrict__ Xt) {
+    const int C8 = ext / 8, NR = N * r;
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (size_t)d_in * C8) return;
+    const int c = (int)(e / C8), c0 = (int)(e - (size_t)c * C8) * 8;
+    u32x4 pk = {0u, 0u, 0u, 0u};
+    if (c0 < NR) {
+        const int ad = c0 / r, q0 = c0 - ad * r;
+        pk = *reinterpret_cast<const u32x4*>(A + ((size_t)ad * d_in + c) * r + q0);
+    } else if (c0 < NR + 3 * kBwdNP) {
+        const int term = (c0 - NR) / kBwdNP, n0 = (c0 - NR) - term * kBwdNP;
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float w = n0 + i < N ? W_gate[(size_t)c * N + n0 + i] : 0.f;
+            const float hi = static_cast<float>(static_cast<bf16_t>(w));
+            v[i] = term == 1 ? w - hi : hi;
+        }
+        pk[0] = pack_bf16x2(v[0], v[1]); pk[1] = pack_bf16x2(v[2], v[3]);
+        pk[2] = pack_bf16x2(v[4], v[5]); pk[3] = pack_bf16x2(v[6], v[7]);
+    }
+    *reinterpret_cast<u32x4*>(Xt + (size_t)c * ext + c0) = pk;
 }
 
 // ---- dW_gate partials: wpart[slice][c][32] = sum over the slice's tokens of x[t][c] * dg[t][:] ----
@@ -331,6 +410,9 @@ GateBackwardLayout gate_backward_layout(int T, int d_in, int d_out, int N, int r
     const int slices = ceil_div(T, wgrad_slice_tokens(T, d_in));
     L.wpart = take((size_t)slices * d_in * kBwdNP * sizeof(float));
     L.bpart = take((size_t)slices * kBwdNP * sizeof(float));
+    L.ext = (int)align_up((size_t)NR + 3 * kBwdNP, 64);
+    L.hx = take((size_t)T * L.ext * sizeof(uint16_t));
+    L.xt = take((size_t)d_in * L.ext * sizeof(uint16_t));
     L.total = off;
     return L;
 }
@@ -338,7 +420,9 @@ GateBackwardLayout gate_backward_layout(int T, int d_in, int d_out, int N, int r
 hipError_t launch_gate_backward(const void* x, const void* dy, const void* wcat, const void* B, const float* bias,
                                 const int32_t* idx_in, const float* w_in, const int32_t* labels, float beta, int T,
                                 int d_in, int d_out, int N, int r, int k, float scale, float* dW_gate, float* dbias,
-                                float* d_logits, const float* part_x_given, char* ws, hipStream_t stream) {
+                                float* d_logits, const float* part_x_given, const void* A, const float* W_gate,
+                                const void* W_t, void* dx, char* ws, hipStream_t stream) {
+    if ((dx != nullptr) && (!A || !W_gate || !W_t)) return hipErrorInvalidValue;
     if (!gate_backward_applies(T, d_in, d_out, N, r, true) || k < 1 || k > kMaxTopK || k > N)
         return hipErrorInvalidValue;
     const GateBackwardLayout L = gate_backward_layout(T, d_in, d_out, N, r);
@@ -356,10 +440,23 @@ hipError_t launch_gate_backward(const void* x, const void* dy, const void* wcat,
     DlogitsArgs a{};
     a.part_x = part_x; a.part_dy = part_dy; a.bias = bias; a.idx_in = idx_in; a.w_in = w_in; a.labels = labels;
     a.dg = dg; a.d_logits = d_logits;
+    a.hx = dx != nullptr ? reinterpret_cast<bf16_t*>(ws + L.hx) : nullptr;
+    a.ext = L.ext;
     a.S1 = gemm_dense_splits(T, d_in, CR); a.S2 = gemm_dense_splits(T, d_out, NR);
     a.CR = CR; a.NR = NR; a.T = T; a.N = N; a.r = r; a.k = k; a.scale = scale; a.beta = beta;
-    gate_bwd_dlogits_kernel<<<ceil_div(T, kBwdTokens), kBwdThreads, 0, stream>>>(a);
+    const size_t u_bytes = dx != nullptr ? (size_t)kBwdTokens * k * r * sizeof(float) : 0;   // at most 32 KB
+    gate_bwd_dlogits_kernel<<<ceil_div(T, kBwdTokens), kBwdThreads, u_bytes, stream>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (dx != nullptr) {
+        uint16_t* xt = reinterpret_cast<uint16_t*>(ws + L.xt);
+        const int64_t chunks = (int64_t)d_in * (L.ext / 8);
+        gate_bwd_pack_kernel<<<(unsigned)ceil_div64(chunks, 256), 256, 0, stream>>>((const uint16_t*)A, W_gate, d_in, N,
+                                                                                    r, L.ext, xt);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        // dx = dy * W_t^T continued over hx * Xt^T: the forward's GEMM with d_in and d_out swapped
+        e = launch_gemm(dy, W_t, T, d_out, d_in, true, ws + L.hx, L.ext, xt, L.ext, dx, 0, nullptr, stream);
+        if (e != hipSuccess) return e;
+    }
     const int slice_tokens = wgrad_slice_tokens(T, d_in);
     const int slices = ceil_div(T, slice_tokens);
     gate_bwd_wgrad_kernel<<<dim3(ceil_div(d_in, kWgCols), slices), 256, 0, stream>>>(

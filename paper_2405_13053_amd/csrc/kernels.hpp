@@ -133,14 +133,17 @@ hipError_t launch_gemm_decode_finish(const DecodeMember* mem, int G, int S, int 
 // [0, N) give that token no classification part.  ws: gate_backward_layout(...).total bytes.
 // part_x_given (optional): the K-split products x * Wcat^T that launch_route_dense_products left for this x
 // (same T, d_in, N, r); NULL computes them here.
+// dx (optional, bf16 [T, d_in]): the input gradient; needs A, W_gate and W_t = the base weight transposed,
+// [d_in, d_out].
 constexpr int kGateBackwardMaxTokens = 65536;
-struct GateBackwardLayout { size_t part_x, part_dy, dg, wpart, bpart, total; };
+struct GateBackwardLayout { size_t part_x, part_dy, dg, wpart, bpart, hx, xt, total; int ext; };
 bool gate_backward_applies(int T, int d_in, int d_out, int N, int r, bool bf16);
 GateBackwardLayout gate_backward_layout(int T, int d_in, int d_out, int N, int r);
 hipError_t launch_gate_backward(const void* x, const void* dy, const void* wcat, const void* B, const float* bias,
                                 const int32_t* idx_in, const float* w_in, const int32_t* labels, float beta, int T,
                                 int d_in, int d_out, int N, int r, int k, float scale, float* dW_gate, float* dbias,
-                                float* d_logits, const float* part_x_given, char* ws, hipStream_t stream);
+                                float* d_logits, const float* part_x_given, const void* A, const float* W_gate,
+                                const void* W_t, void* dx, char* ws, hipStream_t stream);
 
 // ---- base projection out = x * W^T (W stored [d_out, d_in]), optional fused LoRA expand ---
 // If hdense != NULL the contraction is extended by the columns of hdense against the stacked B

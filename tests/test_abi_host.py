@@ -198,9 +198,9 @@ def test_gate_backward_validation(lib):
     pkb = lib.meteora_packed_bytes(256, 256, 4, 8, BF16)
 
     def call(x=P, dy=P, B=P, pk=WS, pkb=pkb, idx=None, w=None, T=64, d_out=256, N=4, r=8, k=2, scale=2.0, beta=0.0,
-             dt=BF16, dW=P, ws=WS, wsb=BIG, fws=None, fwsb=0):
+             dt=BF16, dW=P, ws=WS, wsb=BIG, fws=None, fwsb=0, A=None, Wg=None, Wt=None, dx=None):
         return lib.meteora_gate_backward(x, dy, None, B, pk, pkb, idx, w, None, beta, T, 256, d_out, N, r, k, scale, dt,
-                                         dW, None, None, fws, fwsb, ws, wsb, None)
+                                         dW, None, None, A, Wg, Wt, dx, fws, fwsb, ws, wsb, None)
 
     assert call(T=0) == OK
     assert call(x=None) == INVALID and call(dy=None) == INVALID and call(B=None) == INVALID
@@ -214,6 +214,8 @@ def test_gate_backward_validation(lib):
     assert call(ws=None) == WORKSPACE and call(wsb=1024) == WORKSPACE
     assert call(T=128, fws=WS, fwsb=64) == WORKSPACE       # a forward workspace too small to hold the products
     assert call(T=0, fws=WS, fwsb=64) == OK
+    assert call(dx=P) == INVALID and call(dx=P, A=P, Wg=P) == INVALID    # the input gradient needs A, W_gate and W_t
+    assert call(dx=P, A=P, Wg=P, Wt=ODD) == UNSUPPORTED
 
 
 def test_base_gemm_validation(lib):

@@ -63,6 +63,49 @@ def test_gate_backward_matches_oracle(shape, beta):
     assert float(dl.sum(dim=1).abs().max()) <= 1e-5 * max(1.0, float(dl.abs().max()))
 
 
+@pytest.mark.parametrize("shape", BACKWARD_SHAPES, ids=lambda s: s.name)
+def test_gate_backward_input_gradient_matches_oracle(shape):
+    """dx (bf16 storage, fp32 accumulation: the forward's output bar, 5e-3 of the largest entry) with a
+    classification weight large enough that the gate term is a visible part of it; the other outputs are the
+    same bits as without dx."""
+    beta = 4.0
+    ops, dev, dy, labels = _case(shape, seed=74)
+    ref = oracle_bwd.gate_backward(ops["x"], dy, ops["W_gate"], ops["bias"], ops["A"], ops["B"], shape.k,
+                                   shape.scale, labels, beta, W=ops["W"])
+    W_t = dev["W"].t().contiguous()
+    dW, db, dl, dx = m.gate_backward(dev["x"], dev["dy"], dev["bias"], dev["B"], dev["packed"], shape.k, shape.scale,
+                                     labels=dev["labels"], beta=beta, want_d_logits=True, A=dev["A"],
+                                     W_gate=dev["W_gate"], W_t=W_t, want_dx=True)
+    dW2, db2, dl2 = m.gate_backward(dev["x"], dev["dy"], dev["bias"], dev["B"], dev["packed"], shape.k, shape.scale,
+                                    labels=dev["labels"], beta=beta, want_d_logits=True)
+    torch.cuda.synchronize()
+    assert torch.equal(dW, dW2) and torch.equal(db, db2) and torch.equal(dl, dl2)
+    assert _rel(dx, ref["dx"]) <= 5e-3
+    # the three roads separately visible: without the gate and adapter parts the error would be far above the bar
+    base_only = dy @ ops["W"].astype(np.float64)
+    assert np.abs(ref["dx"] - base_only).max() / np.abs(ref["dx"]).max() > 2e-2
+
+
+def test_gate_backward_input_gradient_gate_term_accuracy():
+    """The gate term alone (dy = 0: no base and no adapter part, d_logits = beta * (softmax - onehot)) is computed
+    from two-term bf16 splits, about 2^-16 of its size: what is left is the one bf16 rounding of dx, so nearly
+    every entry IS the oracle's value rounded to bf16 (single-term bf16 operands, 2^-8, would miss most)."""
+    shape = LS(200, 256, 192, 12, 8, 3, 2.0, "bf16", "zipf", "gate-term")
+    ops, dev, dy, labels = _case(shape, seed=75)
+    dy0 = np.zeros_like(dy)
+    ref = oracle_bwd.gate_backward(ops["x"], dy0, ops["W_gate"], ops["bias"], ops["A"], ops["B"], shape.k,
+                                   shape.scale, labels, 1.0, W=ops["W"])
+    out = m.gate_backward(dev["x"], torch.zeros_like(dev["dy"]), dev["bias"], dev["B"], dev["packed"], shape.k,
+                          shape.scale, labels=dev["labels"], beta=1.0, A=dev["A"], W_gate=dev["W_gate"],
+                          W_t=dev["W"].t().contiguous(), want_dx=True)
+    torch.cuda.synchronize()
+    assert np.abs(ref["dx"]).max() > 0
+    assert _rel(out[3], ref["dx"]) <= 5e-3
+    rounded = gen.round_to_bf16(ref["dx"].astype(np.float32))
+    got = out[3].to(torch.float32).cpu().numpy()
+    assert np.mean(got != rounded) <= 0.02
+
+
 def test_gate_backward_takes_the_forward_routing():
     """Given topk_idx / topk_w of the forward call the result equals the one from ranking again, and the routing
     the entry point would rank is the forward's (same logits, same routine)."""
