@@ -183,3 +183,49 @@ def test_gate_backward_rejects_what_it_does_not_take():
     assert m.gate_backward_workspace_bytes(64, 128, 128, 5, 8, 2, torch.float32) == 0
     assert m.gate_backward_workspace_bytes(64, 128, 128, 40, 8, 2, torch.bfloat16) == 0
     assert m.gate_backward_workspace_bytes(64, 128, 128, 5, 8, 2, torch.bfloat16) > 0
+
+
+def test_training_step_replays_from_a_hip_graph():
+    """Forward + gate gradients + dx captured once (no allocation by the library, no memset recorded) replay
+    bit-identically on new x and dy, with eager work between the replays."""
+    shape = LS(333, 512, 256, 12, 8, 2, 2.0, "bf16", "zipf", "graph-step")
+    ops, dev, dy, labels = _case(shape, seed=76)
+    bf = torch.bfloat16
+    W_t = dev["W"].t().contiguous()
+    ws_f = torch.empty(m.workspace_bytes(shape.T, shape.d_in, shape.d_out, shape.N, shape.r, shape.k, bf),
+                       dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(m.gate_backward_workspace_bytes(shape.T, shape.d_in, shape.d_out, shape.N, shape.r, shape.k, bf),
+                       dtype=torch.uint8, device="cuda")
+    x_in, dy_in = dev["x"].clone(), dev["dy"].clone()
+
+    def step(x, dyt, wsf, wsb):
+        out, idx, w = m.linear_forward(x, dev["W"], dev["W_gate"], dev["bias"], dev["A"], dev["B"], shape.k,
+                                       shape.scale, ws=wsf, return_routing=True, packed=dev["packed"])
+        grads = m.gate_backward(x, dyt, dev["bias"], dev["B"], dev["packed"], shape.k, shape.scale,
+                                labels=dev["labels"], beta=0.3, topk_idx=idx, topk_w=w, want_d_logits=True, ws=wsb,
+                                forward_ws=wsf, A=dev["A"], W_gate=dev["W_gate"], W_t=W_t, want_dx=True)
+        return (out,) + tuple(grads)
+
+    step(x_in, dy_in, ws_f, ws_b)            # first call sets the kernels' LDS attributes
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            held = step(x_in, dy_in, ws_f, ws_b)
+    torch.cuda.synchronize()
+    gen_t = torch.Generator(device="cuda").manual_seed(6)
+    for rep in range(3):
+        x_new = torch.randn(x_in.shape, generator=gen_t, device="cuda", dtype=torch.float32).to(bf)
+        dy_new = (torch.randn(dy_in.shape, generator=gen_t, device="cuda", dtype=torch.float32) / 16).to(bf)
+        ref = step(x_new, dy_new, torch.empty_like(ws_f), torch.empty_like(ws_b))   # eager, own workspaces
+        torch.cuda.synchronize()
+        x_in.copy_(x_new)
+        dy_in.copy_(dy_new)
+        for t in held:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("out", "dW_gate", "dbias", "d_logits", "dx"), held, ref):
+            assert torch.equal(a, b), f"replay {rep}: {name} differs from the eager call"
