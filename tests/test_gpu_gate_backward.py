@@ -153,27 +153,34 @@ def test_gate_backward_reads_the_forward_products(T):
         assert not torch.equal(c[0], a[0])
 
 
-def test_gate_backward_full_size_sampled():
-    """Config 2's layer (T = 4096, 4096 -> 4096, N = 28, r = 8, top-2): d_logits on sampled tokens against the
-    oracle, dW_gate and dbias through properties that hold at any size: dbias = column sums of d_logits,
-    sampled rows of dW_gate = x[:, c]^T d_logits in float64 from the library's own d_logits."""
-    seed, shapes = gen.config_layers(2)
-    shape = shapes[0]
+def _sampled_check(shape, seed, cols):
     ops, dev, dy, labels = _case(shape, seed=seed)
     dW, db, dl = m.gate_backward(dev["x"], dev["dy"], dev["bias"], dev["B"], dev["packed"], shape.k, shape.scale,
                                  labels=dev["labels"], beta=0.25, want_d_logits=True)
     torch.cuda.synchronize()
     rows = np.linspace(0, shape.T - 1, 96).astype(np.int64)
-    sub = {n: ops[n] for n in ("W_gate", "bias", "A", "B")}
-    ref = oracle_bwd.gate_backward(ops["x"][rows], dy[rows], sub["W_gate"], sub["bias"], sub["A"], sub["B"], shape.k,
+    ref = oracle_bwd.gate_backward(ops["x"][rows], dy[rows], ops["W_gate"], ops["bias"], ops["A"], ops["B"], shape.k,
                                    shape.scale, labels[rows], 0.25)
     got = dl[torch.from_numpy(rows).to("cuda")]
     assert _rel(got, ref["d_logits"]) <= TOL
     dl64 = dl.to(torch.float64)
     assert _rel(db, dl64.sum(dim=0).cpu().numpy()) <= 1e-5
-    cols = torch.tensor([0, 1, 127, 128, 2049, 4095], device="cuda")
+    cols = torch.tensor(cols, device="cuda")
     want = dev["x"][:, cols].to(torch.float64).T @ dl64
     assert _rel(dW[cols], want.cpu().numpy()) <= 1e-5
+
+
+def test_gate_backward_full_size_sampled():
+    """Config 2's layer (T = 4096, 4096 -> 4096, N = 28, r = 8, top-2): d_logits on sampled tokens against the
+    oracle, dW_gate and dbias through properties that hold at any size: dbias = column sums of d_logits,
+    sampled rows of dW_gate = x[:, c]^T d_logits in float64 from the library's own d_logits."""
+    seed, shapes = gen.config_layers(2)
+    _sampled_check(shapes[0], seed, [0, 1, 127, 128, 2049, 4095])
+
+
+def test_gate_backward_many_tokens_sampled():
+    """T = 40000 (wide product tiles, one K split, 313 token slices' worth of rows): index arithmetic at scale."""
+    _sampled_check(LS(40000, 320, 192, 28, 8, 2, 2.0, "bf16", "zipf", "T=40000"), 77, [0, 63, 64, 129, 319])
 
 
 def test_gate_backward_rejects_what_it_does_not_take():
