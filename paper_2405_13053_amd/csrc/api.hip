@@ -13,7 +13,7 @@ namespace {
 
 struct WsLayout {
     size_t wsplit, partials, chunk_counts, counts, offsets, bucket_tok, bucket_slot, topk_idx, topk_w, h32,
-        hdense, apack, hpart, splitk, btrans, wcat, dpart, gpart, total;
+        hdense, apack, hpart, splitk, btrans, wcat, dpart, gpart, spart, total;
     int ext_stride;   // columns of hdense: N*r rounded up to 64 (one K tile of the GEMM)
 };
 
@@ -26,6 +26,20 @@ bool shape_ok(int T, int d_in, int d_out, int N, int r, int k) {
 bool decode_fused_applies(int T, int d_in, int d_out, int N, int r, bool bf16) {
     return route_small_applies(T, r, bf16) && gemm_splitk_splits(T, d_in, d_out, bf16) > 0 &&
            route_dense_possible(d_in, N, r, bf16);
+}
+
+// Mid-sized batches whose 128 x 128 output tiles would leave most CUs idle (a few hundred tokens): the base
+// projection is split along K over workgroups like the routing products (fp32 tiles), and the reduction adds the
+// LoRA expand, as for decode.  Returns the number of K splits, 0 = the fused GEMM runs instead.
+int dense_midsplit_splits(int T, int d_in, int d_out, int N, int r, bool bf16) {
+    // measured on 4096 -> 4096 and 4096 -> 14336, T = 65 ... 2048: the split form wins up to about 160 output tiles
+    // of 128 x 128 (35.7 against 56.1 us at T = 65, 53.0 against 60.1 at T = 512 for 4096 -> 4096), beyond that the
+    // fp32 tiles it writes and reads back cost more than the idle CUs
+    const int64_t tiles = (int64_t)ceil_div(T, 128) * ceil_div(d_out, 128);
+    if (!route_dense_applies(T, d_in, N, r, bf16) || tiles > 160 || d_out % 8 != 0 || !gemm_dense_splitk_ok(T, d_in, d_out))
+        return 0;
+    const int S = gemm_dense_splits(T, d_in, d_out);
+    return S >= 2 ? S : 0;
 }
 
 bool shape_supported(int T, int d_in, int d_out, int N, int r, int k) {
@@ -60,6 +74,7 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     L.wcat = take(dense || decode3 ? prep_wcat_bytes(d_in, N, r, bf16) : 0);
     L.dpart = take(route_dense_part_bytes(T, d_in, N, r, bf16));
     L.gpart = take(decode3 ? (size_t)gemm_splitk_splits(T, d_in, d_out, bf16) * T * 3 * NP * sizeof(float) : 0);
+    L.spart = take((size_t)dense_midsplit_splits(T, d_in, d_out, N, r, bf16) * T * d_out * sizeof(float));
     L.total = off;
     return L;
 }
@@ -417,6 +432,22 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
         {
             StageScope sc(ST_GATE_LOGITS, st, tslot);
             METEORA_HIP(launch_route_dense_products(x, pk.wcat, T, d_in, N, r, dpart, st));
+        }
+        if (const int S = dense_midsplit_splits(T, d_in, d_out, N, r, bf16)) {
+            float* hs = at<float>(ws, L.h32);
+            {
+                StageScope sc(ST_GATE_TOPK, st, tslot);
+                METEORA_HIP(launch_route_dense_select(dpart, gate_bias, T, d_in, N, r, k, 1.0f, scale, idx, w, nullptr,
+                                                      L.ext_stride, st, hs));
+            }
+            DecodeMember mem{W, nullptr, gate_bias, A, B, d_out, at<float>(ws, L.spart), nullptr, hs, idx, w, out};
+            {
+                StageScope sc(ST_GEMM, st, tslot);
+                METEORA_HIP(launch_gemm_dense_splitk(x, W, T, d_in, d_out, mem.partial, st));
+            }
+            StageScope sc(ST_EXPAND, st, tslot);
+            METEORA_HIP(launch_gemm_decode_finish(&mem, 1, S, T, k, r, st));
+            return METEORA_OK;
         }
         {
             StageScope sc(ST_GATE_TOPK, st, tslot);

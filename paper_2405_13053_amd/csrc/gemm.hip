@@ -356,7 +356,9 @@ hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out,
             return launch_mfma<1, 1>(a, stream);
         }
         const int64_t big_tiles = (int64_t)ceil_div(T, 256) * ceil_div(d_out, 256);
-        if (T > 128 && big_tiles >= 128) return launch_mfma<4, 4>(a, stream);
+        // 256 x 256 tiles once they fill most of the 256 CUs; below that 128 x 128 tiles keep more CUs busy
+        // (T = 2048, 4096 -> 4096: 128 tiles of 256 x 256 take 109 us, 512 tiles of 128 x 128 take 98 us)
+        if (T > 128 && big_tiles >= 160) return launch_mfma<4, 4>(a, stream);
         if (T > 64) return launch_mfma<2, 2>(a, stream);
         return launch_mfma<1, 1>(a, stream);
     }

@@ -58,7 +58,9 @@ hipError_t launch_route_dense_products(const void* x, const void* wcat, int T, i
                                        hipStream_t stream);
 hipError_t launch_route_dense_select(const float* part, const float* bias, int T, int d_in, int N, int r, int k,
                                      float inv_temperature, float scale, int32_t* topk_idx, float* topk_w,
-                                     void* hdense, int ext_stride, hipStream_t stream);
+                                     void* hdense, int ext_stride, hipStream_t stream, float* hs = nullptr);
+// hs (optional): also write hs[T,k,r] = scale * w * h in fp32 (the operand of launch_gemm_decode_finish); hdense may
+// then be NULL.
 // the GEMM behind launch_route_dense_products: partial[split][T][rows] = x * Wcat^T over the split's K range
 bool gemm_dense_splitk_ok(int T, int d_in, int rows);
 int gemm_dense_splits(int T, int d_in, int rows);

@@ -27,7 +27,7 @@ constexpr int kSelNP = 32;   // gate columns per term in Wcat: the path takes N 
 __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
     const float* __restrict__ part, int S, int CR, const float* __restrict__ bias, int T, int N, int r, int k,
     float inv_temperature, float scale, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-    bf16_t* __restrict__ hdense, int ext_stride) {
+    bf16_t* __restrict__ hdense, int ext_stride, float* __restrict__ hs) {
     constexpr int NP = kSelNP;
     constexpr int TPP = 64 / NP;                     // tokens ranked per pass
     constexpr int G = kSelTokensPerWave / TPP;       // passes (groups) per wavefront
@@ -68,9 +68,10 @@ __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
         const int a = c0 / r;
         bool hit = false;
         float sw = 0.f;
+        int slot = 0;
         if (c0 < N * r)
             for (int s = 0; s < k; ++s)
-                if (s_idx[tl][s] == a) { hit = true; sw = scale * s_w[tl][s]; }
+                if (s_idx[tl][s] == a) { hit = true; sw = scale * s_w[tl][s]; slot = s; }
         u32x4 pk = {0u, 0u, 0u, 0u};
         if (hit) {
             f32x4 h0 = {0.f, 0.f, 0.f, 0.f}, h1 = {0.f, 0.f, 0.f, 0.f};
@@ -87,10 +88,15 @@ __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
                 for (int u = 0; u < 8; ++u)
                     if (s0 + u < S) { h0 += v0[u]; h1 += v1[u]; }
             }
+            if (hs != nullptr) {   // fp32 rows for the expand inside a split-K reduction
+                float* dst = hs + ((size_t)t * k + slot) * r + (c0 - a * r);
+                *reinterpret_cast<f32x4*>(dst) = f32x4{sw * h0[0], sw * h0[1], sw * h0[2], sw * h0[3]};
+                *reinterpret_cast<f32x4*>(dst + 4) = f32x4{sw * h1[0], sw * h1[1], sw * h1[2], sw * h1[3]};
+            }
             pk[0] = pack_bf16x2(sw * h0[0], sw * h0[1]); pk[1] = pack_bf16x2(sw * h0[2], sw * h0[3]);
             pk[2] = pack_bf16x2(sw * h1[0], sw * h1[1]); pk[3] = pack_bf16x2(sw * h1[2], sw * h1[3]);
         }
-        *reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride + c0) = pk;
+        if (hdense != nullptr) *reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride + c0) = pk;
     }
 }
 
@@ -117,12 +123,12 @@ hipError_t launch_route_dense_products(const void* x, const void* wcat, int T, i
 
 hipError_t launch_route_dense_select(const float* part, const float* bias, int T, int d_in, int N, int r, int k,
                                      float inv_temperature, float scale, int32_t* topk_idx, float* topk_w,
-                                     void* hdense, int ext_stride, hipStream_t stream) {
+                                     void* hdense, int ext_stride, hipStream_t stream, float* hs) {
     const int CR = prep_wcat_rows(N, r);
     const int S = gemm_dense_splits(T, d_in, CR);
     const int blocks = ceil_div(T, kSelTokens);
     route_dense_select_kernel<<<blocks, kSelThreads, 0, stream>>>(part, S, CR, bias, T, N, r, k, inv_temperature, scale,
-                                                                  topk_idx, topk_w, (bf16_t*)hdense, ext_stride);
+                                                                  topk_idx, topk_w, (bf16_t*)hdense, ext_stride, hs);
     return hipGetLastError();
 }
 

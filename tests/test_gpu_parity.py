@@ -263,6 +263,10 @@ DENSE_ROUTE_SHAPES = [
     LS(4097, 256, 136, 28, 8, 2, 2.0, "bf16", "uniform", "T=4097-wide-tiles"),
     LS(5000, 832, 264, 14, 16, 3, 2.0, "bf16", "zipf", "T=5000-r16-wide-tiles"),
     LS(260, 384, 136, 28, 8, 8, 1.0, "bf16", "uniform", "T=260-k8"),
+    # few output tiles: the base projection is split along K and the expand runs inside the reduction
+    LS(256, 4096, 4096, 28, 8, 2, 2.0, "bf16", "uniform", "T=256-split-K-projection"),
+    LS(200, 1024, 1096, 28, 8, 2, 2.0, "bf16", "zipf", "T=200-split-K-ragged-columns"),
+    LS(513, 2048, 520, 7, 32, 3, 0.5, "bf16", "uniform", "T=513-split-K-r32"),
 ]
 
 
