@@ -214,9 +214,10 @@ meteora_status meteora_linear_forward_group(const void* x, const meteora_group_m
  *     token t no classification part; labels == NULL or beta == 0 leaves the term out.
  * Outputs (fp32, overwritten):  d_logits[T,N] (may be NULL),  dW_gate[d_in,N] = x^T * d_logits,
  * dbias[N] = sum_t d_logits[t] (may be NULL).
- * The logits are recomputed from x and the packed weights exactly as the forward call for 64 < T <= 8192
- * computes them.  topk_idx / topk_w (both or neither): the routing the forward call returned, to be used
- * as it is; NULL ranks again from the recomputed logits (the same routing as that forward path's).
+ * The logits are recomputed from x and the packed weights with the forward call's arithmetic (three-term bf16
+ * split of W_gate, fp32 sums over K splits; the number of splits, and with it the last bits, can differ from the
+ * forward call's).  topk_idx / topk_w (both or neither): the routing the forward call returned, to be used
+ * as it is; NULL ranks again from the recomputed logits (the same routing unless two logits tie to fp32 accuracy).
  * dx[T,d_in] (storage type dt, optional): the gradient with respect to the module's input, for the modules
  * in front of this one:  dx = dy*W + scale * sum_j w_j * ((dy*B_a^T)*A_a^T) + d_logits*W_gate^T  (base projection,
  * selected adapters, gate).  It needs A[N,d_in,r], W_gate[d_in,N] and W_t = the base weight TRANSPOSED, stored

@@ -429,25 +429,28 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
     }
     if (dense) {
         float* dpart = at<float>(ws, L.dpart);
-        {
-            StageScope sc(ST_GATE_LOGITS, st, tslot);
-            METEORA_HIP(launch_route_dense_products(x, pk.wcat, T, d_in, N, r, dpart, st));
-        }
         if (const int S = dense_midsplit_splits(T, d_in, d_out, N, r, bf16)) {
+            // few output tiles: x * W^T and x * Wcat^T as fp32 K-split tiles of one launch, selection, then the
+            // reduction with the expand (the decode sequence with 128 x 128 tiles and the dense selection)
             float* hs = at<float>(ws, L.h32);
-            {
-                StageScope sc(ST_GATE_TOPK, st, tslot);
-                METEORA_HIP(launch_route_dense_select(dpart, gate_bias, T, d_in, N, r, k, 1.0f, scale, idx, w, nullptr,
-                                                      L.ext_stride, st, hs));
-            }
             DecodeMember mem{W, nullptr, gate_bias, A, B, d_out, at<float>(ws, L.spart), nullptr, hs, idx, w, out};
             {
                 StageScope sc(ST_GEMM, st, tslot);
-                METEORA_HIP(launch_gemm_dense_splitk(x, W, T, d_in, d_out, mem.partial, st));
+                METEORA_HIP(launch_gemm_dense_splitk_pair(x, W, d_out, mem.partial, pk.wcat, prep_wcat_rows(N, r), dpart, S,
+                                                          T, d_in, st));
+            }
+            {
+                StageScope sc(ST_GATE_TOPK, st, tslot);
+                METEORA_HIP(launch_route_dense_select(dpart, gate_bias, T, d_in, N, r, k, 1.0f, scale, idx, w, nullptr,
+                                                      L.ext_stride, st, hs, S));
             }
             StageScope sc(ST_EXPAND, st, tslot);
             METEORA_HIP(launch_gemm_decode_finish(&mem, 1, S, T, k, r, st));
             return METEORA_OK;
+        }
+        {
+            StageScope sc(ST_GATE_LOGITS, st, tslot);
+            METEORA_HIP(launch_route_dense_products(x, pk.wcat, T, d_in, N, r, dpart, st));
         }
         {
             StageScope sc(ST_GATE_TOPK, st, tslot);
@@ -643,13 +646,15 @@ meteora_status meteora_gate_backward(const void* x, const void* dy, const float*
     const void* wcat = static_cast<const char*>(packed) + P.wcat;
     // the forward call of a mid-sized batch leaves x * Wcat^T in its workspace: take it instead of computing it again
     const float* part_x = nullptr;
+    int part_x_splits = 0;
     if (forward_ws != nullptr && route_dense_applies(T, d_in, N, r, bf16)) {
         const WsLayout F = ws_layout(T, d_in, d_out, N, r, k, bf16);
         if (!aligned256(forward_ws) || forward_ws_bytes < F.total) return METEORA_ERR_WORKSPACE;
         part_x = reinterpret_cast<const float*>(static_cast<const char*>(forward_ws) + F.dpart);
+        part_x_splits = dense_midsplit_splits(T, d_in, d_out, N, r, bf16);   // 0: the products launch's own split count
     }
     const hipError_t e = launch_gate_backward(x, dy, wcat, B, gate_bias, topk_idx, topk_w, labels, beta, T, d_in, d_out,
-                                              N, r, k, scale, dW_gate, dbias, d_logits, part_x, A, W_gate, W_t, dx,
+                                              N, r, k, scale, dW_gate, dbias, d_logits, part_x, part_x_splits, A, W_gate, W_t, dx,
                                               static_cast<char*>(ws),
                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? METEORA_OK : METEORA_ERR_HIP;

@@ -9,19 +9,19 @@
 
 namespace meteora {
 
-// part[S][T][CR]; lane `col` (< N) of G token groups: token t0 + lt[i] (clamped to T-1).  Four splits'
-// loads are in flight at a time.  -0 is turned into +0 so that equal logits have equal ranking keys.
-template <int NP, int G>
+// part[S][T][CR]; lane `col` (< N) of G token groups: token t0 + lt[i] (clamped to T-1).  UNR splits'
+// loads are in flight at a time (the sum is taken in split order whatever UNR is).  -0 is turned into +0 so that equal logits have equal ranking keys.
+template <int NP, int G, int UNR = 4>
 __device__ __forceinline__ void dense_logits(const float* __restrict__ part, int S, int CR,
                                              const float* __restrict__ bias, int T, int N, int t0,
                                              const int (&lt)[G], int col, float (&g)[G]) {
 #pragma unroll
     for (int i = 0; i < G; ++i) g[i] = 0.f;
     if (col >= N) return;
-    for (int s0 = 0; s0 < S; s0 += 4) {
-        float v[4][3][G];
+    for (int s0 = 0; s0 < S; s0 += UNR) {
+        float v[UNR][3][G];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < UNR; ++u)
 #pragma unroll
             for (int term = 0; term < 3; ++term)
 #pragma unroll
@@ -30,7 +30,7 @@ __device__ __forceinline__ void dense_logits(const float* __restrict__ part, int
                     v[u][term][i] = s0 + u < S ? part[((size_t)(s0 + u) * T + t) * CR + term * NP + col] : 0.f;
                 }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < UNR; ++u)
 #pragma unroll
             for (int i = 0; i < G; ++i) g[i] += (v[u][2][i] + v[u][1][i]) + v[u][0][i];
     }

@@ -420,8 +420,8 @@ GateBackwardLayout gate_backward_layout(int T, int d_in, int d_out, int N, int r
 hipError_t launch_gate_backward(const void* x, const void* dy, const void* wcat, const void* B, const float* bias,
                                 const int32_t* idx_in, const float* w_in, const int32_t* labels, float beta, int T,
                                 int d_in, int d_out, int N, int r, int k, float scale, float* dW_gate, float* dbias,
-                                float* d_logits, const float* part_x_given, const void* A, const float* W_gate,
-                                const void* W_t, void* dx, char* ws, hipStream_t stream) {
+                                float* d_logits, const float* part_x_given, int part_x_splits, const void* A,
+                                const float* W_gate, const void* W_t, void* dx, char* ws, hipStream_t stream) {
     if ((dx != nullptr) && (!A || !W_gate || !W_t)) return hipErrorInvalidValue;
     if (!gate_backward_applies(T, d_in, d_out, N, r, true) || k < 1 || k > kMaxTopK || k > N)
         return hipErrorInvalidValue;
@@ -442,7 +442,8 @@ hipError_t launch_gate_backward(const void* x, const void* dy, const void* wcat,
     a.dg = dg; a.d_logits = d_logits;
     a.hx = dx != nullptr ? reinterpret_cast<bf16_t*>(ws + L.hx) : nullptr;
     a.ext = L.ext;
-    a.S1 = gemm_dense_splits(T, d_in, CR); a.S2 = gemm_dense_splits(T, d_out, NR);
+    a.S1 = (part_x_given != nullptr && part_x_splits > 0) ? part_x_splits : gemm_dense_splits(T, d_in, CR);
+    a.S2 = gemm_dense_splits(T, d_out, NR);
     a.CR = CR; a.NR = NR; a.T = T; a.N = N; a.r = r; a.k = k; a.scale = scale; a.beta = beta;
     const size_t u_bytes = dx != nullptr ? (size_t)kBwdTokens * k * r * sizeof(float) : 0;   // at most 32 KB
     gate_bwd_dlogits_kernel<<<ceil_div(T, kBwdTokens), kBwdThreads, u_bytes, stream>>>(a);

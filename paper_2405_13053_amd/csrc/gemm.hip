@@ -274,6 +274,33 @@ hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int 
     return dense_small_tiles(T) ? launch_dense<2, 2>(a, stream) : launch_dense<2, 5>(a, stream);
 }
 
+// Two matrices in one split-K launch of 128 x 128 tiles (few-tile batches): partial[s][T][rows] = x * W^T and
+// partial2[s][T][rows2] = x * W2^T over the K range of split s, the column tiles of both in one grid.
+hipError_t launch_gemm_dense_splitk_pair(const void* x, const void* W, int rows, float* partial, const void* W2,
+                                         int rows2, float* partial2, int S, int T, int d_in, hipStream_t stream) {
+    if (S < 1 || !gemm_dense_splitk_ok(T, d_in, rows) || !gemm_dense_splitk_ok(T, d_in, rows2)) return hipErrorInvalidValue;
+    GemmArgs a{};
+    a.x = (const bf16_t*)x; a.T = T; a.d_in = d_in;
+    a.splits = S; a.tiles_per_split = ceil_div(d_in / kGemmBK, S);
+    const int t1 = ceil_div(rows, 128);
+    a.seg[0] = {(const bf16_t*)W, partial, rows, 0};
+    a.seg[1] = {(const bf16_t*)W2, partial2, rows2, t1};
+    a.nseg = 2;
+    a.W = a.seg[0].W; a.d_out = rows; a.partial = partial;   // replaced per workgroup
+    constexpr int smem = gemm_w3_lds_bytes<2, 2>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 2>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    a.tiles_m = ceil_div(T, 128);
+    a.tiles_n = t1 + ceil_div(rows2, 128);
+    gemm_mfma_w3_kernel<2, 2><<<dim3(a.tiles_m * a.tiles_n, S), 256, smem, stream>>>(a);
+    return hipGetLastError();
+}
+
 // Decode in three launches: (1) the main K splits of x * W^T with the gate-term rows of Wcat as extra column
 // tiles (fp32 tiles into `partial` and `gpartial`), (2) routing and shrink on the gate tiles (route_small.hip),
 // (3) reduce + expand.  A group of G layers that share x runs through the same three launches: the column tiles

@@ -651,7 +651,8 @@ __device__ __forceinline__ void sgb_reads(std::integer_sequence<int, I...>) {
 }
 
 template <int MI, int NI>
-__global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) {
+    GemmArgs a = a_in;
     constexpr int BM = MI * 64, BN = NI * 64;
     constexpr int PX = BM / 32, PW = BN / 32;   // pieces per wavefront per tile
     constexpr int NR = MI + NI;                 // fragment reads per k-step
@@ -667,7 +668,17 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a) {
     const int lrow = lane & 31, khalf = lane >> 5;
     int tile_m, tile_n;
     tile_of_workgroup(blockIdx.x, a.tiles_m, a.tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int m0 = tile_m * BM;
+    int n0 = tile_n * BN;
+    if (a.nseg > 0) {   // uniform: the tile is an ordinary tile of its segment's matrix (split-K launches only)
+        int e = 0;
+        for (int i = 1; i < a.nseg; ++i)
+            if (tile_n >= a_in.seg[i].tile0) e = i;
+        n0 = (tile_n - a_in.seg[e].tile0) * BN;
+        a.W = a_in.seg[e].W;
+        a.d_out = a_in.seg[e].rows;
+        a.partial = a_in.seg[e].partial;
+    }
 
     f32x16 acc[MI][NI];
 #pragma unroll

@@ -58,14 +58,19 @@ hipError_t launch_route_dense_products(const void* x, const void* wcat, int T, i
                                        hipStream_t stream);
 hipError_t launch_route_dense_select(const float* part, const float* bias, int T, int d_in, int N, int r, int k,
                                      float inv_temperature, float scale, int32_t* topk_idx, float* topk_w,
-                                     void* hdense, int ext_stride, hipStream_t stream, float* hs = nullptr);
+                                     void* hdense, int ext_stride, hipStream_t stream, float* hs = nullptr,
+                                     int splits = 0);
 // hs (optional): also write hs[T,k,r] = scale * w * h in fp32 (the operand of launch_gemm_decode_finish); hdense may
-// then be NULL.
+// then be NULL.  splits (optional): the number of K splits in `part` if it is not launch_route_dense_products' own.
 // the GEMM behind launch_route_dense_products: partial[split][T][rows] = x * Wcat^T over the split's K range
 bool gemm_dense_splitk_ok(int T, int d_in, int rows);
 int gemm_dense_splits(int T, int d_in, int rows);
 hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int d_in, int rows, float* partial,
                                     hipStream_t stream);
+
+// the same for two matrices in one launch of 128 x 128 tiles, both with S splits
+hipError_t launch_gemm_dense_splitk_pair(const void* x, const void* W, int rows, float* partial, const void* W2,
+                                         int rows2, float* partial2, int S, int T, int d_in, hipStream_t stream);
 
 // ---- bucketing (Sec. 3.3: per-adapter token sets as index lists) --------------------------
 constexpr int kBucketChunkTokens = 64;   // tokens (k pairs each) whose pairs one workgroup histograms and scatters
@@ -134,7 +139,7 @@ hipError_t launch_gemm_decode_finish(const DecodeMember* mem, int G, int S, int 
 // logits.  labels (optional): per-token adapter label of the classification loss, weight beta; values outside
 // [0, N) give that token no classification part.  ws: gate_backward_layout(...).total bytes.
 // part_x_given (optional): the K-split products x * Wcat^T that launch_route_dense_products left for this x
-// (same T, d_in, N, r); NULL computes them here.
+// (same T, d_in, N, r) in part_x_splits K splits (0 = that launcher's own count); NULL computes them here.
 // dx (optional, bf16 [T, d_in]): the input gradient; needs A, W_gate and W_t = the base weight transposed,
 // [d_in, d_out].
 constexpr int kGateBackwardMaxTokens = 65536;
@@ -144,8 +149,8 @@ GateBackwardLayout gate_backward_layout(int T, int d_in, int d_out, int N, int r
 hipError_t launch_gate_backward(const void* x, const void* dy, const void* wcat, const void* B, const float* bias,
                                 const int32_t* idx_in, const float* w_in, const int32_t* labels, float beta, int T,
                                 int d_in, int d_out, int N, int r, int k, float scale, float* dW_gate, float* dbias,
-                                float* d_logits, const float* part_x_given, const void* A, const float* W_gate,
-                                const void* W_t, void* dx, char* ws, hipStream_t stream);
+                                float* d_logits, const float* part_x_given, int part_x_splits, const void* A,
+                                const float* W_gate, const void* W_t, void* dx, char* ws, hipStream_t stream);
 
 // ---- base projection out = x * W^T (W stored [d_out, d_in]), optional fused LoRA expand ---
 // If hdense != NULL the contraction is extended by the columns of hdense against the stacked B

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
     int lt[G];   // token index inside the workgroup
 #pragma unroll
     for (int i = 0; i < G; ++i) lt[i] = wave * kSelTokensPerWave + i * TPP + sub;
-    dense_logits<NP, G>(part, S, CR, bias, T, N, t0, lt, col, g);
+    dense_logits<NP, G, 8>(part, S, CR, bias, T, N, t0, lt, col, g);   // small batches come with up to 16 splits
     int sel_i[G];
     float sel_w[G];
     wave_topk_softmax<NP, G>(g, lane, N, k, inv_temperature, sel_i, sel_w);
@@ -76,16 +76,16 @@ __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
         if (hit) {
             f32x4 h0 = {0.f, 0.f, 0.f, 0.f}, h1 = {0.f, 0.f, 0.f, 0.f};
             const float* src = part + (size_t)t * CR + 3 * NP + c0;
-            for (int s0 = 0; s0 < S; s0 += 8) {   // splits in order, 16 loads in flight
-                f32x4 v0[8], v1[8];
+            for (int s0 = 0; s0 < S; s0 += 16) {   // splits in order, 32 loads in flight
+                f32x4 v0[16], v1[16];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < 16; ++u) {
                     const float* p = src + (size_t)min(s0 + u, S - 1) * T * CR;
                     v0[u] = *reinterpret_cast<const f32x4*>(p);
                     v1[u] = *reinterpret_cast<const f32x4*>(p + 4);
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
+                for (int u = 0; u < 16; ++u)
                     if (s0 + u < S) { h0 += v0[u]; h1 += v1[u]; }
             }
             if (hs != nullptr) {   // fp32 rows for the expand inside a split-K reduction
@@ -123,9 +123,9 @@ hipError_t launch_route_dense_products(const void* x, const void* wcat, int T, i
 
 hipError_t launch_route_dense_select(const float* part, const float* bias, int T, int d_in, int N, int r, int k,
                                      float inv_temperature, float scale, int32_t* topk_idx, float* topk_w,
-                                     void* hdense, int ext_stride, hipStream_t stream, float* hs) {
+                                     void* hdense, int ext_stride, hipStream_t stream, float* hs, int splits) {
     const int CR = prep_wcat_rows(N, r);
-    const int S = gemm_dense_splits(T, d_in, CR);
+    const int S = splits > 0 ? splits : gemm_dense_splits(T, d_in, CR);
     const int blocks = ceil_div(T, kSelTokens);
     route_dense_select_kernel<<<blocks, kSelThreads, 0, stream>>>(part, S, CR, bias, T, N, r, k, inv_temperature, scale,
                                                                   topk_idx, topk_w, (bf16_t*)hdense, ext_stride, hs);

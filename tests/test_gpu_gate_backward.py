@@ -129,11 +129,13 @@ def test_gate_backward_takes_the_forward_routing():
     assert not torch.equal(c[2], d[2])
 
 
-@pytest.mark.parametrize("T", [300, 40])
-def test_gate_backward_reads_the_forward_products(T):
-    """With the forward call's workspace the products of x are not computed again: same bits as without it
-    (T = 300: taken from the workspace; T = 40: that forward path leaves none, the argument is ignored)."""
-    shape = LS(T, 256, 192, 12, 8, 3, 2.0, "bf16", "zipf", "forward-ws")
+@pytest.mark.parametrize("T,d_in,d_out,same_bits", [(300, 256, 192, True), (40, 256, 192, True), (300, 1024, 512, False)])
+def test_gate_backward_reads_the_forward_products(T, d_in, d_out, same_bits):
+    """With the forward call's workspace the products of x are not computed again.  T = 300, 256 -> 192: taken from
+    the workspace, same bits as without it; T = 40: that forward path leaves none, the argument is ignored;
+    T = 300, 1024 -> 512: the forward ran them inside its split-K projection launch with another number of K
+    splits, so the sums differ in their last bits: equal to fp32 accuracy, and to the oracle as ever."""
+    shape = LS(T, d_in, d_out, 12, 8, 3, 2.0, "bf16", "zipf", "forward-ws")
     ops, dev, dy, labels = _case(shape, seed=73)
     ws = torch.empty(m.workspace_bytes(T, shape.d_in, shape.d_out, shape.N, shape.r, shape.k, torch.bfloat16),
                      dtype=torch.uint8, device="cuda")
@@ -145,7 +147,14 @@ def test_gate_backward_reads_the_forward_products(T):
                         labels=dev["labels"], beta=0.3, topk_idx=idx, topk_w=w, want_d_logits=True, forward_ws=ws)
     torch.cuda.synchronize()
     for u, v in zip(a, b):
-        assert torch.equal(u, v)
+        if same_bits:
+            assert torch.equal(u, v)
+        else:
+            assert float((u - v).abs().max()) <= 1e-5 * float(u.abs().max())
+    if not same_bits:
+        ref = oracle_bwd.gate_backward(ops["x"], dy, ops["W_gate"], ops["bias"], ops["A"], ops["B"], shape.k,
+                                       shape.scale, labels, 0.3)
+        assert _rel(b[0], ref["dW_gate"]) <= TOL and _rel(b[2], ref["d_logits"]) <= TOL
     if T > 64:   # and it is really read: a cleared workspace changes the result
         ws.zero_()
         c = m.gate_backward(dev["x"], dev["dy"], dev["bias"], dev["B"], dev["packed"], shape.k, shape.scale,

@@ -201,13 +201,22 @@ def test_linear_forward_matches_oracle(shape):
     _check_layer(shape, seed=41)
 
 
-def test_linear_forward_zero_B_is_base_and_deterministic():
-    shape = LS(200, 512, 520, 28, 8, 2, 2.0, "bf16")
+@pytest.mark.parametrize("d_in,same_kernel", [(128, True), (512, False)])
+def test_linear_forward_zero_B_is_base_and_deterministic(d_in, same_kernel):
+    """B = 0: the layer is the base projection.  d_in = 128: the same GEMM kernel as meteora_base_gemm runs, equal
+    bits; d_in = 512: this batch's projection is split along K (other fp32 summation order than the one-sweep
+    base GEMM), so the bf16 results agree up to the rounding of sums that differ in their last bits."""
+    shape = LS(200, d_in, 520, 28, 8, 2, 2.0, "bf16")
     ops, dev = util.make_case(shape, seed=42)
     zB = torch.zeros_like(dev["B"])
     y0 = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], None, dev["A"], zB, 2, 2.0)
     yb = m.base_gemm(dev["x"], dev["W"])
-    assert torch.equal(y0, yb)
+    if same_kernel:
+        assert torch.equal(y0, yb)
+    else:
+        diff = (y0.float() - yb.float()).abs()
+        assert float((diff / yb.float().abs().clamp_min(1e-3)).max()) <= 2.0 ** -7      # one bf16 ulp
+        assert float((diff > 0).float().mean()) <= 0.02
     y1 = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], None, dev["A"], dev["B"], 2, 2.0)
     y2 = m.linear_forward(dev["x"], dev["W"], dev["W_gate"], None, dev["A"], dev["B"], 2, 2.0)
     assert torch.equal(y1, y2)
