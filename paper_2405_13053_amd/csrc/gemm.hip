@@ -206,15 +206,16 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
         const size_t n8 = (size_t)a.T * a.d_out / 8;
         gemm_splitk_reduce_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, stream>>>(a.partial, nsplit, a.T, a.d_out,
                                                                                    a.out, a.accumulate);
-    } else if (dma_ok && MI == 4 && NI == 4) {
+    } else if (dma_ok && ((MI == 4 && NI == 4) || (MI == 2 && NI == 2))) {
+        constexpr int M3 = MI == 4 ? 4 : 2;   // the instantiations of the three-deep-ring kernel that exist
         static bool w3_attr_set = false;
         if (!w3_attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<4, 4>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, gemm_w3_lds_bytes<4, 4>());
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<M3, M3>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, gemm_w3_lds_bytes<M3, M3>());
             if (e != hipSuccess) return e;
             w3_attr_set = true;
         }
-        gemm_mfma_w3_kernel<4, 4><<<a.tiles_m * a.tiles_n, 256, gemm_w3_lds_bytes<4, 4>(), stream>>>(a);
+        gemm_mfma_w3_kernel<M3, M3><<<a.tiles_m * a.tiles_n, 256, gemm_w3_lds_bytes<M3, M3>(), stream>>>(a);
     } else if (dma_ok) {
         gemm_mfma_dma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
     } else {
