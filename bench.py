@@ -6,11 +6,14 @@ so their kernel-side layouts are packed once before the timed region (meteora_pa
 every step calls meteora_linear_forward_packed; the same loop with per-call packing
 (meteora_linear_forward) is timed as well and reported beside it.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layer 0] [--no-cpu-baseline] [--graph]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layer 0] [--tokens T] [--no-cpu-baseline] [--graph]
 
 The defaults (1000 timed steps after 100 warm-up steps, about 0.15 s) reach the steady state of the
 clocks; runs of a few dozen steps measure 4-5% slower.  --graph also replays the step from a captured
 HIP graph (works, tested; eager enqueue is faster because the host stays ahead of the GPU).
+
+--tokens T runs the configuration's layer shapes with T tokens instead of its own batch (for the batch sizes
+between decode and prefill; the headline workload is the configuration's own T).
 
 --layer -1 runs every layer of the configuration one after the other per step (config 5: the seven
 projections of a Llama3-8B block, each a MeteoRA layer with its own gate and adapters, fed the same
@@ -75,6 +78,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="run the configuration's layer shapes with this many tokens instead of its own T")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a captured HIP graph (reported as hip_graph)")
@@ -90,6 +95,9 @@ def main():
 
     torch.cuda.set_device(0)
     seed, layers = gen.config_layers(args.config)
+    if args.tokens > 0:
+        import dataclasses
+        layers = [dataclasses.replace(sh, T=args.tokens) for sh in layers]
     which = list(range(len(layers))) if args.layer < 0 else [args.layer]
     dt_of = lambda sh: torch.bfloat16 if sh.dtype == "bf16" else torch.float32
     calls = []   # one entry per layer: everything a call needs, resident on the GPU
@@ -166,7 +174,7 @@ def main():
     roofline = {"kernel": "base GEMM (bf16 MFMA)" if shape.dtype == "bf16" else "base GEMM (fp32)",
                 "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_MFMA_BF16_TFLOPS,
-                "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get((args.config, args.layer)),
+                "traffic": None if args.tokens > 0 else MEASURED_GEMM_TRAFFIC_BYTES.get((args.config, args.layer)),
                 "algorithmic_bytes": alg["gemm"]["bytes"], "us": gemm_us}
     per_stage = {}
     # mid-sized batches: one launch computes the gate logits and the shrink (no bucket / shrink stage is timed);
