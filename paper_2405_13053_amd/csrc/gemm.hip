@@ -244,6 +244,7 @@ int gemm_dense_splits(int T, int d_in, int rows) {
     const int tiles = ceil_div(T, 128) * ceil_div(rows, small ? 128 : 320), nk = d_in / kGemmBK;
     int S = ((small ? 384 : 256) + tiles / 2) / tiles;
     if (S > nk / 4) S = nk / 4;                // at least 4 K tiles per split
+    if (S > 8) S = 8;                          // more splits cost the kernel that adds them more than they save here
     return S < 1 ? 1 : S;
 }
 
