@@ -228,7 +228,7 @@ meteora_status meteora_linear_forward_group(const void* x, const meteora_group_m
  * adapters and the same T, d_in, d_out, N, r, k, dt, not written to since.  For 64 < T <= 8192 that call leaves
  * its products of x with the packed gate and A operands there and they are read instead of being computed
  * again (one launch less); for other T the argument is ignored.  The caller vouches for the contents.
- * Limits: dt == METEORA_BF16, N <= 32, r % 8 == 0, d_in % 64 == 0, d_out % 64 == 0, 3*32 + N*r <= 320,
+ * Limits: dt == METEORA_BF16, N <= 32, r % 8 == 0, d_in % 64 == 0, d_out % 64 == 0, 3*32 + N*r <= 640,
  * T <= 65536; otherwise METEORA_ERR_UNSUPPORTED (meteora_gate_backward_workspace_bytes returns 0).
  * All pointers but the host-side scalars are device memory; ws as for the other entry points.
  */

@@ -27,6 +27,7 @@ BACKWARD_SHAPES = [
     LS(1000, 1088, 576, 28, 8, 2, 2.0, "bf16", "zipf", "T=1000-ragged-K17"),
     LS(260, 384, 128, 28, 8, 8, 1.0, "bf16", "uniform", "T=260-k8"),
     LS(4500, 192, 320, 14, 16, 3, 2.0, "bf16", "zipf", "T=4500-r16-wide-tiles"),
+    LS(300, 512, 256, 28, 16, 2, 2.0, "bf16", "uniform", "T=300-r16-N28-544-rows"),
 ]
 
 

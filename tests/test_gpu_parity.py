@@ -242,6 +242,7 @@ SMALL_BATCH_SHAPES = [
     LS(7, 264, 136, 5, 16, 1, 1.0, "bf16", "zipf", "T=7-r16-top1-ragged"),
     LS(64, 1024, 520, 64, 32, 8, 0.5, "bf16", "uniform", "T=64-N64-r32-k8"),
     LS(33, 5120, 264, 28, 8, 2, 2.0, "bf16", "zipf", "T=33-decode-shape"),
+    LS(48, 1024, 520, 28, 16, 2, 2.0, "bf16", "uniform", "T=48-r16-N28-three-launch"),
 ]
 
 
@@ -276,6 +277,11 @@ DENSE_ROUTE_SHAPES = [
     LS(256, 4096, 4096, 28, 8, 2, 2.0, "bf16", "uniform", "T=256-split-K-projection"),
     LS(200, 1024, 1096, 28, 8, 2, 2.0, "bf16", "zipf", "T=200-split-K-ragged-columns"),
     LS(513, 2048, 520, 7, 32, 3, 0.5, "bf16", "uniform", "T=513-split-K-r32"),
+    # 28 adapters of rank 16: 544 rows of Wcat, several column tiles of the routing products
+    LS(70, 512, 264, 28, 16, 2, 2.0, "bf16", "zipf", "T=70-r16-N28-split-K"),
+    LS(1000, 1088, 520, 28, 16, 2, 2.0, "bf16", "uniform", "T=1000-r16-N28"),
+    LS(4500, 256, 136, 28, 16, 3, 2.0, "bf16", "zipf", "T=4500-r16-N28-two-wide-tiles"),
+    LS(300, 320, 200, 32, 16, 4, 1.0, "bf16", "uniform", "T=300-r16-N32-608-rows"),
 ]
 
 
