@@ -25,6 +25,9 @@ constexpr int kSelThreads = kSelTokens / kSelTokensPerWave * 64;
 constexpr int kWcatMaxRows = 640;
 constexpr int kSelNP = 32;   // gate columns per term in Wcat: the path takes N <= 32 only (more adapters exceed its row limit)
 
+// WIDE: twice as many K splits' loads in flight (batches of a few hundred tokens come with up to 8 splits; with 4 or
+// fewer the narrow form is about 1 us faster)
+template <bool WIDE>
 __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
     const float* __restrict__ part, int S, int CR, const float* __restrict__ bias, int T, int N, int r, int k,
     float inv_temperature, float scale, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
@@ -42,7 +45,7 @@ __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
     int lt[G];   // token index inside the workgroup
 #pragma unroll
     for (int i = 0; i < G; ++i) lt[i] = wave * kSelTokensPerWave + i * TPP + sub;
-    dense_logits<NP, G, 8>(part, S, CR, bias, T, N, t0, lt, col, g);   // small batches come with up to 16 splits
+    dense_logits<NP, G, WIDE ? 8 : 4>(part, S, CR, bias, T, N, t0, lt, col, g);
     int sel_i[G];
     float sel_w[G];
     wave_topk_softmax<NP, G>(g, lane, N, k, inv_temperature, sel_i, sel_w);
@@ -77,16 +80,21 @@ __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
         if (hit) {
             f32x4 h0 = {0.f, 0.f, 0.f, 0.f}, h1 = {0.f, 0.f, 0.f, 0.f};
             const float* src = part + (size_t)t * CR + 3 * NP + c0;
-            for (int s0 = 0; s0 < S; s0 += 16) {   // splits in order, 32 loads in flight
-                f32x4 v0[16], v1[16];
+            constexpr int HU = WIDE ? 16 : 8;
+            for (int s0 = 0; s0 < S; s0 += HU) {   // splits in order, 2 * HU loads in flight
+                f32x4 v0[HU], v1[HU];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    const float* p = src + (size_t)min(s0 + u, S - 1) * T * CR;
-                    v0[u] = *reinterpret_cast<const f32x4*>(p);
-                    v1[u] = *reinterpret_cast<const f32x4*>(p + 4);
+                for (int u = 0; u < HU; ++u) {
+                    v0[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    v1[u] = v0[u];
+                    if (s0 + u < S) {   // uniform: no loads beyond the last split
+                        const float* p = src + (size_t)(s0 + u) * T * CR;
+                        v0[u] = *reinterpret_cast<const f32x4*>(p);
+                        v1[u] = *reinterpret_cast<const f32x4*>(p + 4);
+                    }
                 }
 #pragma unroll
-                for (int u = 0; u < 16; ++u)
+                for (int u = 0; u < HU; ++u)
                     if (s0 + u < S) { h0 += v0[u]; h1 += v1[u]; }
             }
             if (hs != nullptr) {   // fp32 rows for the expand inside a split-K reduction
@@ -130,8 +138,14 @@ hipError_t launch_route_dense_select(const float* part, const float* bias, int T
     const int CR = prep_wcat_rows(N, r);
     const int S = splits > 0 ? splits : gemm_dense_splits(T, d_in, CR);
     const int blocks = ceil_div(T, kSelTokens);
-    route_dense_select_kernel<<<blocks, kSelThreads, 0, stream>>>(part, S, CR, bias, T, N, r, k, inv_temperature, scale,
-                                                                  topk_idx, topk_w, (bf16_t*)hdense, ext_stride, hs);
+    if (S > 4)
+        route_dense_select_kernel<true><<<blocks, kSelThreads, 0, stream>>>(part, S, CR, bias, T, N, r, k, inv_temperature,
+                                                                            scale, topk_idx, topk_w, (bf16_t*)hdense,
+                                                                            ext_stride, hs);
+    else
+        route_dense_select_kernel<false><<<blocks, kSelThreads, 0, stream>>>(part, S, CR, bias, T, N, r, k, inv_temperature,
+                                                                             scale, topk_idx, topk_w, (bf16_t*)hdense,
+                                                                             ext_stride, hs);
     return hipGetLastError();
 }
 
