@@ -436,8 +436,8 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
             DecodeMember mem{W, nullptr, gate_bias, A, B, d_out, at<float>(ws, L.spart), nullptr, hs, idx, w, out};
             {
                 StageScope sc(ST_GEMM, st, tslot);
-                METEORA_HIP(launch_gemm_dense_splitk_pair(x, W, d_out, mem.partial, pk.wcat, prep_wcat_rows(N, r), dpart, S,
-                                                          T, d_in, st));
+                const DenseOperand two[2] = {{W, d_out, mem.partial}, {pk.wcat, prep_wcat_rows(N, r), dpart}};
+                METEORA_HIP(launch_gemm_dense_splitk_multi(x, two, 2, S, T, d_in, st));
             }
             {
                 StageScope sc(ST_GATE_TOPK, st, tslot);
@@ -500,15 +500,34 @@ bool group_fused(const meteora_group_member* m, int G, int T, int d_in, int N, i
     return true;
 }
 
+// Second fused form: a few hundred tokens, every member on the dense routing path with packed weights, few output
+// tiles in all: the projections and routing products of all members as K-split tiles of one launch, one selection
+// launch, one reduction with the expands.  Returns the number of K splits, 0 = not this form.
+int group_mid_splits(const int* d_out, const bool* packed, int G, int T, int d_in, int N, int r, bool bf16) {
+    if (G < 2 || G > kMaxDecodeGroup || !route_dense_applies(T, d_in, N, r, bf16)) return 0;
+    const int cat_rows = prep_wcat_rows(N, r);
+    int64_t tiles = 0;
+    for (int g = 0; g < G; ++g) {
+        if (!packed[g] || d_out[g] % 8 != 0 || !gemm_dense_splitk_ok(T, d_in, d_out[g])) return 0;
+        tiles += (int64_t)ceil_div(T, 128) * (ceil_div(d_out[g], 128) + ceil_div(cat_rows, 128));
+    }
+    if (tiles > 320) return 0;   // beyond: member by member (each on the path its own size selects)
+    const int nk = d_in / 64;
+    int S = (int)((384 + tiles / 2) / tiles);
+    if (S > nk / 4) S = nk / 4;
+    if (S > 8) S = 8;
+    return S < 1 ? 1 : S;
+}
+
 struct GroupLayout { size_t partial[kMaxDecodeGroup], gpart[kMaxDecodeGroup], hs[kMaxDecodeGroup], idx[kMaxDecodeGroup],
                             w[kMaxDecodeGroup], total; int S; };
 
-GroupLayout group_layout(const int* d_out, int G, int T, int d_in, int N, int r, int k) {
+// gate_rows: columns of gpart per member (the gate terms for decode, every row of Wcat for the second form)
+GroupLayout group_layout(const int* d_out, int G, int T, int d_in, int N, int r, int k, int S, int gate_rows) {
     GroupLayout L{};
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    const int gate_rows = 3 * padded_adapters(N);
-    L.S = gemm_group_splits(T, d_in, d_out, G, gate_rows);
+    L.S = S;
     for (int g = 0; g < G; ++g) {
         L.partial[g] = take((size_t)L.S * T * d_out[g] * sizeof(float));
         L.gpart[g] = take((size_t)L.S * T * gate_rows * sizeof(float));
@@ -536,8 +555,17 @@ extern "C" size_t meteora_group_workspace_bytes(const int* d_out, int G, int T, 
         fused = fused && decode_fused_applies(T, d_in, d_out[g], N, r, bf16);
     }
     if (fused) {
-        const size_t f = group_layout(d_out, G, T, d_in, N, r, k).total + 256;
+        const int gate_rows = 3 * padded_adapters(N);
+        const size_t f = group_layout(d_out, G, T, d_in, N, r, k, gemm_group_splits(T, d_in, d_out, G, gate_rows),
+                                      gate_rows).total + 256;
         need = f > need ? f : need;
+    }
+    if (G >= 2 && G <= kMaxDecodeGroup) {
+        bool all_packed[kMaxDecodeGroup] = {true, true, true, true};   // sized as if packed: the larger need
+        if (const int S = group_mid_splits(d_out, all_packed, G, T, d_in, N, r, bf16)) {
+            const size_t f = group_layout(d_out, G, T, d_in, N, r, k, S, prep_wcat_rows(N, r)).total + 256;
+            need = f > need ? f : need;
+        }
     }
     return need;
 }
@@ -566,6 +594,36 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
         return METEORA_ERR_WORKSPACE;
     if (T == 0) return METEORA_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    bool is_packed[64];
+    for (int g = 0; g < G; ++g) is_packed[g] = members[g].packed != nullptr;
+    if (const int S = (G <= kMaxDecodeGroup ? group_mid_splits(d_outs, is_packed, G, T, d_in, N, r, bf16) : 0)) {
+        const int cat_rows = prep_wcat_rows(N, r);
+        const GroupLayout L = group_layout(d_outs, G, T, d_in, N, r, k, S, cat_rows);
+        DecodeMember mem[kMaxDecodeGroup];
+        DenseOperand ops[2 * kMaxDecodeGroup];
+        for (int g = 0; g < G; ++g) {
+            const meteora_group_member& m = members[g];
+            const PackLayout P = pack_layout(d_in, m.d_out, N, r, bf16);
+            mem[g] = DecodeMember{m.W, at<void>(const_cast<void*>(m.packed), P.wcat), m.gate_bias, m.A, m.B, m.d_out,
+                                  at<float>(ws, L.partial[g]), at<float>(ws, L.gpart[g]), at<float>(ws, L.hs[g]),
+                                  m.topk_idx_out ? m.topk_idx_out : at<int32_t>(ws, L.idx[g]),
+                                  m.topk_w_out ? m.topk_w_out : at<float>(ws, L.w[g]), m.out};
+            ops[2 * g] = {mem[g].W, m.d_out, mem[g].partial};
+            ops[2 * g + 1] = {mem[g].wg3, cat_rows, mem[g].gpartial};
+        }
+        const int tslot = timing_begin_call();
+        {
+            StageScope sc(ST_GEMM, st, tslot);
+            METEORA_HIP(launch_gemm_dense_splitk_multi(x, ops, 2 * G, S, T, d_in, st));
+        }
+        {
+            StageScope sc(ST_GATE_TOPK, st, tslot);
+            METEORA_HIP(launch_route_dense_select_group(mem, G, S, T, N, r, k, 1.0f, scale, st));
+        }
+        StageScope sc(ST_EXPAND, st, tslot);
+        METEORA_HIP(launch_gemm_decode_finish(mem, G, S, T, k, r, st));
+        return METEORA_OK;
+    }
     if (!group_fused(members, G, T, d_in, N, r, bf16)) {
         // the same result one layer after the other (they share the workspace, which the stream order allows)
         for (int g = 0; g < G; ++g) {
@@ -577,7 +635,9 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
         }
         return METEORA_OK;
     }
-    const GroupLayout L = group_layout(d_outs, G, T, d_in, N, r, k);
+    const int gate_rows = 3 * padded_adapters(N);
+    const GroupLayout L = group_layout(d_outs, G, T, d_in, N, r, k, gemm_group_splits(T, d_in, d_outs, G, gate_rows),
+                                       gate_rows);
     DecodeMember mem[kMaxDecodeGroup];
     for (int g = 0; g < G; ++g) {
         const meteora_group_member& m = members[g];
@@ -587,7 +647,6 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
                               m.topk_idx_out ? m.topk_idx_out : at<int32_t>(ws, L.idx[g]),
                               m.topk_w_out ? m.topk_w_out : at<float>(ws, L.w[g]), m.out};
     }
-    const int gate_rows = 3 * padded_adapters(N);
     const int tslot = timing_begin_call();
     {
         StageScope sc(ST_GEMM, st, tslot);

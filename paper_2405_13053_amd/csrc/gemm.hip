@@ -276,19 +276,22 @@ hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int 
     return dense_small_tiles(T) ? launch_dense<2, 2>(a, stream) : launch_dense<2, 5>(a, stream);
 }
 
-// Two matrices in one split-K launch of 128 x 128 tiles (few-tile batches): partial[s][T][rows] = x * W^T and
-// partial2[s][T][rows2] = x * W2^T over the K range of split s, the column tiles of both in one grid.
-hipError_t launch_gemm_dense_splitk_pair(const void* x, const void* W, int rows, float* partial, const void* W2,
-                                         int rows2, float* partial2, int S, int T, int d_in, hipStream_t stream) {
-    if (S < 1 || !gemm_dense_splitk_ok(T, d_in, rows) || !gemm_dense_splitk_ok(T, d_in, rows2)) return hipErrorInvalidValue;
+// Several matrices in one split-K launch of 128 x 128 tiles (few-tile batches): ops[i].partial[s][T][rows_i] =
+// x * W_i^T over the K range of split s, the column tiles of all of them in one grid.
+hipError_t launch_gemm_dense_splitk_multi(const void* x, const DenseOperand* ops, int n_ops, int S, int T, int d_in,
+                                          hipStream_t stream) {
+    if (S < 1 || n_ops < 1 || n_ops > GemmArgs::kMaxSegments) return hipErrorInvalidValue;
     GemmArgs a{};
     a.x = (const bf16_t*)x; a.T = T; a.d_in = d_in;
     a.splits = S; a.tiles_per_split = ceil_div(d_in / kGemmBK, S);
-    const int t1 = ceil_div(rows, 128);
-    a.seg[0] = {(const bf16_t*)W, partial, rows, 0};
-    a.seg[1] = {(const bf16_t*)W2, partial2, rows2, t1};
-    a.nseg = 2;
-    a.W = a.seg[0].W; a.d_out = rows; a.partial = partial;   // replaced per workgroup
+    int tile0 = 0;
+    for (int i = 0; i < n_ops; ++i) {
+        if (!gemm_dense_splitk_ok(T, d_in, ops[i].rows)) return hipErrorInvalidValue;
+        a.seg[i] = {(const bf16_t*)ops[i].W, ops[i].partial, ops[i].rows, tile0};
+        tile0 += ceil_div(ops[i].rows, 128);
+    }
+    a.nseg = n_ops;
+    a.W = a.seg[0].W; a.d_out = a.seg[0].rows; a.partial = a.seg[0].partial;   // replaced per workgroup
     constexpr int smem = gemm_w3_lds_bytes<2, 2>();
     static bool attr_set = false;
     if (!attr_set) {
@@ -298,7 +301,7 @@ hipError_t launch_gemm_dense_splitk_pair(const void* x, const void* W, int rows,
         attr_set = true;
     }
     a.tiles_m = ceil_div(T, 128);
-    a.tiles_n = t1 + ceil_div(rows2, 128);
+    a.tiles_n = tile0;
     gemm_mfma_w3_kernel<2, 2><<<dim3(a.tiles_m * a.tiles_n, S), 256, smem, stream>>>(a);
     return hipGetLastError();
 }

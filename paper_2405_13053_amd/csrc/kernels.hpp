@@ -68,9 +68,10 @@ int gemm_dense_splits(int T, int d_in, int rows);
 hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int d_in, int rows, float* partial,
                                     hipStream_t stream);
 
-// the same for two matrices in one launch of 128 x 128 tiles, both with S splits
-hipError_t launch_gemm_dense_splitk_pair(const void* x, const void* W, int rows, float* partial, const void* W2,
-                                         int rows2, float* partial2, int S, int T, int d_in, hipStream_t stream);
+// the same for several matrices in one launch of 128 x 128 tiles, all with S splits (at most 8 matrices)
+struct DenseOperand { const void* W; int rows; float* partial; };
+hipError_t launch_gemm_dense_splitk_multi(const void* x, const DenseOperand* ops, int n_ops, int S, int T, int d_in,
+                                          hipStream_t stream);
 
 // ---- bucketing (Sec. 3.3: per-adapter token sets as index lists) --------------------------
 constexpr int kBucketChunkTokens = 64;   // tokens (k pairs each) whose pairs one workgroup histograms and scatters
@@ -132,6 +133,10 @@ hipError_t launch_gemm_decode_main(const void* x, const DecodeMember* mem, int G
 hipError_t launch_route_shrink_small_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
                                            int r, int k, float inv_temperature, float scale, hipStream_t stream);
 hipError_t launch_gemm_decode_finish(const DecodeMember* mem, int G, int S, int T, int k, int r, hipStream_t stream);
+// The same three launches for batches of a few hundred tokens with few output tiles: launch_gemm_dense_splitk_multi over
+// every W_g and Wcat_g (gpartial_g then holds [S][T][prep_wcat_rows]), this selection for all members, the finish above.
+hipError_t launch_route_dense_select_group(const DecodeMember* mem, int G, int S, int T, int N, int r, int k,
+                                           float inv_temperature, float scale, hipStream_t stream);
 
 // ---- gate gradients (Sec. 3.2, Eq. 4): dW_gate[d_in,N], dbias[N] (optional) and d_logits[T,N] (optional) from
 // x, dy = dL/do, the packed Wcat and B; bf16 shapes of the dense routing path with d_out % 64 == 0.

@@ -27,11 +27,29 @@ constexpr int kSelNP = 32;   // gate columns per term in Wcat: the path takes N 
 
 // WIDE: twice as many K splits' loads in flight (batches of a few hundred tokens come with up to 8 splits; with 4 or
 // fewer the narrow form is about 1 us faster)
+// Members of one launch (blockIdx.y): layers that share x and the shapes T, N, r, k, S, CR, each with its own
+// partial products, bias and outputs.
+struct SelectMembers {
+    struct Member {
+        const float* part;   // [S][T][CR]
+        const float* bias;   // [N] or NULL
+        int32_t* topk_idx;   // [T,k]
+        float* topk_w;       // [T,k]
+        bf16_t* hdense;      // [T][ext_stride] or NULL
+        float* hs;           // [T,k,r] or NULL
+    } m[kMaxDecodeGroup];
+};
+
 template <bool WIDE>
-__global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(
-    const float* __restrict__ part, int S, int CR, const float* __restrict__ bias, int T, int N, int r, int k,
-    float inv_temperature, float scale, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-    bf16_t* __restrict__ hdense, int ext_stride, float* __restrict__ hs) {
+__global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(const SelectMembers sm, int S, int CR, int T,
+                                                                         int N, int r, int k, float inv_temperature,
+                                                                         float scale, int ext_stride) {
+    const float* __restrict__ part = sm.m[blockIdx.y].part;
+    const float* __restrict__ bias = sm.m[blockIdx.y].bias;
+    int32_t* __restrict__ topk_idx = sm.m[blockIdx.y].topk_idx;
+    float* __restrict__ topk_w = sm.m[blockIdx.y].topk_w;
+    bf16_t* __restrict__ hdense = sm.m[blockIdx.y].hdense;
+    float* __restrict__ hs = sm.m[blockIdx.y].hs;
     constexpr int NP = kSelNP;
     constexpr int TPP = 64 / NP;                     // tokens ranked per pass
     constexpr int G = kSelTokensPerWave / TPP;       // passes (groups) per wavefront
@@ -132,21 +150,37 @@ hipError_t launch_route_dense_products(const void* x, const void* wcat, int T, i
     return launch_gemm_dense_splitk(x, wcat, T, d_in, prep_wcat_rows(N, r), part, stream);
 }
 
+static hipError_t launch_select(const SelectMembers& sm, int G, int S, int T, int N, int r, int k,
+                                float inv_temperature, float scale, int ext_stride, hipStream_t stream) {
+    const int CR = prep_wcat_rows(N, r);
+    const dim3 grid(ceil_div(T, kSelTokens), G);
+    if (S > 4)
+        route_dense_select_kernel<true><<<grid, kSelThreads, 0, stream>>>(sm, S, CR, T, N, r, k, inv_temperature, scale,
+                                                                          ext_stride);
+    else
+        route_dense_select_kernel<false><<<grid, kSelThreads, 0, stream>>>(sm, S, CR, T, N, r, k, inv_temperature, scale,
+                                                                           ext_stride);
+    return hipGetLastError();
+}
+
 hipError_t launch_route_dense_select(const float* part, const float* bias, int T, int d_in, int N, int r, int k,
                                      float inv_temperature, float scale, int32_t* topk_idx, float* topk_w,
                                      void* hdense, int ext_stride, hipStream_t stream, float* hs, int splits) {
-    const int CR = prep_wcat_rows(N, r);
-    const int S = splits > 0 ? splits : gemm_dense_splits(T, d_in, CR);
-    const int blocks = ceil_div(T, kSelTokens);
-    if (S > 4)
-        route_dense_select_kernel<true><<<blocks, kSelThreads, 0, stream>>>(part, S, CR, bias, T, N, r, k, inv_temperature,
-                                                                            scale, topk_idx, topk_w, (bf16_t*)hdense,
-                                                                            ext_stride, hs);
-    else
-        route_dense_select_kernel<false><<<blocks, kSelThreads, 0, stream>>>(part, S, CR, bias, T, N, r, k, inv_temperature,
-                                                                             scale, topk_idx, topk_w, (bf16_t*)hdense,
-                                                                             ext_stride, hs);
-    return hipGetLastError();
+    const int S = splits > 0 ? splits : gemm_dense_splits(T, d_in, prep_wcat_rows(N, r));
+    SelectMembers sm{};
+    sm.m[0] = {part, bias, topk_idx, topk_w, (bf16_t*)hdense, hs};
+    return launch_select(sm, 1, S, T, N, r, k, inv_temperature, scale, ext_stride, stream);
+}
+
+// The members of a group in one launch: mem[g].gpartial holds x * Wcat_g^T in S splits, results go to mem[g].idx,
+// mem[g].w and mem[g].hs.
+hipError_t launch_route_dense_select_group(const DecodeMember* mem, int G, int S, int T, int N, int r, int k,
+                                           float inv_temperature, float scale, hipStream_t stream) {
+    if (G < 1 || G > kMaxDecodeGroup || S < 1) return hipErrorInvalidValue;
+    SelectMembers sm{};
+    for (int g = 0; g < G; ++g) sm.m[g] = {mem[g].gpartial, mem[g].bias, mem[g].idx, mem[g].w, nullptr, mem[g].hs};
+    // ext_stride only enumerates the 8-column pieces of a token's N*r shrink values here (no hdense is written)
+    return launch_select(sm, G, S, T, N, r, k, inv_temperature, scale, (int)align_up((size_t)N * r, 64), stream);
 }
 
 }  // namespace meteora

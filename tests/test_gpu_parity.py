@@ -393,9 +393,15 @@ def _group_case(T, d_in, d_outs, N, r, k, routing, seed):
     (64, 4096, (1032, 1032), 12, 16, 3, "zipf", True),           # gate/up-like, r = 16, bias
     (8, 512, (256, 264, 136, 72), 28, 8, 2, "uniform", True),    # four members
     (33, 1024, (520, 136), 28, 8, 2, "uniform", False),          # not packed: member by member
-    (300, 512, (256, 264), 28, 8, 2, "uniform", True),           # not decode-sized: member by member
+    (300, 512, (256, 264), 28, 8, 2, "uniform", True),           # a few hundred tokens: three launches with 128-row tiles
     (16, 512, (264,), 28, 8, 2, "zipf", True),                   # a group of one is the single-layer call
-], ids=["qkv", "gate-up-r16", "four", "unpacked", "T=300", "one"])
+    (128, 1024, (520, 136, 136), 28, 8, 2, "uniform", True),     # q/k/v-like at T = 128
+    (200, 1024, (776, 776), 12, 16, 3, "zipf", True),            # gate/up-like, r = 16, bias, ragged token tile
+    (130, 512, (256, 264, 136, 72), 28, 8, 2, "uniform", True),  # four members: eight matrices in one launch
+    (300, 512, (256, 264), 28, 8, 2, "uniform", False),          # a few hundred tokens, not packed: member by member
+    (2000, 512, (2048, 2048, 2048), 28, 8, 2, "uniform", True),  # too many output tiles for one launch: member by member
+], ids=["qkv", "gate-up-r16", "four", "unpacked", "T=300", "one", "qkv-T128", "gate-up-T200-r16", "four-T130",
+        "T=300-unpacked", "T=2000"])
 def test_group_call_matches_oracle_and_single_calls(T, d_in, d_outs, N, r, k, routing, packed):
     shapes, all_ops, members, x, rows = _group_case(T, d_in, d_outs, N, r, k, routing, seed=50)
     for mb in members:
