@@ -65,6 +65,17 @@ int meteora_version(void);
 const char* meteora_status_string(meteora_status s);
 
 /*
+ * Optional set-up of HIP device `device` (-1 = the current device): everything that a kernel's first
+ * launch on a device otherwise does by itself, which is one host-side function attribute per kernel
+ * that uses more than 64 KB of LDS.  Setting that attribute is not a stream operation and is not
+ * allowed while the stream is being captured into a HIP graph: a caller that captures its first call
+ * of an entry point runs meteora_init (or one eager call of the same entry point at the same kind of
+ * batch size) beforehand.  Cheap to repeat; thread-safe.  Returns METEORA_ERR_HIP without a usable
+ * device, METEORA_ERR_INVALID_ARG if `device` cannot be selected.  Leaves the current device unchanged.
+ */
+meteora_status meteora_init(int device);
+
+/*
  * Scratch bytes needed by meteora_gate_topk, meteora_bucket_tokens,
  * meteora_lora_forward and meteora_linear_forward for this problem size (the
  * maximum over the four; entry points that take no d_out or r accept the
@@ -72,6 +83,20 @@ const char* meteora_status_string(meteora_status s);
  * Host only, no HIP call.  Returns 0 for arguments outside the limits.
  */
 size_t meteora_workspace_bytes(int T, int d_in, int d_out, int N, int r, int k, meteora_dtype dt);
+
+/*
+ * Audit of the workspace carving of meteora_linear_forward (with_packed = 0) or
+ * meteora_linear_forward_packed with a blob (with_packed = 1), for tests.  Host only, no HIP call.
+ * Entry i of the host arrays (each may be NULL) receives region i's name (static string), its
+ * byte offset in ws, the bytes reserved for it, and the bytes that the launch sequence this
+ * shape selects writes there (from that sequence's own tile and K-split counts).  Returns the
+ * number of regions (at most max_regions entries are filled), or -1 for arguments outside the
+ * limits.  Every written extent must fit its reservation, and offset + reserved must stay inside
+ * meteora_workspace_bytes.
+ */
+int meteora_workspace_regions(int T, int d_in, int d_out, int N, int r, int k, meteora_dtype dt,
+                              int with_packed, const char** names /*host*/, size_t* offset /*host*/,
+                              size_t* reserved /*host*/, size_t* written /*host*/, int max_regions);
 
 /*
  * Gate network and top-k routing (Sec. 3.1: G(x), I(x); Eq. 3).
@@ -119,13 +144,18 @@ meteora_status meteora_lora_forward(const void* x, const void* A, const void* B,
 
 /*
  * Whole layer, Eq. 2: out = x*W + scale * sum_{i in I(x)} w_i * ((x*A_i)*B_i),
- * with I(x), w from the gate as in meteora_gate_topk (inv_temperature = 1).
+ * with I(x), w from the gate as in meteora_gate_topk.  inv_temperature as there:
+ * 1.0f is Eq. 3 as printed, 1/tau the softmax temperature that App. A.6 uses for the
+ * composite tasks (tau = 15, 20, 30); it changes the weights, never the selection.
+ * With k = 1 (the top-1 strategy of App. A.1) the weight is exactly 1: no exponential is
+ * evaluated, and the per-token work of the shrink and expand is that of one adapter.
  * If topk_idx_out / topk_w_out are not NULL they receive the routing used.
+ * Errors: a non-finite scale or inv_temperature is METEORA_ERR_INVALID_ARG.
  */
 meteora_status meteora_linear_forward(const void* x, const void* W, const float* W_gate,
                                       const float* gate_bias, const void* A, const void* B,
                                       int T, int d_in, int d_out, int N, int r, int k,
-                                      float scale, meteora_dtype dt,
+                                      float scale, float inv_temperature, meteora_dtype dt,
                                       void* out /*[T,d_out]*/,
                                       int32_t* topk_idx_out /*[T,k] or NULL*/,
                                       float* topk_w_out /*[T,k] or NULL*/,
@@ -162,7 +192,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
                                              const float* gate_bias, const void* A, const void* B,
                                              const void* packed, size_t packed_bytes,
                                              int T, int d_in, int d_out, int N, int r, int k,
-                                             float scale, meteora_dtype dt,
+                                             float scale, float inv_temperature, meteora_dtype dt,
                                              void* out /*[T,d_out]*/,
                                              int32_t* topk_idx_out /*[T,k] or NULL*/,
                                              float* topk_w_out /*[T,k] or NULL*/,
@@ -171,7 +201,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
 /*
  * Several MeteoRA layers on the same input: the layers of a decoder block that share x (q/k/v, and
  * gate/up; Sec. 4.1 embeds the adapters in all seven linear layers) each have their own base weight,
- * gate and adapters but the same T, d_in, N, r, k and scale.  The result is that of one
+ * gate and adapters but the same T, d_in, N, r, k, scale and inv_temperature.  The result is that of one
  * meteora_linear_forward_packed call per member (same routing; outputs equal to bf16 accuracy, the
  * split-K sums may run in another order).  For decode-sized batches (T <= 64) and for batches of a few
  * hundred tokens whose members have few output tiles in all (at most 320 tiles of 128 x 128, routing
@@ -201,7 +231,8 @@ size_t meteora_group_workspace_bytes(const int* d_out /*host, [G]*/, int G, int 
                                      meteora_dtype dt);
 
 meteora_status meteora_linear_forward_group(const void* x, const meteora_group_member* members /*host*/, int G,
-                                            int T, int d_in, int N, int r, int k, float scale, meteora_dtype dt,
+                                            int T, int d_in, int N, int r, int k, float scale,
+                                            float inv_temperature, meteora_dtype dt,
                                             void* ws, size_t ws_bytes, meteora_stream stream);
 
 /*

@@ -124,7 +124,7 @@ def lora_delta(x, A, B, idx, w, scale: float, rows=None, return_h: bool = False)
     T, d_in = x.shape
     N, d_in2, r = A.shape
     N2, r2, d_out = B.shape
-    assert d_in2 == d_in and N2 == N and r2 == r and r <= 256
+    assert d_in2 == d_in and N2 == N and r2 == r
     rows, n = _rows(rows, T)
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     w = np.ascontiguousarray(w, dtype=np.float64)
@@ -141,9 +141,10 @@ def lora_delta(x, A, B, idx, w, scale: float, rows=None, return_h: bool = False)
     return (delta, h) if return_h else delta
 
 
-def linear_forward(x, W, W_gate, bias, A, B, k: int, scale: float, rows=None):
+def linear_forward(x, W, W_gate, bias, A, B, k: int, scale: float, rows=None, temperature: float = 1.0):
     """Whole layer (Eq. 2) on the given rows.
 
+    temperature: the softmax temperature of App. A.6 (1.0 = Eq. 3 as printed).
     Returns dict(y[nrows,d_out] f64, logits[nrows,N] f32, idx[nrows,k] i32, w[nrows,k] f64).
     """
     x, W, W_gate, A, B = _f32(x), _f32(W), _f32(W_gate), _f32(A), _f32(B)
@@ -152,7 +153,7 @@ def linear_forward(x, W, W_gate, bias, A, B, k: int, scale: float, rows=None):
     d_out = W.shape[0]
     N, _, r = A.shape
     assert W.shape == (d_out, d_in) and W_gate.shape == (d_in, N)
-    assert A.shape == (N, d_in, r) and B.shape == (N, r, d_out) and r <= 256
+    assert A.shape == (N, d_in, r) and B.shape == (N, r, d_out)
     if not (1 <= k <= N):
         raise ValueError("need 1 <= k <= N")
     rows, n = _rows(rows, T)
@@ -165,6 +166,7 @@ def linear_forward(x, W, W_gate, bias, A, B, k: int, scale: float, rows=None):
     _load().oracle_linear_forward(_ptr(x), _ptr(W), _ptr(W_gate), _ptr(bias), _ptr(A), _ptr(B),
                                   ctypes.c_int(d_in), ctypes.c_int(d_out), ctypes.c_int(N),
                                   ctypes.c_int(r), ctypes.c_int(k), ctypes.c_double(scale),
+                                  ctypes.c_double(1.0 / temperature),
                                   _ptr(rows), ctypes.c_int(n), _ptr(y), _ptr(logits), _ptr(idx),
                                   _ptr(w), _ptr(s64), _ptr(delta))
     return {"y": y, "logits": logits, "idx": idx, "w": w}

@@ -32,7 +32,11 @@
  *
  * Parity pins: every function here is pinned by tests/test_oracle_pins.py
  * (hand-worked example, brute-force dense evaluation, invariants, fp64 matmul
- * special cases).  Nothing is "parity unpinned".
+ * special cases).  One reading is "parity unpinned": the softmax temperature
+ * of App. A.6, for which the paper prints values (15, 20, 30) but no formula.
+ * It is read as softmax(g / tau) over the k selected logits; the tests pin
+ * the arithmetic of that reading (closed forms), not the reading itself.
+ * inv_temperature = 1 is Eq. 3 as printed and is fully pinned.
  */
 #include <math.h>
 #include <stddef.h>
@@ -167,7 +171,7 @@ void oracle_lora_delta(const float* x, const float* A, const float* B,
             const int a = idx[i * k + s];
             const float* Aa = A + (int64_t)a * d_in * r;
             const float* Ba = B + (int64_t)a * r * d_out;
-            double hq[256];
+            double hq[r > 0 ? r : 1];   /* C99 variable-length array: any rank */
             for (int q = 0; q < r; ++q) {
                 double acc = 0.0;
                 for (int c = 0; c < d_in; ++c)
@@ -190,17 +194,18 @@ void oracle_lora_delta(const float* x, const float* A, const float* B,
  * Eq. 3 -> base + LoRA.  Outputs: y[nrows,d_out] double, and the routing
  * (logits32[nrows,N], idx[nrows,k], w[nrows,k]) it used.
  * scratch64 must hold nrows*N doubles; delta must hold nrows*d_out doubles.
- * r must be <= 256.
+ * inv_temperature as in oracle_topk_softmax (1.0 = Eq. 3).
  */
 void oracle_linear_forward(const float* x, const float* W, const float* W_gate,
                            const float* bias, const float* A, const float* B,
                            int d_in, int d_out, int N, int r, int k, double scale,
+                           double inv_temperature,
                            const int32_t* rows, int nrows, double* y,
                            float* logits32, int32_t* idx, double* w,
                            double* scratch64, double* delta) {
     oracle_gate_logits(x, W_gate, bias, d_in, N, rows, nrows, scratch64);
     for (int64_t p = 0; p < (int64_t)nrows * N; ++p) logits32[p] = (float)scratch64[p];
-    oracle_topk_softmax(logits32, nrows, N, k, 1.0, idx, w);
+    oracle_topk_softmax(logits32, nrows, N, k, inv_temperature, idx, w);
     oracle_base(x, W, d_in, d_out, rows, nrows, y);
     oracle_lora_delta(x, A, B, idx, w, d_in, d_out, r, k, scale, rows, nrows, delta, NULL);
     for (int64_t p = 0; p < (int64_t)nrows * d_out; ++p) y[p] += delta[p];

@@ -54,18 +54,22 @@ def load_library():
     lib.meteora_lora_forward.restype = i
     lib.meteora_lora_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp, i, vp, sz, vp]
     lib.meteora_linear_forward.restype = i
-    lib.meteora_linear_forward.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp, vp, vp, vp, sz, vp]
+    lib.meteora_linear_forward.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, f, i, vp, vp, vp, vp, sz, vp]
+    lib.meteora_init.restype = i
+    lib.meteora_init.argtypes = [i]
+    lib.meteora_workspace_regions.restype = i
+    lib.meteora_workspace_regions.argtypes = [i, i, i, i, i, i, i, i, vp, vp, vp, vp, i]
     lib.meteora_packed_bytes.restype = sz
     lib.meteora_packed_bytes.argtypes = [i, i, i, i, i]
     lib.meteora_pack_weights.restype = i
     lib.meteora_pack_weights.argtypes = [vp, vp, vp, i, i, i, i, i, vp, sz, vp]
     lib.meteora_linear_forward_packed.restype = i
-    lib.meteora_linear_forward_packed.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, i, vp, vp,
+    lib.meteora_linear_forward_packed.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, i, i, i, i, i, i, f, f, i, vp, vp,
                                                   vp, vp, sz, vp]
     lib.meteora_group_workspace_bytes.restype = sz
     lib.meteora_group_workspace_bytes.argtypes = [vp, i, i, i, i, i, i, i]
     lib.meteora_linear_forward_group.restype = i
-    lib.meteora_linear_forward_group.argtypes = [vp, vp, i, i, i, i, i, i, f, i, vp, sz, vp]
+    lib.meteora_linear_forward_group.argtypes = [vp, vp, i, i, i, i, i, i, f, f, i, vp, sz, vp]
     lib.meteora_gate_backward_workspace_bytes.restype = sz
     lib.meteora_gate_backward_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
     lib.meteora_gate_backward.restype = i
@@ -114,6 +118,28 @@ def _stream():
 def workspace_bytes(T, d_in, d_out, N, r, k, dtype) -> int:
     dt = BF16 if dtype in (torch.bfloat16, BF16, "bf16") else F32
     return int(load_library().meteora_workspace_bytes(T, d_in, d_out, N, r, k, dt))
+
+
+def init(device: int = -1) -> None:
+    """meteora_init: per-device set-up ahead of the first launch (needed before a first call is graph-captured)."""
+    st = load_library().meteora_init(int(device))
+    if st != 0:
+        raise MeteoraError(st, "meteora_init")
+
+
+def workspace_regions(T, d_in, d_out, N, r, k, dtype, with_packed: bool = False):
+    """meteora_workspace_regions: list of (name, offset, reserved, written) or None for unsupported arguments."""
+    dt = BF16 if dtype in (torch.bfloat16, BF16, "bf16") else F32
+    cap = 64
+    names = (ctypes.c_char_p * cap)()
+    off = (ctypes.c_size_t * cap)()
+    res = (ctypes.c_size_t * cap)()
+    wr = (ctypes.c_size_t * cap)()
+    n = load_library().meteora_workspace_regions(T, d_in, d_out, N, r, k, dt, int(bool(with_packed)), names, off,
+                                                 res, wr, cap)
+    if n < 0:
+        return None
+    return [(names[j].decode(), int(off[j]), int(res[j]), int(wr[j])) for j in range(n)]
 
 
 def _ws(ws: Optional[torch.Tensor], need: int, device) -> torch.Tensor:
@@ -202,7 +228,7 @@ def pack_weights(W_gate, A, B, out: Optional[torch.Tensor] = None) -> torch.Tens
 
 def linear_forward(x, W, W_gate, gate_bias, A, B, k: int, scale: float, out: Optional[torch.Tensor] = None,
                    ws: Optional[torch.Tensor] = None, return_routing: bool = False,
-                   packed: Optional[torch.Tensor] = None):
+                   packed: Optional[torch.Tensor] = None, inv_temperature: float = 1.0):
     """meteora_linear_forward / meteora_linear_forward_packed (if `packed` is given): the whole layer (Eq. 2)."""
     T, d_in = x.shape
     d_out = W.shape[0]
@@ -222,12 +248,13 @@ def linear_forward(x, W, W_gate, gate_bias, A, B, k: int, scale: float, out: Opt
     lib = load_library()
     if packed is None:
         st = lib.meteora_linear_forward(_p(x), _p(W), _p(W_gate), _p(gate_bias), _p(A), _p(B), T, d_in, d_out, N, r,
-                                        k, float(scale), _dt(x), _p(out), _p(idx), _p(w), _p(ws), ws.numel(),
-                                        _stream())
+                                        k, float(scale), float(inv_temperature), _dt(x), _p(out), _p(idx), _p(w),
+                                        _p(ws), ws.numel(), _stream())
     else:
         st = lib.meteora_linear_forward_packed(_p(x), _p(W), _p(W_gate), _p(gate_bias), _p(A), _p(B), _p(packed),
-                                               packed.numel(), T, d_in, d_out, N, r, k, float(scale), _dt(x),
-                                               _p(out), _p(idx), _p(w), _p(ws), ws.numel(), _stream())
+                                               packed.numel(), T, d_in, d_out, N, r, k, float(scale),
+                                               float(inv_temperature), _dt(x), _p(out), _p(idx), _p(w), _p(ws),
+                                               ws.numel(), _stream())
     if st != 0:
         raise MeteoraError(st, "meteora_linear_forward")
     return (out, idx, w) if return_routing else out
@@ -249,7 +276,7 @@ def group_workspace_bytes(d_outs: Sequence[int], T: int, d_in: int, N: int, r: i
 
 
 def linear_forward_group(x, members, k: int, scale: float, ws: Optional[torch.Tensor] = None,
-                         return_routing: bool = False):
+                         return_routing: bool = False, inv_temperature: float = 1.0):
     """meteora_linear_forward_group: layers that share x.  `members` is a sequence of dicts with W, W_gate,
     gate_bias (or None), A, B, packed (or None) and optionally out; returns the list of outputs
     (or of (out, idx, w) with return_routing)."""
@@ -278,8 +305,8 @@ def linear_forward_group(x, members, k: int, scale: float, ws: Optional[torch.Te
         keep.append((out, idx, w))
         res.append((out, idx, w) if return_routing else out)
     ws = _ws(ws, group_workspace_bytes([mb["W"].shape[0] for mb in members], T, d_in, N, r, k, x.dtype), x.device)
-    st = load_library().meteora_linear_forward_group(_p(x), arr, len(members), T, d_in, N, r, k, float(scale), _dt(x),
-                                                     _p(ws), ws.numel(), _stream())
+    st = load_library().meteora_linear_forward_group(_p(x), arr, len(members), T, d_in, N, r, k, float(scale),
+                                                     float(inv_temperature), _dt(x), _p(ws), ws.numel(), _stream())
     if st != 0:
         raise MeteoraError(st, "meteora_linear_forward_group")
     return res

@@ -2,6 +2,7 @@
 // carving and the launch sequence of each entry point.  No device memory is allocated here
 // and nothing synchronises with the host.
 #include <math.h>
+#include <string.h>
 
 #include "../../include/meteora.h"
 #include "common.hpp"
@@ -72,9 +73,13 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     const bool dense = route_dense_applies(T, d_in, N, r, bf16);
     const bool decode3 = decode_fused_applies(T, d_in, d_out, N, r, bf16);
     L.wcat = take(dense || decode3 ? prep_wcat_bytes(d_in, N, r, bf16) : 0);
-    L.dpart = take(route_dense_part_bytes(T, d_in, N, r, bf16));
+    // the routing products come in the K splits of the launch that writes them: the products launch's own count, or
+    // that of the split base projection when both share one launch (which may be the larger of the two)
+    const int S_mid = dense_midsplit_splits(T, d_in, d_out, N, r, bf16);
+    L.dpart = take(S_mid > 0 ? (size_t)S_mid * T * prep_wcat_rows(N, r) * sizeof(float)
+                             : route_dense_part_bytes(T, d_in, N, r, bf16));
     L.gpart = take(decode3 ? (size_t)gemm_splitk_splits(T, d_in, d_out, bf16) * T * 3 * NP * sizeof(float) : 0);
-    L.spart = take((size_t)dense_midsplit_splits(T, d_in, d_out, N, r, bf16) * T * d_out * sizeof(float));
+    L.spart = take((size_t)S_mid * T * d_out * sizeof(float));
     L.total = off;
     return L;
 }
@@ -185,7 +190,17 @@ meteora_status meteora_stage_timing_read(float* ms_sum, int* launches, int* call
     return METEORA_OK;
 }
 
-int meteora_version(void) { return 100; }
+int meteora_version(void) { return 200; }
+
+meteora_status meteora_init(int device) {
+    int cur = 0;
+    if (hipGetDevice(&cur) != hipSuccess) return METEORA_ERR_HIP;
+    const bool other = device >= 0 && device != cur;
+    if (other && hipSetDevice(device) != hipSuccess) return METEORA_ERR_INVALID_ARG;
+    const hipError_t e = init_kernels();
+    if (other) (void)hipSetDevice(cur);
+    return e == hipSuccess ? METEORA_OK : METEORA_ERR_HIP;
+}
 
 const char* meteora_status_string(meteora_status s) {
     switch (s) {
@@ -202,6 +217,83 @@ size_t meteora_workspace_bytes(int T, int d_in, int d_out, int N, int r, int k, 
     if (!shape_ok(T, d_in, d_out, N, r, k) || !shape_supported(T, d_in, d_out, N, r, k)) return 0;
     if (dt != METEORA_F32 && dt != METEORA_BF16) return 0;
     return ws_layout(T, d_in, d_out, N, r, k, dt == METEORA_BF16).total + 256;
+}
+
+// Host-only audit of the workspace carving of meteora_linear_forward(_packed): for every region, where it starts,
+// how many bytes the layout reserves and how many bytes the launch sequence that this shape selects writes there.
+// The written extents are derived from the launch decisions (which path, how many K splits), not from the layout's
+// own size formulas, so that a region sized for another split count than the one that writes it shows up.
+int meteora_workspace_regions(int T, int d_in, int d_out, int N, int r, int k, meteora_dtype dt, int with_packed,
+                              const char** names, size_t* offset, size_t* reserved, size_t* written, int max_regions) {
+    if (!shape_ok(T, d_in, d_out, N, r, k) || !shape_supported(T, d_in, d_out, N, r, k)) return -1;
+    if (dt != METEORA_F32 && dt != METEORA_BF16) return -1;
+    const bool bf16 = dt == METEORA_BF16;
+    const WsLayout L = ws_layout(T, d_in, d_out, N, r, k, bf16);
+    struct Region { const char* name; size_t off, written; };
+    Region R[19] = {{"wsplit", L.wsplit, 0}, {"partials", L.partials, 0}, {"chunk_counts", L.chunk_counts, 0},
+                    {"counts", L.counts, 0}, {"offsets", L.offsets, 0}, {"bucket_tok", L.bucket_tok, 0},
+                    {"bucket_slot", L.bucket_slot, 0}, {"topk_idx", L.topk_idx, 0}, {"topk_w", L.topk_w, 0},
+                    {"h32", L.h32, 0}, {"hdense", L.hdense, 0}, {"apack", L.apack, 0}, {"hpart", L.hpart, 0},
+                    {"splitk", L.splitk, 0}, {"btrans", L.btrans, 0}, {"wcat", L.wcat, 0}, {"dpart", L.dpart, 0},
+                    {"gpart", L.gpart, 0}, {"spart", L.spart, 0}};
+    auto wr = [&](const char* name, size_t bytes) {
+        for (Region& g : R)
+            if (strcmp(g.name, name) == 0 && bytes > g.written) g.written = bytes;
+    };
+    const int NP = padded_adapters(N);
+    const size_t pairs = (size_t)T * k;
+    const int CR = prep_wcat_rows(N, r);
+    const bool dense = route_dense_applies(T, d_in, N, r, bf16);
+    const bool decode3 = decode_fused_applies(T, d_in, d_out, N, r, bf16);
+    wr("topk_idx", pairs * sizeof(int32_t));
+    wr("topk_w", pairs * sizeof(float));
+    if (!with_packed) {
+        if (!dense && !decode3) { wr("wsplit", gate_wsplit_bytes(d_in, N, bf16)); wr("apack", shrink_apack_bytes(d_in, N, r, bf16)); }
+        if (!decode3) wr("btrans", prep_btrans_bytes(d_out, N, r, bf16));
+        if (dense || decode3) wr("wcat", prep_wcat_bytes(d_in, N, r, bf16));
+    }
+    if (decode3) {
+        const int S = gemm_group_splits(T, d_in, &d_out, 1, 3 * NP);
+        wr("splitk", (size_t)S * T * d_out * sizeof(float));
+        wr("gpart", (size_t)S * T * 3 * NP * sizeof(float));
+        wr("h32", pairs * r * sizeof(float));
+    } else if (dense) {
+        if (const int S = dense_midsplit_splits(T, d_in, d_out, N, r, bf16)) {
+            wr("spart", (size_t)S * T * d_out * sizeof(float));
+            wr("dpart", (size_t)S * T * CR * sizeof(float));
+            wr("h32", pairs * r * sizeof(float));
+        } else {
+            wr("dpart", (size_t)gemm_dense_splits(T, d_in, CR) * T * CR * sizeof(float));
+            wr("hdense", (size_t)T * L.ext_stride * sizeof(uint16_t));
+        }
+    } else {
+        wr("partials", (size_t)gate_kslices(d_in, bf16) * T * NP * sizeof(float));
+        const bool fused = gemm_fuses_expand(bf16);
+        if (fused) wr("hdense", (size_t)T * L.ext_stride * sizeof(uint16_t));
+        if (route_small_applies(T, r, bf16)) {
+            const int S = gemm_splitk_splits(T, d_in, d_out, bf16);
+            if (S > 0) wr("splitk", (size_t)(S + 1) * T * d_out * sizeof(float));
+        } else {
+            wr("chunk_counts", (size_t)bucket_chunks(T) * N * sizeof(int32_t));
+            wr("counts", (size_t)N * sizeof(int32_t));
+            wr("offsets", (size_t)(N + 1) * sizeof(int32_t));
+            wr("bucket_tok", pairs * sizeof(int32_t));
+            wr("bucket_slot", pairs * sizeof(int32_t));
+            wr("hpart", shrink_hpart_bytes(T, d_in, r, k, bf16));
+            if (!fused) wr("h32", pairs * r * sizeof(float));
+            const int S = gemm_splitk_splits(T, d_in, d_out, bf16);
+            if (fused && S > 0) wr("splitk", (size_t)(S + 1) * T * d_out * sizeof(float));
+        }
+    }
+    const int n = (int)(sizeof(R) / sizeof(R[0]));
+    for (int i = 0; i < n && i < max_regions; ++i) {
+        const size_t end = i + 1 < n ? R[i + 1].off : L.total;
+        if (names) names[i] = R[i].name;
+        if (offset) offset[i] = R[i].off;
+        if (reserved) reserved[i] = end - R[i].off;
+        if (written) written[i] = R[i].written;
+    }
+    return n;
 }
 
 meteora_status meteora_gate_topk(const void* x, const float* W_gate, const float* gate_bias, int T, int d_in,
@@ -370,10 +462,10 @@ meteora_status meteora_pack_weights(const float* W_gate, const void* A, const vo
 meteora_status meteora_linear_forward_packed(const void* x, const void* W, const float* W_gate,
                                              const float* gate_bias, const void* A, const void* B,
                                              const void* packed, size_t packed_bytes, int T, int d_in, int d_out,
-                                             int N, int r, int k, float scale, meteora_dtype dt, void* out,
-                                             int32_t* topk_idx_out, float* topk_w_out, void* ws, size_t ws_bytes,
-                                             meteora_stream stream) {
-    if (!W || !W_gate) return METEORA_ERR_INVALID_ARG;
+                                             int N, int r, int k, float scale, float inv_temperature,
+                                             meteora_dtype dt, void* out, int32_t* topk_idx_out, float* topk_w_out,
+                                             void* ws, size_t ws_bytes, meteora_stream stream) {
+    if (!W || !W_gate || !isfinite(inv_temperature)) return METEORA_ERR_INVALID_ARG;
     meteora_status s = check_lora_args(x, A, B, T, d_in, d_out, N, r, k, scale, dt, out);
     if (s != METEORA_OK) return s;
     if (!aligned16(W) || !aligned16(W_gate) || (gate_bias && !aligned4(gate_bias)) ||
@@ -421,7 +513,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
         }
         {
             StageScope sc(ST_SHRINK, st, tslot);
-            METEORA_HIP(launch_route_shrink_small_group(x, &mem, 1, S, T, d_in, N, r, k, 1.0f, scale, st));
+            METEORA_HIP(launch_route_shrink_small_group(x, &mem, 1, S, T, d_in, N, r, k, inv_temperature, scale, st));
         }
         StageScope sc(ST_EXPAND, st, tslot);
         METEORA_HIP(launch_gemm_decode_finish(&mem, 1, S, T, k, r, st));
@@ -441,7 +533,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
             }
             {
                 StageScope sc(ST_GATE_TOPK, st, tslot);
-                METEORA_HIP(launch_route_dense_select(dpart, gate_bias, T, d_in, N, r, k, 1.0f, scale, idx, w, nullptr,
+                METEORA_HIP(launch_route_dense_select(dpart, gate_bias, T, d_in, N, r, k, inv_temperature, scale, idx, w, nullptr,
                                                       L.ext_stride, st, hs, S));
             }
             StageScope sc(ST_EXPAND, st, tslot);
@@ -454,7 +546,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
         }
         {
             StageScope sc(ST_GATE_TOPK, st, tslot);
-            METEORA_HIP(launch_route_dense_select(dpart, gate_bias, T, d_in, N, r, k, 1.0f, scale, idx, w,
+            METEORA_HIP(launch_route_dense_select(dpart, gate_bias, T, d_in, N, r, k, inv_temperature, scale, idx, w,
                                                   at<void>(ws, L.hdense), L.ext_stride, st));
         }
         StageScope sc(ST_GEMM, st, tslot);
@@ -471,7 +563,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
         {
             StageScope sc(ST_SHRINK, st, tslot);
             METEORA_HIP(launch_route_shrink_small(x, partials, gate_kslices(d_in, bf16), gate_bias, A, T, d_in, N, r,
-                                                  k, 1.0f, scale, idx, w, at<void>(ws, L.hdense), L.ext_stride, st));
+                                                  k, inv_temperature, scale, idx, w, at<void>(ws, L.hdense), L.ext_stride, st));
         }
         StageScope sc(ST_GEMM, st, tslot);
         METEORA_HIP(launch_gemm(x, W, T, d_in, d_out, bf16, at<void>(ws, L.hdense), L.ext_stride, pk.btrans, N * r,
@@ -481,7 +573,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
     }
     {
         StageScope sc(ST_GATE_TOPK, st, tslot);
-        METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, 1.0f, idx, w,
+        METEORA_HIP(launch_gate_topk(partials, gate_kslices(d_in, bf16), gate_bias, T, N, k, inv_temperature, idx, w,
                                      nullptr, at<int32_t>(ws, L.chunk_counts), st));
     }
     return run_lora(x, W, A, B, idx, w, T, d_in, d_out, N, r, k, scale, bf16, out, 0, ws, L, pk, st, tslot, true);
@@ -571,9 +663,10 @@ extern "C" size_t meteora_group_workspace_bytes(const int* d_out, int G, int T, 
 }
 
 extern "C" meteora_status meteora_linear_forward_group(const void* x, const meteora_group_member* members, int G, int T,
-                                                       int d_in, int N, int r, int k, float scale, meteora_dtype dt,
-                                                       void* ws, size_t ws_bytes, meteora_stream stream) {
-    if (!members || G < 1 || G > 64) return METEORA_ERR_INVALID_ARG;
+                                                       int d_in, int N, int r, int k, float scale,
+                                                       float inv_temperature, meteora_dtype dt, void* ws,
+                                                       size_t ws_bytes, meteora_stream stream) {
+    if (!members || G < 1 || G > 64 || !isfinite(inv_temperature)) return METEORA_ERR_INVALID_ARG;
     if (dt != METEORA_F32 && dt != METEORA_BF16) return METEORA_ERR_UNSUPPORTED;
     const bool bf16 = dt == METEORA_BF16;
     int d_outs[64];
@@ -618,7 +711,7 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
         }
         {
             StageScope sc(ST_GATE_TOPK, st, tslot);
-            METEORA_HIP(launch_route_dense_select_group(mem, G, S, T, N, r, k, 1.0f, scale, st));
+            METEORA_HIP(launch_route_dense_select_group(mem, G, S, T, N, r, k, inv_temperature, scale, st));
         }
         StageScope sc(ST_EXPAND, st, tslot);
         METEORA_HIP(launch_gemm_decode_finish(mem, G, S, T, k, r, st));
@@ -629,8 +722,8 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
         for (int g = 0; g < G; ++g) {
             const meteora_group_member& m = members[g];
             const meteora_status s = meteora_linear_forward_packed(
-                x, m.W, m.W_gate, m.gate_bias, m.A, m.B, m.packed, m.packed_bytes, T, d_in, m.d_out, N, r, k, scale, dt,
-                m.out, m.topk_idx_out, m.topk_w_out, ws, ws_bytes, stream);
+                x, m.W, m.W_gate, m.gate_bias, m.A, m.B, m.packed, m.packed_bytes, T, d_in, m.d_out, N, r, k, scale,
+                inv_temperature, dt, m.out, m.topk_idx_out, m.topk_w_out, ws, ws_bytes, stream);
             if (s != METEORA_OK) return s;
         }
         return METEORA_OK;
@@ -654,7 +747,7 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
     }
     {
         StageScope sc(ST_SHRINK, st, tslot);
-        METEORA_HIP(launch_route_shrink_small_group(x, mem, G, L.S, T, d_in, N, r, k, 1.0f, scale, st));
+        METEORA_HIP(launch_route_shrink_small_group(x, mem, G, L.S, T, d_in, N, r, k, inv_temperature, scale, st));
     }
     StageScope sc(ST_EXPAND, st, tslot);
     METEORA_HIP(launch_gemm_decode_finish(mem, G, L.S, T, k, r, st));
@@ -665,10 +758,11 @@ extern "C" {
 
 meteora_status meteora_linear_forward(const void* x, const void* W, const float* W_gate, const float* gate_bias,
                                       const void* A, const void* B, int T, int d_in, int d_out, int N, int r,
-                                      int k, float scale, meteora_dtype dt, void* out, int32_t* topk_idx_out,
-                                      float* topk_w_out, void* ws, size_t ws_bytes, meteora_stream stream) {
+                                      int k, float scale, float inv_temperature, meteora_dtype dt, void* out,
+                                      int32_t* topk_idx_out, float* topk_w_out, void* ws, size_t ws_bytes,
+                                      meteora_stream stream) {
     return meteora_linear_forward_packed(x, W, W_gate, gate_bias, A, B, nullptr, 0, T, d_in, d_out, N, r, k, scale,
-                                         dt, out, topk_idx_out, topk_w_out, ws, ws_bytes, stream);
+                                         inv_temperature, dt, out, topk_idx_out, topk_w_out, ws, ws_bytes, stream);
 }
 
 size_t meteora_gate_backward_workspace_bytes(int T, int d_in, int d_out, int N, int r, int k, meteora_dtype dt) {

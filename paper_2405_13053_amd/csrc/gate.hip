@@ -259,8 +259,7 @@ hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_i
     // (measured faster than 32 or 128 tokens on every configuration, 4096 to 16384 tokens)
     auto launch = [&](auto kern, int rb) -> hipError_t {
         const int smem = 4 * gate_region_bytes(NCB, rb);
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        hipError_t err = ensure_lds_limit(reinterpret_cast<const void*>(kern), smem);
         if (err != hipSuccess) return err;
         kern<<<ceil_div(T, rb * 32) * KS, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)wsplit, T, d_in, KS,
                                                               partials);
@@ -268,6 +267,12 @@ hipError_t launch_gate_logits(const void* x, const float* W_gate, int T, int d_i
     };
     if (NCB == 1) return launch(gate_logits_mfma_kernel<1, 2>, 2);
     return launch(gate_logits_mfma_kernel<2, 2>, 2);
+}
+
+hipError_t gate_init_kernels() {
+    hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&gate_logits_mfma_kernel<1, 2>), 4 * gate_region_bytes(1, 2));
+    if (e != hipSuccess) return e;
+    return ensure_lds_limit(reinterpret_cast<const void*>(&gate_logits_mfma_kernel<2, 2>), 4 * gate_region_bytes(2, 2));
 }
 
 hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, int T, int N, int k,

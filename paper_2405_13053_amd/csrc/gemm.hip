@@ -178,29 +178,13 @@ size_t gemm_splitk_bytes(int T, int d_in, int d_out, bool bf16) {
     return S == 0 ? 0 : (size_t)(S + 1) * T * d_out * sizeof(float);   // +1: the expand extension
 }
 
-// Kernels with more than 64 KB of dynamic LDS need the limit raised by a host-side attribute, which HIP keeps per
-// device: done once per (kernel, device).  The flags are plain bools: two threads racing here both set the same
-// attribute, which is harmless.
-constexpr int kMaxDevices = 64;
-static hipError_t ensure_lds_limit(const void* kernel, int bytes, bool (&done)[kMaxDevices]) {
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    if (done[dev]) return hipSuccess;
-    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess) done[dev] = true;
-    return e;
-}
-
 template <int MI, int NI>
 static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
     constexpr int BM = MI * 64, BN = NI * 64;
     constexpr int smem = gemm_lds_bytes<MI, NI>();
-    static bool done_plain[kMaxDevices], done_dma[kMaxDevices];
-    hipError_t e0 = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_kernel<MI, NI>), smem, done_plain);
+    hipError_t e0 = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_kernel<MI, NI>), smem);
     if (e0 != hipSuccess) return e0;
-    e0 = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_dma_kernel<MI, NI>), smem, done_dma);
+    e0 = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_dma_kernel<MI, NI>), smem);
     if (e0 != hipSuccess) return e0;
     a.tiles_m = ceil_div(a.T, BM);
     a.tiles_n = ceil_div(a.d_out, BN);
@@ -218,9 +202,8 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
                                                                                    a.out, a.accumulate);
     } else if (dma_ok && ((MI == 4 && NI == 4) || (MI == 2 && NI == 2))) {
         constexpr int M3 = MI == 4 ? 4 : 2;   // the instantiations of the three-deep-ring kernel that exist
-        static bool done_w3[kMaxDevices];
         const hipError_t e1 = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<M3, M3>),
-                                               gemm_w3_lds_bytes<M3, M3>(), done_w3);
+                                               gemm_w3_lds_bytes<M3, M3>());
         if (e1 != hipSuccess) return e1;
         gemm_mfma_w3_kernel<M3, M3><<<a.tiles_m * a.tiles_n, 256, gemm_w3_lds_bytes<M3, M3>(), stream>>>(a);
     } else if (dma_ok) {
@@ -259,8 +242,7 @@ template <int MI, int NI>
 static hipError_t launch_dense(GemmArgs a, hipStream_t stream) {   // three-deep W ring, fp32 split-K tiles
     constexpr int smem = gemm_w3_lds_bytes<MI, NI>();
     auto kern = &gemm_mfma_w3_kernel<MI, NI>;
-    static bool done[kMaxDevices];
-    const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(kern), smem, done);
+    const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(kern), smem);
     if (ea != hipSuccess) return ea;
     a.tiles_m = ceil_div(a.T, MI * 64);
     a.tiles_n = ceil_div(a.d_out, NI * 64);
@@ -296,8 +278,7 @@ hipError_t launch_gemm_dense_splitk_multi(const void* x, const DenseOperand* ops
     a.nseg = n_ops;
     a.W = a.seg[0].W; a.d_out = a.seg[0].rows; a.partial = a.seg[0].partial;   // replaced per workgroup
     constexpr int smem = gemm_w3_lds_bytes<2, 2>();
-    static bool done[kMaxDevices];
-    const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 2>), smem, done);
+    const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 2>), smem);
     if (ea != hipSuccess) return ea;
     a.tiles_m = ceil_div(T, 128);
     a.tiles_n = tile0;
@@ -340,8 +321,7 @@ hipError_t launch_gemm_decode_main(const void* x, const DecodeMember* mem, int G
     a.nseg = 2 * G;
     a.W = a.seg[0].W; a.d_out = a.seg[0].rows; a.partial = a.seg[0].partial;   // replaced per workgroup
     constexpr int smem = gemm_lds_bytes<1, 1>();
-    static bool done[kMaxDevices];
-    const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_dma_kernel<1, 1>), smem, done);
+    const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_dma_kernel<1, 1>), smem);
     if (ea != hipSuccess) return ea;
     a.tiles_m = ceil_div(T, 64);
     a.tiles_n = tile0;
@@ -365,6 +345,27 @@ hipError_t launch_gemm_decode_finish(const DecodeMember* mem, int G, int S, int 
 }
 
 bool gemm_fuses_expand(bool bf16) { return bf16; }
+
+template <int MI, int NI>
+static hipError_t init_tile_kernels() {
+    hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_kernel<MI, NI>), gemm_lds_bytes<MI, NI>());
+    if (e != hipSuccess) return e;
+    return ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_dma_kernel<MI, NI>), gemm_lds_bytes<MI, NI>());
+}
+
+// every kernel of this file that a launcher above may start with more than the default dynamic LDS
+hipError_t gemm_init_kernels() {
+    hipError_t e = init_tile_kernels<4, 4>();
+    if (e == hipSuccess) e = init_tile_kernels<2, 2>();
+    if (e == hipSuccess) e = init_tile_kernels<1, 1>();
+    if (e == hipSuccess)
+        e = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<4, 4>), gemm_w3_lds_bytes<4, 4>());
+    if (e == hipSuccess)
+        e = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 2>), gemm_w3_lds_bytes<2, 2>());
+    if (e == hipSuccess)
+        e = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 5>), gemm_w3_lds_bytes<2, 5>());
+    return e;
+}
 
 hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out, bool bf16,
                        const void* hdense, int ext_stride, const void* Bt, int ext_k,

@@ -8,6 +8,14 @@
 
 namespace meteora {
 
+// ---- process state (runtime.hip): raise a kernel's dynamic-LDS limit once per device (thread-safe), and the
+// set-up of every kernel of the library ahead of its first launch, for the current device (meteora_init)
+hipError_t ensure_lds_limit(const void* kernel, int bytes);
+hipError_t init_kernels();
+hipError_t gemm_init_kernels();
+hipError_t gate_init_kernels();
+hipError_t shrink_init_kernels();
+
 // ---- weight repacking, one launch: W_gate -> split bf16 fragments (bf16 gate), A -> MFMA fragments,
 // stacked B -> its transpose Bt[d_out, N*r rounded up to 64] (zero-padded) for the GEMM's K-extension.
 // Any pair (W_gate, wsplit) / (A, apack) / (B, btrans) may be NULL to skip it; sizes are gate_wsplit_bytes,

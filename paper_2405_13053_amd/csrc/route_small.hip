@@ -130,7 +130,9 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
 #pragma unroll
                 for (int c = 0; c < R8; ++c) {
                     v0[u][c] = reinterpret_cast<const u32x4*>(Aa0 + (size_t)ic * r)[c];
-                    v1[u][c] = reinterpret_cast<const u32x4*>(Aa1 + (size_t)ic * r)[c];
+                    // an odd last slot (the only one with the top-1 strategy of App. A.1) has no partner: its half
+                    // of the loads and of the arithmetic below is skipped
+                    v1[u][c] = two ? reinterpret_cast<const u32x4*>(Aa1 + (size_t)ic * r)[c] : u32x4{0u, 0u, 0u, 0u};
                 }
             }
 #pragma unroll
@@ -142,8 +144,10 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
                         const int q = c * 8 + 2 * e;
                         acc0[q] = fmaf(xv[u], bf16_bits_to_float(v0[u][c][e] & 0xffffu), acc0[q]);
                         acc0[q + 1] = fmaf(xv[u], bf16_bits_to_float(v0[u][c][e] >> 16), acc0[q + 1]);
-                        acc1[q] = fmaf(xv[u], bf16_bits_to_float(v1[u][c][e] & 0xffffu), acc1[q]);
-                        acc1[q + 1] = fmaf(xv[u], bf16_bits_to_float(v1[u][c][e] >> 16), acc1[q + 1]);
+                        if (two) {
+                            acc1[q] = fmaf(xv[u], bf16_bits_to_float(v1[u][c][e] & 0xffffu), acc1[q]);
+                            acc1[q + 1] = fmaf(xv[u], bf16_bits_to_float(v1[u][c][e] >> 16), acc1[q + 1]);
+                        }
                     }
         }
         // Wavefront sums of the 2r values a lane holds, in a fixed order.  A plain butterfly per value would cost

@@ -481,6 +481,17 @@ size_t shrink_hpart_bytes(int T, int d_in, int r, int k, bool bf16) {
     return (size_t)shrink_kslices(d_in) * T * k * r * sizeof(float);
 }
 
+hipError_t shrink_init_kernels() {
+    hipError_t e = ensure_lds_limit(reinterpret_cast<const void*>(&shrink_fullk_kernel<1, 1>), 4 * shrink_fullk_region_bytes(1, 1));
+    if (e == hipSuccess)
+        e = ensure_lds_limit(reinterpret_cast<const void*>(&shrink_fullk_kernel<2, 1>), 4 * shrink_fullk_region_bytes(2, 1));
+    if (e == hipSuccess)
+        e = ensure_lds_limit(reinterpret_cast<const void*>(&shrink_mfma_kernel<1, 2>), 4 * shrink_region_bytes(1, 2));
+    if (e == hipSuccess)
+        e = ensure_lds_limit(reinterpret_cast<const void*>(&shrink_mfma_kernel<2, 2>), 4 * shrink_region_bytes(2, 2));
+    return e;
+}
+
 hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, const float* topk_w,
                          const int32_t* offsets, const int32_t* bucket_tok, const int32_t* bucket_slot,
                          int T, int d_in, int N, int r, int k, float scale, bool bf16,
@@ -493,8 +504,7 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
         if (shrink_whole_k(bf16, r, pairs)) {
             auto launch_wk = [&](auto kern) -> hipError_t {
                 const int smem = 4 * shrink_fullk_region_bytes(RCB, 1);
-                hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+                hipError_t err = ensure_lds_limit(reinterpret_cast<const void*>(kern), smem);
                 if (err != hipSuccess) return err;
                 const int64_t max_tiles = ceil_div64(pairs, 32) + N;   // every bucket rounds up by at most one tile
                 kern<<<(unsigned)max_tiles, 256, smem, stream>>>((const bf16_t*)x, (const u32x4*)apack, offsets,
@@ -508,8 +518,7 @@ hipError_t launch_shrink(const void* x, const void* A, const int32_t* topk_idx, 
         // other computes); measured faster than 32- or 128-pair tiles on every configuration
         auto launch = [&](auto kern, int rb) -> hipError_t {
             const int smem = 4 * shrink_region_bytes(RCB, rb);
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            hipError_t err = ensure_lds_limit(reinterpret_cast<const void*>(kern), smem);
             if (err != hipSuccess) return err;
             // upper bound of the tile count: every bucket rounds up by at most one tile
             const int64_t max_tiles = ceil_div64(pairs, rb * 32) + N;

@@ -52,6 +52,13 @@ __device__ __forceinline__ void wave_topk_softmax(const float (&g)[G], int lane,
             if (col == s) { sel_g[i] = key_logit(best[i]); sel_i[i] = win; }
         }
     }
+    if (k == 1) {
+        // Top-1 strategy (App. A.1): the softmax over a single logit is exactly 1 whatever the logit and the
+        // temperature, so neither the exponential nor the normalising sum is evaluated
+#pragma unroll
+        for (int i = 0; i < G; ++i) sel_w[i] = col == 0 ? 1.f : 0.f;
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < G; ++i) {
         const float gmax = __shfl(sel_g[i], lane & ~(NP - 1));

@@ -47,6 +47,50 @@ def test_workspace_bytes(lib):
     assert lib.meteora_workspace_bytes(64, 256, 256, 4, 8, 2, 7) == 0        # unknown dtype
 
 
+def test_workspace_regions_hold_what_the_launches_write():
+    """Walk batch sizes and layer shapes across every launch sequence (decode, split-K mid batches, dense routing,
+    bucketed): each region of the workspace is at least as large as what the selected launches write into it
+    (tile and K-split counts taken from the launch decisions), regions do not overlap, and all of them lie inside
+    meteora_workspace_bytes."""
+    Ts = [1, 7, 33, 64, 65, 100, 128, 129, 200, 256, 300, 512, 513, 700, 1000, 1150, 1151, 1500, 2000, 2048, 3000,
+          4096, 4097, 5000, 8192, 8193, 16384, 70000]
+    dims = [(4096, 4096), (4096, 8), (4096, 256), (4096, 512), (4096, 1024), (4096, 14336), (14336, 4096),
+            (5120, 5120), (5120, 13824), (512, 264), (1088, 520), (64, 72), (256, 136)]
+    checked = 0
+    for dtype in ("bf16", "f32"):
+        for (N, r, k) in [(28, 8, 2), (28, 16, 2), (7, 32, 3), (64, 8, 8), (5, 5, 1)]:
+            for d_in, d_out in dims:
+                for T in Ts:
+                    for with_packed in (False, True):
+                        regs = m.workspace_regions(T, d_in, d_out, N, r, k, dtype, with_packed)
+                        assert regs is not None
+                        total = m.workspace_bytes(T, d_in, d_out, N, r, k, dtype)
+                        end_prev = 0
+                        for name, off, reserved, written in regs:
+                            where = f"{name} T={T} {d_in}->{d_out} N={N} r={r} k={k} {dtype} packed={with_packed}"
+                            assert off >= end_prev and off % 256 == 0, where
+                            assert written <= reserved, f"{where}: writes {written} B into {reserved} B"
+                            assert off + reserved <= total, where
+                            end_prev = off + reserved
+                        checked += 1
+    assert checked > 5000
+    # the shapes of the round-1 finding: the split projection has more K splits than the routing products alone
+    for T, d_in, d_out in ((3000, 4096, 256), (4096, 4096, 8)):
+        regs = {n: (o, rsv, w) for n, o, rsv, w in m.workspace_regions(T, d_in, d_out, 28, 8, 2, "bf16", True)}
+        assert regs["dpart"][2] <= regs["dpart"][1]
+
+
+def test_init_without_a_device_reports_an_error(lib):
+    """meteora_init is host code around HIP calls: on a machine with no GPU it returns an error code, it does not
+    abort; with a GPU it succeeds and may be repeated."""
+    import torch
+    st = lib.meteora_init(-1)
+    if torch.cuda.is_available():
+        assert st == OK and lib.meteora_init(0) == OK
+    else:
+        assert st == HIP
+
+
 # Fake, suitably aligned, never-dereferenced addresses: validation must reject before any launch.
 P = ctypes.c_void_p(0x10000)
 ODD = ctypes.c_void_p(0x10004)
@@ -93,8 +137,8 @@ def test_lora_and_linear_validation(lib):
         return lib.meteora_lora_forward(x, A, B, idx, w, T, di, do, N, r, k, s, dt, out, acc, ws, wsb, None)
 
     def lin(x=P, W=P, Wg=P, bias=None, A=P, B=P, T=64, di=256, do=256, N=4, r=8, k=2, s=2.0, dt=BF16, out=P,
-            io=None, wo=None, ws=WS, wsb=BIG):
-        return lib.meteora_linear_forward(x, W, Wg, bias, A, B, T, di, do, N, r, k, s, dt, out, io, wo, ws, wsb,
+            io=None, wo=None, ws=WS, wsb=BIG, it=1.0):
+        return lib.meteora_linear_forward(x, W, Wg, bias, A, B, T, di, do, N, r, k, s, it, dt, out, io, wo, ws, wsb,
                                           None)
 
     for f in (lora, lin):
@@ -115,6 +159,7 @@ def test_lora_and_linear_validation(lib):
     assert lora(acc=2) == INVALID
     assert lin(W=None) == INVALID
     assert lin(Wg=None) == INVALID
+    assert lin(it=float("nan")) == INVALID and lin(it=float("inf")) == INVALID
     need = m.workspace_bytes(64, 256, 256, 4, 8, 2, "bf16")
     assert lin(wsb=need - 512) == WORKSPACE
 
@@ -141,7 +186,7 @@ def test_pack_weights_validation(lib):
     assert pack(dt=F32, pk=None, pkb=0) == OK                           # nothing to pack
 
     def linp(pk=WS, pkb=BIG, T=64, ws=WS, wsb=BIG, W=P):
-        return lib.meteora_linear_forward_packed(P, W, P, None, P, P, pk, pkb, T, 256, 256, 4, 8, 2, 2.0, BF16, P,
+        return lib.meteora_linear_forward_packed(P, W, P, None, P, P, pk, pkb, T, 256, 256, 4, 8, 2, 2.0, 1.0, BF16, P,
                                                  None, None, ws, wsb, None)
 
     assert linp(pkb=64) == WORKSPACE
@@ -165,14 +210,15 @@ def test_group_validation(lib):
     def member(W=P.value, Wg=P.value, A=P.value, B=P.value, pk=None, pkb=0, d_out=256, out=P.value):
         return GroupMember(W, Wg, None, A, B, pk, pkb, d_out, out, None, None)
 
-    def call(ms, T=64, ws=WS, wsb=BIG, G=None, x=P):
+    def call(ms, T=64, ws=WS, wsb=BIG, G=None, x=P, it=1.0):
         arr = (GroupMember * len(ms))(*ms)
-        return lib.meteora_linear_forward_group(x, arr, len(ms) if G is None else G, T, 256, 4, 8, 2, 2.0, BF16, ws,
-                                                wsb, None)
+        return lib.meteora_linear_forward_group(x, arr, len(ms) if G is None else G, T, 256, 4, 8, 2, 2.0, it, BF16,
+                                                ws, wsb, None)
 
     two = [member(), member(d_out=264)]
     assert call(two, T=0) == OK
     assert call(two, G=0) == INVALID
+    assert call(two, it=float("nan")) == INVALID
     assert call(two, x=None) == INVALID
     assert call([member(), member(W=None)]) == INVALID
     assert call([member(), member(out=None)]) == INVALID
@@ -181,7 +227,7 @@ def test_group_validation(lib):
     assert call([member(), member(pk=WS.value, pkb=64)]) == WORKSPACE
     assert call(two, wsb=1024) == WORKSPACE
     assert call(two, ws=None) == WORKSPACE
-    assert lib.meteora_linear_forward_group(P, None, 2, 64, 256, 4, 8, 2, 2.0, BF16, WS, BIG, None) == INVALID
+    assert lib.meteora_linear_forward_group(P, None, 2, 64, 256, 4, 8, 2, 2.0, 1.0, BF16, WS, BIG, None) == INVALID
 
 
 def test_gate_backward_validation(lib):

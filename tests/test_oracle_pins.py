@@ -20,6 +20,7 @@ import oracle
 from gen import inputs as gen
 
 HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
 
 
 def _rand_layer(seed, T=7, d_in=12, d_out=20, N=5, r=3, dtype="f32", routing="uniform", k=2):
@@ -178,6 +179,29 @@ def test_temperature_reading():
     idx, w = oracle.topk_softmax(g, 2, temperature=2.0)
     assert idx.tolist() == [[1, 2]]
     np.testing.assert_allclose(w, [[1 / (1 + np.exp(-1.0)), 1 - 1 / (1 + np.exp(-1.0))]], atol=1e-15)
+
+
+def test_temperature_in_the_whole_layer():
+    """The layer with a temperature: same selection, weights sigma((g0 - g1) / tau) for k = 2 (closed form of a
+    two-way softmax), y = base + s * sum w_j * (x A_j) B_j with those weights; tau -> infinity gives the plain mean
+    of the k selected adapters; tau = 1 is the untempered layer bit for bit."""
+    shape, o = _rand_layer(21, T=9, N=6)
+    args = (o["x"], o["W"], o["W_gate"], None, o["A"], o["B"], 2, 2.0)
+    ref = oracle.linear_forward(*args)
+    one = oracle.linear_forward(*args, temperature=1.0)
+    assert np.array_equal(one["y"], ref["y"]) and np.array_equal(one["w"], ref["w"])
+    for tau in (15.0, 20.0, 30.0):
+        out = oracle.linear_forward(*args, temperature=tau)
+        assert np.array_equal(out["idx"], ref["idx"])
+        g = ref["logits"].astype(np.float64)
+        gap = np.take_along_axis(g, ref["idx"][:, :1].astype(np.int64), 1) - \
+            np.take_along_axis(g, ref["idx"][:, 1:2].astype(np.int64), 1)
+        w0 = 1.0 / (1.0 + np.exp(-gap / tau))
+        np.testing.assert_allclose(out["w"], np.concatenate([w0, 1 - w0], axis=1), rtol=0, atol=1e-15)
+        delta = oracle.lora_delta(o["x"], o["A"], o["B"], ref["idx"], out["w"], 2.0)
+        np.testing.assert_allclose(out["y"], oracle.base(o["x"], o["W"]) + delta, rtol=0, atol=1e-12)
+    far = oracle.linear_forward(*args, temperature=1e12)
+    np.testing.assert_allclose(far["w"], 0.5, rtol=0, atol=1e-11)
 
 
 def test_permutation_invariances():
@@ -398,3 +422,57 @@ def test_gate_backward_dx_matches_finite_differences_of_the_forward(k):
     # without adapters' weight and gate (scale 0, beta 0) dx is the base projection's: dy W
     plain = gb.gate_backward(ops["x"], dy, ops["W_gate"], bias, ops["A"], ops["B"], k, 0.0, None, 0.0, W=ops["W"])
     np.testing.assert_allclose(plain["dx"], dy @ ops["W"].astype(np.float64), rtol=1e-12, atol=1e-12)
+
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """Host sanitizer build of the checker: the C oracle compiled with -fsanitize=address,undefined runs the
+    hand-worked example, a ragged row subset and a layer of rank 300 (beyond any fixed buffer) in a child process
+    without a report.  The sanitizer runtime has to be loaded first, hence the child process and LD_PRELOAD."""
+    import subprocess
+    import sys
+    import textwrap
+    src = os.path.join(ROOT, "oracle", "meteora_oracle.c")
+    lib = str(tmp_path / "liboracle_asan.so")
+    subprocess.check_call(["gcc", "-O1", "-g", "-std=c99", "-fPIC", "-shared", "-fno-omit-frame-pointer",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-ffp-contract=off",
+                           "-o", lib, src, "-lm"])
+    asan = subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
+    ubsan = subprocess.check_output(["gcc", "-print-file-name=libubsan.so"], text=True).strip()
+    code = textwrap.dedent(f"""
+        import ctypes, json, numpy as np
+        L = ctypes.CDLL({lib!r})
+        ex = json.load(open({os.path.join(ROOT, "tests", "golden", "hand_example.json")!r}))
+        f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+        p = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+        def layer(x, W, Wg, A, B, k, scale, rows=None):
+            T, d_in = x.shape; d_out = W.shape[0]; N, _, r = A.shape
+            n = T if rows is None else rows.size
+            y = np.empty((n, d_out)); lg = np.empty((n, N), dtype=np.float32)
+            idx = np.empty((n, k), dtype=np.int32); w = np.empty((n, k))
+            s64 = np.empty((n, N)); dl = np.empty((n, d_out))
+            L.oracle_linear_forward(p(x), p(W), p(Wg), None, p(A), p(B), ctypes.c_int(d_in), ctypes.c_int(d_out),
+                                    ctypes.c_int(N), ctypes.c_int(r), ctypes.c_int(k), ctypes.c_double(scale),
+                                    ctypes.c_double(1.0), None if rows is None else p(rows), ctypes.c_int(n), p(y),
+                                    p(lg), p(idx), p(w), p(s64), p(dl))
+            return y, idx
+        y, idx = layer(f(ex["x"]), f(ex["W"]), f(ex["W_gate"]), f(ex["A"]), f(ex["B"]), ex["k"], ex["scale"])
+        assert np.allclose(y, ex["expect"]["y"], atol=1e-12) and idx.tolist() == ex["expect"]["idx"]
+        g = np.random.default_rng(0)
+        T, d_in, d_out, N, r = 11, 9, 13, 4, 300
+        x, W, Wg = f(g.standard_normal((T, d_in))), f(g.standard_normal((d_out, d_in))), f(g.standard_normal((d_in, N)))
+        A, B = f(g.standard_normal((N, d_in, r))), f(g.standard_normal((N, r, d_out)))
+        rows = np.array([10, 0, 3], dtype=np.int32)
+        y, idx = layer(x, W, Wg, A, B, 3, 0.5, rows)
+        tok = np.array([[0, 1, 0], [2, 2, 1]], dtype=np.int32)      # bucketing with an empty bucket
+        c = np.empty(4, dtype=np.int32); o = np.empty(5, dtype=np.int32)
+        bt = np.empty(6, dtype=np.int32); bs = np.empty(6, dtype=np.int32)
+        L.oracle_bucket(p(tok), ctypes.c_int(2), ctypes.c_int(3), ctypes.c_int(4), p(c), p(o), p(bt), p(bs))
+        assert c.tolist() == [2, 2, 2, 0]
+        print("sanitized oracle ok")
+    """)
+    # the sanitizer runtimes go first; whatever the environment already preloads stays in the list
+    preload = " ".join([asan, ubsan, os.environ.get("LD_PRELOAD", "")]).strip()
+    env = dict(os.environ, LD_PRELOAD=preload, ASAN_OPTIONS="detect_leaks=0", OMP_NUM_THREADS="2")
+    res = subprocess.run([sys.executable, "-c", code], env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
+                         text=True, timeout=300)
+    assert res.returncode == 0 and "sanitized oracle ok" in res.stdout, res.stdout[-3000:]

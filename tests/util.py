@@ -43,9 +43,16 @@ def tol(shape) -> float:
     return 5e-3 if shape.dtype == "bf16" else 1e-5
 
 
-def sample_rows(T, counts=None, offsets=None, bucket_tok=None, n_strided=256, n_extreme=8):
-    """Deterministic row sample: strided rows plus rows of the smallest non-empty and largest bucket."""
+def sample_rows(T, counts=None, offsets=None, bucket_tok=None, n_strided=256, n_extreme=8, block=128):
+    """Deterministic row sample: at least 256 evenly strided rows, one row in every block of `block` rows (at an
+    offset inside the block that changes from block to block, so that every row tile of a GEMM and different
+    positions inside the tiles are compared), plus rows of the smallest non-empty and the largest bucket."""
+    n_strided = max(n_strided, 256)
     rows = set(np.linspace(0, T - 1, min(T, n_strided)).astype(np.int64).tolist())
+    for b in range((T + block - 1) // block):
+        lo, hi = b * block, min(T, (b + 1) * block)
+        rows.add(lo + (b * 37 + 11) % (hi - lo))
+    rows.add(T - 1)
     if counts is not None:
         nz = np.nonzero(counts)[0]
         if nz.size:
@@ -54,6 +61,20 @@ def sample_rows(T, counts=None, offsets=None, bucket_tok=None, n_strided=256, n_
             for j in (small, large):
                 rows.update(bucket_tok[offsets[j]:offsets[j + 1]][:n_extreme].tolist())
     return np.array(sorted(rows), dtype=np.int32)
+
+
+def weight_bound(ops, idx_ref, inv_temperature=1.0):
+    """Per-token bound on |w_gpu - w_oracle| of the Eq. 3 weights, [T, 1].
+
+    1e-6 for the softmax arithmetic itself (exp and division in fp32), plus the effect of the fp32 summation noise
+    of the logits: sum_j |d w_i / d g_j| = 2 w_i (1 - w_i) <= 1/2, and the noise of a selected logit is bounded, as
+    the gate test requires of the kernel's logits, by 8 * 2^-24 * (sum_i |x_i * W_gate_ij| + |bias_j|); a
+    temperature scales the logit differences, and with them the noise, by 1/tau."""
+    mag = np.abs(ops["x"].astype(np.float64)) @ np.abs(ops["W_gate"].astype(np.float64))
+    if ops["bias"] is not None:
+        mag = mag + np.abs(ops["bias"].astype(np.float64))
+    noise = 8 * 2.0 ** -24 * np.take_along_axis(mag, idx_ref.astype(np.int64), axis=1).max(axis=1, keepdims=True)
+    return 1e-6 + 0.5 * abs(inv_temperature) * noise
 
 
 def oracle_routing(ops, k):
