@@ -50,7 +50,8 @@ typedef enum {
     METEORA_ERR_INVALID_ARG = 1, /* null required pointer, negative size, k<1, k>N, non-finite scale */
     METEORA_ERR_UNSUPPORTED = 2, /* shape/dtype/alignment outside the limits above */
     METEORA_ERR_WORKSPACE = 3,   /* ws is NULL or ws_bytes too small */
-    METEORA_ERR_HIP = 4          /* a HIP launch reported an error */
+    METEORA_ERR_HIP = 4,         /* a HIP launch reported an error */
+    METEORA_ERR_TOO_LARGE = 5    /* beyond the fixed scratch of an entry point that takes no workspace */
 } meteora_status;
 
 typedef enum { METEORA_F32 = 0, METEORA_BF16 = 1 } meteora_dtype;
@@ -128,6 +129,25 @@ meteora_status meteora_bucket_tokens(const int32_t* topk_idx /*[T,k]*/, int T, i
                                      int32_t* counts /*[N]*/, int32_t* offsets /*[N+1]*/,
                                      int32_t* bucket_tok /*[T*k]*/, int32_t* bucket_slot /*[T*k]*/,
                                      void* ws, size_t ws_bytes, meteora_stream stream);
+
+/*
+ * meteora_bucket_tokens for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * outputs, order and bit-exact results; the per-chunk histograms that the other entry point keeps in
+ * `ws` live in a fixed 256 KiB device array inside the library (one copy per GPU, held until the
+ * process ends), so the call allocates nothing and frees nothing.
+ *   Limit: T <= 65536 tokens (any k <= 8, N <= 64); beyond that METEORA_ERR_TOO_LARGE, nothing is launched.
+ *   The array's device address is looked up on the first call on each device (or by meteora_init).
+ *   All calls on one GPU share the array: calls that can overlap on one GPU (different streams with
+ *   no ordering between them, or several host threads) race on it and must be serialised by the
+ *   caller.  Nothing in it needs clearing between calls: the histogram pass overwrites every entry
+ *   the scatter pass reads, so a call may follow a larger one.
+ * Other errors as for meteora_bucket_tokens.
+ */
+meteora_status meteora_bucket_tokens_noalloc(const int32_t* topk_idx /*[T,k]*/, int T, int k, int N,
+                                             int32_t* counts /*[N]*/, int32_t* offsets /*[N+1]*/,
+                                             int32_t* bucket_tok /*[T*k]*/, int32_t* bucket_slot /*[T*k]*/,
+                                             meteora_stream stream);
 
 /*
  * LoRA term of Eq. 2 for a given routing:

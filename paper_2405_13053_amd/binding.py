@@ -51,6 +51,8 @@ def load_library():
     lib.meteora_gate_topk.argtypes = [vp, vp, vp, i, i, i, i, i, f, vp, vp, vp, vp, sz, vp]
     lib.meteora_bucket_tokens.restype = i
     lib.meteora_bucket_tokens.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp, sz, vp]
+    lib.meteora_bucket_tokens_noalloc.restype = i
+    lib.meteora_bucket_tokens_noalloc.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp]
     lib.meteora_lora_forward.restype = i
     lib.meteora_lora_forward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp, i, vp, sz, vp]
     lib.meteora_linear_forward.restype = i
@@ -180,6 +182,23 @@ def bucket_tokens(topk_idx, N: int, ws: Optional[torch.Tensor] = None):
                                               _p(ws), ws.numel(), _stream())
     if st != 0:
         raise MeteoraError(st, "meteora_bucket_tokens")
+    return counts, offsets, tok, slot
+
+
+def bucket_tokens_noalloc(topk_idx, N: int, out=None):
+    """meteora_bucket_tokens_noalloc: as bucket_tokens, on the library's own fixed scratch.  `out` = the four
+    result tensors (counts, offsets, bucket_tok, bucket_slot) if the caller has them already."""
+    _chk(topk_idx, "topk_idx", torch.int32)
+    T, k = topk_idx.shape
+    dev = topk_idx.device
+    if out is None:
+        out = (torch.empty(N, dtype=torch.int32, device=dev), torch.empty(N + 1, dtype=torch.int32, device=dev),
+               torch.empty(T * k, dtype=torch.int32, device=dev), torch.empty(T * k, dtype=torch.int32, device=dev))
+    counts, offsets, tok, slot = out
+    st = load_library().meteora_bucket_tokens_noalloc(_p(topk_idx), T, k, N, _p(counts), _p(offsets), _p(tok),
+                                                      _p(slot), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_bucket_tokens_noalloc")
     return counts, offsets, tok, slot
 
 

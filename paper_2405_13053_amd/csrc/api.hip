@@ -209,6 +209,7 @@ const char* meteora_status_string(meteora_status s) {
         case METEORA_ERR_UNSUPPORTED: return "unsupported shape, dtype or alignment";
         case METEORA_ERR_WORKSPACE: return "workspace missing or too small";
         case METEORA_ERR_HIP: return "HIP launch error";
+        case METEORA_ERR_TOO_LARGE: return "problem larger than the fixed scratch of a call that takes no workspace";
     }
     return "unknown status";
 }
@@ -340,6 +341,24 @@ meteora_status meteora_bucket_tokens(const int32_t* topk_idx, int T, int k, int 
     }
     METEORA_HIP(launch_bucket(topk_idx, T, k, N, static_cast<int32_t*>(ws), false, counts, offsets, bucket_tok,
                               bucket_slot, nullptr, 0, static_cast<hipStream_t>(stream)));
+    return METEORA_OK;
+}
+
+meteora_status meteora_bucket_tokens_noalloc(const int32_t* topk_idx, int T, int k, int N, int32_t* counts,
+                                             int32_t* offsets, int32_t* bucket_tok, int32_t* bucket_slot,
+                                             meteora_stream stream) {
+    if (!topk_idx || !counts || !offsets || !bucket_tok || !bucket_slot) return METEORA_ERR_INVALID_ARG;
+    if (!shape_ok(T, 8, 8, N, 1, k)) return METEORA_ERR_INVALID_ARG;
+    if (!shape_supported(T, 8, 8, N, 1, k)) return METEORA_ERR_UNSUPPORTED;
+    if (T > kStaticBucketMaxTokens) return METEORA_ERR_TOO_LARGE;   // beyond the library's fixed scratch
+    if (!aligned16(topk_idx) || !aligned4(counts) || !aligned4(offsets) || !aligned16(bucket_tok) ||
+        !aligned16(bucket_slot))
+        return METEORA_ERR_UNSUPPORTED;
+    if (T == 0) return METEORA_OK;
+    int32_t* chunk_counts = nullptr;   // the current device's copy of the library's scratch array
+    METEORA_HIP(bucket_static_scratch(&chunk_counts));
+    METEORA_HIP(launch_bucket(topk_idx, T, k, N, chunk_counts, false, counts, offsets, bucket_tok, bucket_slot, nullptr,
+                              0, static_cast<hipStream_t>(stream)));
     return METEORA_OK;
 }
 

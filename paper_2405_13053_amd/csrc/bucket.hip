@@ -9,10 +9,47 @@
 //           in order.  The in-chunk rank uses wavefront ballots, so the result is the stable
 //           sort: ascending token, then ascending slot, inside every bucket.
 // Integer work only; the output is unique and bit-comparable.
+#include <mutex>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
 namespace meteora {
+
+// Scratch of the entry point that allocates nothing and takes no workspace (meteora_bucket_tokens_noalloc): the
+// per-chunk histograms of up to kStaticBucketMaxTokens tokens, 256 KiB that every GPU the library runs on holds
+// until the process ends.  In host code the array's name is only a stand-in for the symbol: the device address
+// comes from hipGetSymbolAddress, once per device, and only that pointer is handed to kernels.
+static __device__ __align__(256) int32_t scratch[(kStaticBucketMaxTokens / kBucketChunkTokens) * kMaxAdapters];
+
+namespace {
+constexpr int kScratchMaxDevices = 64;
+int32_t* g_scratch_ptr[kScratchMaxDevices];
+std::mutex g_scratch_mutex;
+}  // namespace
+
+// Device address of `scratch` on the current device (looked up on first use, then kept).
+hipError_t bucket_static_scratch(int32_t** ptr) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kScratchMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+hipError_t bucket_init_scratch() {
+    int32_t* p = nullptr;
+    return bucket_static_scratch(&p);
+}
 
 __global__ __launch_bounds__(256) void bucket_hist_kernel(const int32_t* __restrict__ topk_idx,
                                                           int64_t pairs, int k, int N,

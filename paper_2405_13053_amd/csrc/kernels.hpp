@@ -15,6 +15,7 @@ hipError_t init_kernels();
 hipError_t gemm_init_kernels();
 hipError_t gate_init_kernels();
 hipError_t shrink_init_kernels();
+hipError_t bucket_init_scratch();
 
 // ---- weight repacking, one launch: W_gate -> split bf16 fragments (bf16 gate), A -> MFMA fragments,
 // stacked B -> its transpose Bt[d_out, N*r rounded up to 64] (zero-padded) for the GEMM's K-extension.
@@ -84,6 +85,10 @@ hipError_t launch_gemm_dense_splitk_multi(const void* x, const DenseOperand* ops
 // ---- bucketing (Sec. 3.3: per-adapter token sets as index lists) --------------------------
 constexpr int kBucketChunkTokens = 64;   // tokens (k pairs each) whose pairs one workgroup histograms and scatters
 inline int bucket_chunks(int T) { return (T + kBucketChunkTokens - 1) / kBucketChunkTokens; }
+// The library's own histogram scratch (a file-scope device array, one copy per GPU) for the entry point that takes
+// no workspace: room for kStaticBucketMaxTokens tokens and any supported N; the pointer is the current device's.
+constexpr int kStaticBucketMaxTokens = 65536;
+hipError_t bucket_static_scratch(int32_t** ptr);
 // have_hist: chunk_counts already holds the histograms (written by launch_gate_topk)
 // clear_rows (optional): a [T][clear_row_bytes] array (row bytes a multiple of 16) that the scatter zeroes,
 // every chunk its own rows: the dense expand operand that launch_shrink then fills in (shrink_clears_hdense)

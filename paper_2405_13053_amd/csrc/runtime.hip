@@ -45,7 +45,9 @@ hipError_t init_kernels() {
     if (e != hipSuccess) return e;
     e = gate_init_kernels();
     if (e != hipSuccess) return e;
-    return shrink_init_kernels();
+    e = shrink_init_kernels();
+    if (e != hipSuccess) return e;
+    return bucket_init_scratch();
 }
 
 }  // namespace meteora

@@ -271,3 +271,17 @@ def test_base_gemm_validation(lib):
     assert f(di=12) == UNSUPPORTED
     assert f(dt=2) == UNSUPPORTED
     assert f(T=0) == OK
+
+
+def test_bucket_tokens_noalloc_validation(lib):
+    """The entry point on the library's own scratch rejects bad arguments and sizes beyond its fixed scratch on the
+    host, before any HIP call."""
+    f = lambda idx=P, T=64, k=2, N=4, c=P, o=P, bt=P, bs=P: lib.meteora_bucket_tokens_noalloc(idx, T, k, N, c, o, bt,
+                                                                                          bs, None)
+    assert f(idx=None) == INVALID and f(c=None) == INVALID and f(bs=None) == INVALID
+    assert f(k=5) == INVALID and f(T=-1) == INVALID
+    assert f(N=65, k=2) == UNSUPPORTED
+    assert f(idx=ODD) == UNSUPPORTED
+    assert f(T=65537) == 5 and f(T=1 << 20) == 5          # METEORA_ERR_TOO_LARGE
+    assert b"fixed scratch" in lib.meteora_status_string(5)
+    assert f(T=0) == OK
