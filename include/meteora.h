@@ -300,6 +300,36 @@ meteora_status meteora_gate_backward(const void* x /*[T,d_in]*/, const void* dy 
                                      void* ws, size_t ws_bytes, meteora_stream stream);
 
 /*
+ * The paper's own schedules of Eq. 2 (Sec. 3.3), as baselines to measure against on the same GPU.  Same
+ * arguments, result and routing as meteora_linear_forward (inv_temperature = 1); only the LoRA term is
+ * scheduled differently, from this library's gate, bucketing and GEMM kernels plus plain gather / scatter /
+ * batched-product kernels.  Not part of the layer's own path.
+ *   METEORA_VARIANT_LOOP_ORIGINAL  "loop-original": for each adapter i in turn, gather the tokens routed to it
+ *       (X_i), two GEMMs (X_i A_i) B_i, weighted scatter-add into out.  The launch shapes depend on the
+ *       routing, so the call SYNCHRONISES `stream` once to read the per-adapter counts on the host (it cannot
+ *       be captured into a HIP graph); up to 4 launches per non-empty adapter.
+ *   METEORA_VARIANT_BMM_GATHER     Eq. 5 ("bmm-torch"): A_{I(t)_j} and B_{I(t)_j} are copied for every
+ *       (token, slot) pair (T*k/N times the size of the stacked adapters, the cost Sec. 3.3 names), then two
+ *       batched products over the T*k pairs and the weighted sum over the k slots.
+ * Intermediates are stored in dt (X_i A_i, (X_i A_i) B_i and the running output are rounded to bf16 for
+ * METEORA_BF16, as a framework-level implementation does), so outputs agree with the layer call to a few
+ * bf16 roundings, not bit for bit.
+ * Limits: as meteora_linear_forward, and r % 8 == 0.  ws: meteora_variant_workspace_bytes (bmm-gather:
+ * about T*k*r*(d_in+d_out) elements).  Errors as for meteora_linear_forward.
+ */
+typedef enum { METEORA_VARIANT_LOOP_ORIGINAL = 0, METEORA_VARIANT_BMM_GATHER = 1 } meteora_variant;
+
+size_t meteora_variant_workspace_bytes(meteora_variant variant, int T, int d_in, int d_out, int N, int r, int k,
+                                       meteora_dtype dt);
+
+meteora_status meteora_variant_forward(meteora_variant variant, const void* x, const void* W, const float* W_gate,
+                                       const float* gate_bias, const void* A, const void* B,
+                                       int T, int d_in, int d_out, int N, int r, int k, float scale, meteora_dtype dt,
+                                       void* out /*[T,d_out]*/, int32_t* topk_idx_out /*[T,k] or NULL*/,
+                                       float* topk_w_out /*[T,k] or NULL*/,
+                                       void* ws, size_t ws_bytes, meteora_stream stream);
+
+/*
  * Base projection alone, first term of Eq. 1 / Eq. 2: out = x * W
  * (W stored [d_out, d_in]).  Exposed so the dense contraction can be checked
  * and timed on its own.
@@ -311,7 +341,8 @@ meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, 
  * Optional per-stage timing, for benchmarks.  Host only; off by default.
  * While enabled, meteora_lora_forward and meteora_linear_forward record
  * hipEvents on `stream` around each stage (prep, gate_logits, gate_topk,
- * bucket, shrink, gemm, expand) for up to 256 calls.  A stage that a batch size
+ * bucket, shrink, gemm, expand) for up to 256 calls.  A stage's reading is its kernels' time
+ * plus the dispatch gap in front of them (about 2 us per launch against a kernel trace).  A stage that a batch size
  * folds into another is not reported: for 64 < T <= 8192 (bf16) gate_logits covers
  * the gate logits and the shrink, gate_topk the top-k, softmax and selection (batches with few output tiles:
  * gemm covers the K-split projection with those products, expand the reduction with the expand); for

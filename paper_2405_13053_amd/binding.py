@@ -77,6 +77,10 @@ def load_library():
     lib.meteora_gate_backward.restype = i
     lib.meteora_gate_backward.argtypes = [vp, vp, vp, vp, vp, sz, vp, vp, vp, f, i, i, i, i, i, i, f, i, vp, vp, vp,
                                           vp, vp, vp, vp, vp, sz, vp, sz, vp]
+    lib.meteora_variant_workspace_bytes.restype = sz
+    lib.meteora_variant_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
+    lib.meteora_variant_forward.restype = i
+    lib.meteora_variant_forward.argtypes = [i, vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp, vp, vp, vp, sz, vp]
     lib.meteora_base_gemm.restype = i
     lib.meteora_base_gemm.argtypes = [vp, vp, i, i, i, i, vp, vp]
     lib.meteora_stage_count.restype = i
@@ -374,6 +378,43 @@ def gate_backward(x, dy, gate_bias, B, packed, k: int, scale: float, labels=None
     if st != 0:
         raise MeteoraError(st, "meteora_gate_backward")
     return (dW, db, dl, dxo) if want_dx else (dW, db, dl)
+
+
+LOOP_ORIGINAL, BMM_GATHER = 0, 1
+
+
+def variant_workspace_bytes(variant: int, T, d_in, d_out, N, r, k, dtype) -> int:
+    dt = BF16 if dtype in (torch.bfloat16, BF16, "bf16") else F32
+    return int(load_library().meteora_variant_workspace_bytes(int(variant), T, d_in, d_out, N, r, k, dt))
+
+
+def variant_forward(variant: int, x, W, W_gate, gate_bias, A, B, k: int, scale: float,
+                    out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                    return_routing: bool = False):
+    """meteora_variant_forward: the layer through one of the paper's own schedules (LOOP_ORIGINAL, BMM_GATHER)."""
+    T, d_in = x.shape
+    d_out = W.shape[0]
+    N, _, r = A.shape
+    _chk(x, "x"); _chk(W, "W", x.dtype, (d_out, d_in)); _chk(W_gate, "W_gate", torch.float32, (d_in, N))
+    _chk(gate_bias, "gate_bias", torch.float32, (N,))
+    _chk(A, "A", x.dtype, (N, d_in, r)); _chk(B, "B", x.dtype, (N, r, d_out))
+    if out is None:
+        out = torch.empty((T, d_out), dtype=x.dtype, device=x.device)
+    _chk(out, "out", x.dtype, (T, d_out))
+    idx = w = None
+    if return_routing:
+        idx = torch.empty((T, k), dtype=torch.int32, device=x.device)
+        w = torch.empty((T, k), dtype=torch.float32, device=x.device)
+    need = variant_workspace_bytes(variant, T, d_in, d_out, N, r, k, x.dtype)
+    if need == 0 and T > 0:
+        raise MeteoraError(2, "meteora_variant_workspace_bytes")
+    ws = _ws(ws, need, x.device)
+    st = load_library().meteora_variant_forward(int(variant), _p(x), _p(W), _p(W_gate), _p(gate_bias), _p(A), _p(B),
+                                                T, d_in, d_out, N, r, k, float(scale), _dt(x), _p(out), _p(idx),
+                                                _p(w), _p(ws), ws.numel(), _stream())
+    if st != 0:
+        raise MeteoraError(st, "meteora_variant_forward")
+    return (out, idx, w) if return_routing else out
 
 
 def base_gemm(x, W, out: Optional[torch.Tensor] = None):

@@ -134,7 +134,7 @@ struct StageScope {
     }
 };
 
-int timing_begin_call() {
+int timing_begin_call(hipStream_t) {
     if (!g_timing.on || g_timing.calls >= kTimingRing) return -1;
     return g_timing.calls++;
 }
@@ -435,7 +435,7 @@ meteora_status meteora_lora_forward(const void* x, const void* A, const void* B,
     }
     const PackedPtrs pk{nullptr, at<void>(ws, L.apack), at<void>(ws, L.btrans), nullptr};
     return run_lora(x, nullptr, A, B, topk_idx, topk_w, T, d_in, d_out, N, r, k, scale, bf16, out, accumulate, ws, L,
-                    pk, static_cast<hipStream_t>(stream), timing_begin_call(), false);
+                    pk, static_cast<hipStream_t>(stream), timing_begin_call(static_cast<hipStream_t>(stream)), false);
 }
 
 meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, int d_out, meteora_dtype dt,
@@ -501,7 +501,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
     int32_t* idx = topk_idx_out ? topk_idx_out : at<int32_t>(ws, L.topk_idx);
     float* w = topk_w_out ? topk_w_out : at<float>(ws, L.topk_w);
     float* partials = at<float>(ws, L.partials);
-    const int tslot = timing_begin_call();
+    const int tslot = timing_begin_call(st);
     // mid-sized batch: gate logits and the shrink of every adapter in one MFMA launch, selection afterwards
     const bool dense = route_dense_applies(T, d_in, N, r, bf16);
     const bool decode3 = decode_fused_applies(T, d_in, d_out, N, r, bf16);
@@ -723,7 +723,7 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
             ops[2 * g] = {mem[g].W, m.d_out, mem[g].partial};
             ops[2 * g + 1] = {mem[g].wg3, cat_rows, mem[g].gpartial};
         }
-        const int tslot = timing_begin_call();
+        const int tslot = timing_begin_call(st);
         {
             StageScope sc(ST_GEMM, st, tslot);
             METEORA_HIP(launch_gemm_dense_splitk_multi(x, ops, 2 * G, S, T, d_in, st));
@@ -759,7 +759,7 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
                               m.topk_idx_out ? m.topk_idx_out : at<int32_t>(ws, L.idx[g]),
                               m.topk_w_out ? m.topk_w_out : at<float>(ws, L.w[g]), m.out};
     }
-    const int tslot = timing_begin_call();
+    const int tslot = timing_begin_call(st);
     {
         StageScope sc(ST_GEMM, st, tslot);
         METEORA_HIP(launch_gemm_decode_main(x, mem, G, gate_rows, L.S, T, d_in, st));

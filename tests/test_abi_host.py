@@ -285,3 +285,25 @@ def test_bucket_tokens_noalloc_validation(lib):
     assert f(T=65537) == 5 and f(T=1 << 20) == 5          # METEORA_ERR_TOO_LARGE
     assert b"fixed scratch" in lib.meteora_status_string(5)
     assert f(T=0) == OK
+
+
+def test_variant_validation(lib):
+    """The paper's schedules as baselines: sizes and argument checks on the host."""
+    LOOP, BMM = 0, 1
+    wl = lib.meteora_variant_workspace_bytes(LOOP, 4096, 4096, 4096, 28, 8, 2, BF16)
+    wb = lib.meteora_variant_workspace_bytes(BMM, 4096, 4096, 4096, 28, 8, 2, BF16)
+    assert wl > 0 and wb >= 4096 * 2 * 8 * (4096 + 4096) * 2        # the gathered copies of A and B
+    assert lib.meteora_variant_workspace_bytes(2, 64, 256, 256, 4, 8, 2, BF16) == 0     # unknown variant
+    assert lib.meteora_variant_workspace_bytes(LOOP, 64, 256, 256, 4, 5, 2, BF16) == 0  # r % 8
+
+    def call(v=LOOP, x=P, W=P, A=P, T=64, r=8, k=2, s=2.0, ws=WS, wsb=BIG, out=P):
+        return lib.meteora_variant_forward(v, x, W, P, None, A, P, T, 256, 256, 4, r, k, s, BF16, out, None, None, ws,
+                                           wsb, None)
+
+    for v in (LOOP, BMM):
+        assert call(v, x=None) == INVALID and call(v, out=None) == INVALID and call(v, W=None) == INVALID
+        assert call(v, k=5) == INVALID and call(v, s=float("nan")) == INVALID
+        assert call(v, r=5) == UNSUPPORTED and call(v, A=ODD) == UNSUPPORTED
+        assert call(v, ws=None) == WORKSPACE and call(v, wsb=1024) == WORKSPACE
+        assert call(v, T=0) == OK
+    assert call(v=7) == INVALID
