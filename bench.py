@@ -358,13 +358,14 @@ def summarize_pmc(fetch_dir, write_dir):
         sys.exit("summarize-pmc: no FETCH_SIZE / WRITE_SIZE rows found")
 
     def copy_scale(rows):
-        # the calibration copy: torch's elementwise copy kernel, three dispatches of CALIBRATION_COPY_BYTES each
-        cand = [(k, v) for k, v in rows.items() if "elementwise_kernel" in k and "copy" in k.lower()]
-        best = max(cand, key=lambda kv: sum(kv[1]) / len(kv[1]), default=None)
-        if best is None:
+        # the calibration copy: the runtime's device-to-device copy kernel, the first three dispatches of it are
+        # --pmc-calibration's copies of CALIBRATION_COPY_BYTES each (they run before anything else)
+        cand = [(k, v) for k, v in rows.items() if "copyBuffer" in k]
+        if not cand or len(cand[0][1]) < 3:
             sys.exit("summarize-pmc: calibration copy kernel not found (run bench.py with --pmc-calibration)")
-        avg = sum(best[1][-3:]) / len(best[1][-3:])
-        return (CALIBRATION_COPY_BYTES / 1024.0) / avg, best[0], avg
+        name, vals = cand[0]
+        avg = sum(vals[:3]) / 3.0
+        return (CALIBRATION_COPY_BYTES / 1024.0) / avg, name, avg
     fs, fname, favg = copy_scale(fetch)
     wsc, wname, wavg = copy_scale(write)
     kernels = {}

@@ -329,6 +329,8 @@ GRAPH_SHAPES = [
     LS(33, 1024, 520, 28, 8, 2, 2.0, "bf16", "uniform", "graph-decode"),
     LS(333, 1024, 520, 28, 8, 2, 2.0, "bf16", "zipf", "graph-dense-route"),
     LS(400, 1024, 520, 28, 16, 2, 2.0, "bf16", "uniform", "graph-bucketed"),
+    # dense routing in front of the fused GEMM (too many output tiles for the split-K form)
+    LS(2500, 512, 2056, 28, 8, 2, 2.0, "bf16", "uniform", "graph-dense-route-fused-gemm"),
 ]
 
 
@@ -362,6 +364,30 @@ def test_layer_call_replays_from_a_hip_graph(shape):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, ref), f"replay {rep} differs from the eager call"
+
+
+@pytest.mark.parametrize("T", [40, 300, 2500, 9000])
+def test_layer_call_does_not_depend_on_workspace_contents(T):
+    """The workspace arrives uninitialised: whatever it holds (zeros, all ones, random bytes, the leftovers of other
+    calls), the result is the same, call after call."""
+    shape = LS(T, 512, 2056, 28, 8, 2, 2.0, "bf16", "zipf", "workspace-garbage")
+    ops, dev = util.make_case(shape, seed=55, condition=False)
+    dt = torch.bfloat16
+    packed = m.pack_weights(dev["W_gate"], dev["A"], dev["B"])
+    args = (dev["x"], dev["W"], dev["W_gate"], dev["bias"], dev["A"], dev["B"], shape.k, shape.scale)
+    ref, idx_ref, w_ref = m.linear_forward(*args, packed=packed, return_routing=True)
+    nbytes = m.workspace_bytes(shape.T, shape.d_in, shape.d_out, shape.N, shape.r, shape.k, dt)
+    gen_t = torch.Generator(device="cuda").manual_seed(9)
+    fills = [lambda n: torch.zeros(n, dtype=torch.uint8, device="cuda"),
+             lambda n: torch.full((n,), 255, dtype=torch.uint8, device="cuda"),
+             lambda n: torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda", generator=gen_t),
+             lambda n: torch.full((n,), 1, dtype=torch.uint8, device="cuda")]
+    for fill in fills:
+        ws = fill(nbytes)
+        for rep in range(2):   # the second call finds what the first one left
+            out, idx, w = m.linear_forward(*args, packed=packed, ws=ws, return_routing=True)
+            torch.cuda.synchronize()
+            assert torch.equal(idx, idx_ref) and torch.equal(w, w_ref) and torch.equal(out, ref)
 
 
 def test_many_tokens_small_layer_sampled_rows():
