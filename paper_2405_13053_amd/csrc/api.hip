@@ -530,12 +530,9 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
             StageScope sc(ST_GEMM, st, tslot);
             METEORA_HIP(launch_gemm_decode_main(x, &mem, 1, gate_rows, S, T, d_in, st));
         }
-        {
-            StageScope sc(ST_SHRINK, st, tslot);
-            METEORA_HIP(launch_route_shrink_small_group(x, &mem, 1, S, T, d_in, N, r, k, inv_temperature, scale, st));
-        }
-        StageScope sc(ST_EXPAND, st, tslot);
-        METEORA_HIP(launch_gemm_decode_finish(&mem, 1, S, T, k, r, st));
+        // top-k, softmax, the shrink of the selected adapters, then the split-K reduction with the expand: one launch
+        StageScope sc(ST_SHRINK, st, tslot);
+        METEORA_HIP(launch_route_shrink_finish_group(x, &mem, 1, S, T, d_in, N, r, k, inv_temperature, scale, st));
         return METEORA_OK;
     }
     if (dense) {
@@ -764,12 +761,8 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
         StageScope sc(ST_GEMM, st, tslot);
         METEORA_HIP(launch_gemm_decode_main(x, mem, G, gate_rows, L.S, T, d_in, st));
     }
-    {
-        StageScope sc(ST_SHRINK, st, tslot);
-        METEORA_HIP(launch_route_shrink_small_group(x, mem, G, L.S, T, d_in, N, r, k, inv_temperature, scale, st));
-    }
-    StageScope sc(ST_EXPAND, st, tslot);
-    METEORA_HIP(launch_gemm_decode_finish(mem, G, L.S, T, k, r, st));
+    StageScope sc(ST_SHRINK, st, tslot);
+    METEORA_HIP(launch_route_shrink_finish_group(x, mem, G, L.S, T, d_in, N, r, k, inv_temperature, scale, st));
     return METEORA_OK;
 }
 

@@ -146,6 +146,11 @@ hipError_t launch_gemm_decode_main(const void* x, const DecodeMember* mem, int G
 hipError_t launch_route_shrink_small_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
                                            int r, int k, float inv_temperature, float scale, hipStream_t stream);
 hipError_t launch_gemm_decode_finish(const DecodeMember* mem, int G, int S, int T, int k, int r, hipStream_t stream);
+// launch_route_shrink_small_group and launch_gemm_decode_finish in ONE launch: every token's row is cut into
+// stretches, one workgroup each, which repeat the token's routing and shrink and then reduce and expand their
+// stretch (same bits as the two launches; mem[g].hs is not written)
+hipError_t launch_route_shrink_finish_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
+                                            int r, int k, float inv_temperature, float scale, hipStream_t stream);
 // The same three launches for batches of a few hundred tokens with few output tiles: launch_gemm_dense_splitk_multi over
 // every W_g and Wcat_g (gpartial_g then holds [S][T][prep_wcat_rows]), this selection for all members, the finish above.
 hipError_t launch_route_dense_select_group(const DecodeMember* mem, int G, int S, int T, int N, int r, int k,

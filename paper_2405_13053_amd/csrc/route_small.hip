@@ -27,12 +27,30 @@ struct RouteGroup {
     int G;   // 0: the kernel's own pointer arguments describe the one layer
 };
 
-template <int R8>   // R8 = r / 8: 16-byte pieces per row of A_a
+// The rest of a decode-sized layer call in the same launch (FINISH): once a token's shrink values are known its
+// workgroup also adds the K-split tiles of the base projection for a stretch of the token's output row, in split
+// order, adds the expand of Eq. 2 from the shrink values it holds in LDS, and rounds once:
+//   out[t, c] = bf16( sum_s partial[s][t][c] + sum_slot sum_q (scale * w * h)[slot][q] * B[a_slot][q][c] ).
+// A token's row is cut into `chunks` stretches, one workgroup each (blockIdx = (member * T + token) * chunks +
+// chunk), so that the launch fills the chip; the workgroups of a token repeat its routing and shrink (a few hundred
+// KB from L2 each) instead of waiting for one another.  Arithmetic and order are those of
+// gemm_splitk_reduce_expand_kernel.
+struct FinishGroup {
+    struct Member {
+        const float* partial;   // [S][T][d_out]
+        const bf16_t* B;        // [N, r, d_out]
+        bf16_t* out;            // [T, d_out]
+        int d_out;
+    } m[kMaxDecodeGroup];
+    int nsplit, chunks;         // chunks == 0: no finish stage
+};
+
+template <int R8, bool FINISH = false>   // R8 = r / 8: 16-byte pieces per row of A_a
 __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
     const bf16_t* __restrict__ x, const float* __restrict__ partials, int KS, const float* bias_in,
     const bf16_t* A_in, int T, int d_in, int N, int NP, int k, float inv_temperature, float scale,
     int32_t* idx_in, float* w_in, bf16_t* __restrict__ hdense, int ext_stride,
-    const float* gpart_in, int GS, float* hs_in, const RouteGroup rg) {
+    const float* gpart_in, int GS, float* hs_in, const RouteGroup rg, const FinishGroup fg) {
     constexpr int r = R8 * 8;
     constexpr int ROWS = 8 / R8;   // rows of A_a per slot whose loads are in flight together
     __shared__ int sel_idx[kMaxTopK];
@@ -40,7 +58,11 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
     __shared__ float red[kSmallWaves][kMaxTopK][r];
     __shared__ float gsum[2][kSmallWaves][kMaxAdapters];   // per-split logit terms, double-buffered over rounds
     float glog = 0.f;
-    int t = blockIdx.x;
+    int t = blockIdx.x, member = 0, chunk = 0;
+    if constexpr (FINISH) {
+        chunk = blockIdx.x % fg.chunks;
+        t = blockIdx.x / fg.chunks;
+    }
     const float* __restrict__ bias = bias_in;
     const bf16_t* __restrict__ A = A_in;
     int32_t* __restrict__ topk_idx = idx_in;
@@ -48,12 +70,34 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
     const float* __restrict__ gpart = gpart_in;
     float* __restrict__ hs = hs_in;
     if (rg.G > 0) {   // uniform
-        const int g = blockIdx.x / T;
-        t = blockIdx.x - g * T;
+        const int g = t / T;
+        t = t - g * T;
+        member = g;
         bias = rg.m[g].bias; A = rg.m[g].A; topk_idx = rg.m[g].idx; topk_w = rg.m[g].w;
         gpart = rg.m[g].gpart; hs = rg.m[g].hs;
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    // FINISH: the K-split tiles of this thread's first 8 output columns do not depend on the routing: their loads
+    // (the first 8 splits) go out now and are added, in split order, once the top-k is done, so that their latency
+    // hides behind the logit fetch and the ranking
+    f32x4 pre0[8], pre1[8];
+    f32x4 pre_lo = {0.f, 0.f, 0.f, 0.f}, pre_hi = {0.f, 0.f, 0.f, 0.f};
+    int fin_first = 0, fin_end = 0;
+    if constexpr (FINISH) {
+        const int c8 = fg.m[member].d_out / 8, per = (c8 + fg.chunks - 1) / fg.chunks;
+        fin_first = chunk * per + threadIdx.x;
+        fin_end = min(c8, (chunk + 1) * per);
+        if (fin_first < fin_end) {
+            const float* base = fg.m[member].partial + (size_t)t * fg.m[member].d_out + fin_first * 8;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float* src = base + (size_t)min(u, fg.nsplit - 1) * T * fg.m[member].d_out;
+                pre0[u] = *reinterpret_cast<const f32x4*>(src);
+                pre1[u] = *reinterpret_cast<const f32x4*>(src + 4);
+            }
+        }
+    }
 
     // this token's row of the dense expand operand starts as zeros
     if (hdense != nullptr) {
@@ -103,11 +147,20 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
         if (lane < k) {
             sel_idx[lane] = my_i[0];
             sel_w[lane] = my_w[0];
-            topk_idx[(size_t)t * k + lane] = my_i[0];
-            topk_w[(size_t)t * k + lane] = my_w[0];
+            if (chunk == 0) {   // the workgroups of a token compute the same routing: one of them reports it
+                topk_idx[(size_t)t * k + lane] = my_i[0];
+                topk_w[(size_t)t * k + lane] = my_w[0];
+            }
         }
     }
     __syncthreads();
+    if constexpr (FINISH) {
+        if (fin_first < fin_end) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (u < fg.nsplit) { pre_lo += pre0[u]; pre_hi += pre1[u]; }
+        }
+    }
 
     // shrink: thread `tid` takes rows tid, tid + 1024, ... of A_a (r bf16 = R8 16-byte pieces each); two slots
     // at a time so that both adapters' loads are in flight together
@@ -185,13 +238,71 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
         }
     }
     __syncthreads();
+    __shared__ float hsl[kMaxTopK * r];   // scale * w * h of this token (FINISH)
     for (int e = threadIdx.x; e < k * r; e += kSmallThreads) {
         const int slot = e / r, q = e - slot * r;
         float h = 0.f;
 #pragma unroll
         for (int wv = 0; wv < kSmallWaves; ++wv) h += red[wv][slot][q];   // fixed order
-        if (hs != nullptr) hs[((size_t)t * k + slot) * r + q] = scale * sel_w[slot] * h;
-        else hdense[(size_t)t * ext_stride + sel_idx[slot] * r + q] = from_float<bf16_t>(scale * sel_w[slot] * h);
+        const float v = scale * sel_w[slot] * h;
+        if constexpr (FINISH) {
+            hsl[e] = v;
+            if (hs != nullptr && chunk == 0) hs[((size_t)t * k + slot) * r + q] = v;
+        } else {
+            if (hs != nullptr) hs[((size_t)t * k + slot) * r + q] = v;
+            else hdense[(size_t)t * ext_stride + sel_idx[slot] * r + q] = from_float<bf16_t>(v);
+        }
+    }
+    if constexpr (FINISH) {
+        __syncthreads();
+        const float* __restrict__ partial = fg.m[member].partial;
+        const bf16_t* __restrict__ B = fg.m[member].B;
+        bf16_t* __restrict__ out = fg.m[member].out;
+        const int d_out = fg.m[member].d_out, nsplit = fg.nsplit;
+        for (int gi = fin_first; gi < fin_end; gi += kSmallThreads) {   // 8 consecutive columns
+            const int c = gi * 8;
+            // the first stretch of this thread starts from the sums of the splits fetched at the top
+            const bool first = gi == fin_first;
+            f32x4 lo = first ? pre_lo : f32x4{0.f, 0.f, 0.f, 0.f}, hi = first ? pre_hi : f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int s0 = first ? 8 : 0; s0 < nsplit; s0 += 8) {   // tiles in order, 8 tiles' loads in flight
+                f32x4 v0[8], v1[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float* src = partial + ((size_t)min(s0 + u, nsplit - 1) * T + t) * d_out + c;
+                    v0[u] = *reinterpret_cast<const f32x4*>(src);
+                    v1[u] = *reinterpret_cast<const f32x4*>(src + 4);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < nsplit) { lo += v0[u]; hi += v1[u]; }
+            }
+            for (int slot = 0; slot < k; ++slot) {
+                const bf16_t* Ba = B + (size_t)sel_idx[slot] * r * d_out + c;
+                const float* h = hsl + slot * r;
+#pragma unroll
+                for (int q0 = 0; q0 < r; q0 += 8) {   // 8 rows of B in flight
+                    u32x4 b[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) b[u] = *reinterpret_cast<const u32x4*>(Ba + (size_t)(q0 + u) * d_out);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const float hv = h[q0 + u];
+                        lo[0] = fmaf(hv, bf16_bits_to_float(b[u][0] & 0xffffu), lo[0]);
+                        lo[1] = fmaf(hv, bf16_bits_to_float(b[u][0] >> 16), lo[1]);
+                        lo[2] = fmaf(hv, bf16_bits_to_float(b[u][1] & 0xffffu), lo[2]);
+                        lo[3] = fmaf(hv, bf16_bits_to_float(b[u][1] >> 16), lo[3]);
+                        hi[0] = fmaf(hv, bf16_bits_to_float(b[u][2] & 0xffffu), hi[0]);
+                        hi[1] = fmaf(hv, bf16_bits_to_float(b[u][2] >> 16), hi[1]);
+                        hi[2] = fmaf(hv, bf16_bits_to_float(b[u][3] & 0xffffu), hi[2]);
+                        hi[3] = fmaf(hv, bf16_bits_to_float(b[u][3] >> 16), hi[3]);
+                    }
+                }
+            }
+            u32x4 pk;
+            pk[0] = pack_bf16x2(lo[0], lo[1]); pk[1] = pack_bf16x2(lo[2], lo[3]);
+            pk[2] = pack_bf16x2(hi[0], hi[1]); pk[3] = pack_bf16x2(hi[2], hi[3]);
+            *reinterpret_cast<u32x4*>(out + (size_t)t * d_out + c) = pk;
+        }
     }
 }
 
@@ -205,7 +316,7 @@ hipError_t launch_route_shrink_small(const void* x, const float* partials, int K
     auto go = [&](auto kern) {
         kern<<<T, kSmallThreads, 0, stream>>>((const bf16_t*)x, partials, KS, bias, (const bf16_t*)A, T, d_in, N, NP, k,
                                     inv_temperature, scale, topk_idx, topk_w, (bf16_t*)hdense, ext_stride, gpart,
-                                    GS, hs, RouteGroup{});
+                                    GS, hs, RouteGroup{}, FinishGroup{});
         return hipGetLastError();
     };
     if (r == 8) return go(route_shrink_small_kernel<1>);
@@ -225,12 +336,46 @@ hipError_t launch_route_shrink_small_group(const void* x, const DecodeMember* me
     auto go = [&](auto kern) {
         kern<<<G * T, kSmallThreads, 0, stream>>>((const bf16_t*)x, nullptr, 0, nullptr, nullptr, T, d_in, N, NP, k,
                                                   inv_temperature, scale, nullptr, nullptr, nullptr, 0, nullptr, S,
-                                                  nullptr, rg);
+                                                  nullptr, rg, FinishGroup{});
         return hipGetLastError();
     };
     if (r == 8) return go(route_shrink_small_kernel<1>);
     if (r == 16) return go(route_shrink_small_kernel<2>);
     if (r == 32) return go(route_shrink_small_kernel<4>);
+    return hipErrorInvalidValue;
+}
+
+// Routing, shrink, split-K reduction and expand of decode-sized calls in one launch (the FINISH form of the kernel):
+// replaces launch_route_shrink_small_group followed by launch_gemm_decode_finish, with the same results bit for bit.
+int decode_finish_chunks(int T, int G) {
+    // about one workgroup per CU (a workgroup is 16 wavefronts): 256 / (G * T), at least 1, at most 16
+    int ch = 256 / (G * T > 0 ? G * T : 1);
+    return ch < 1 ? 1 : (ch > 16 ? 16 : ch);
+}
+
+hipError_t launch_route_shrink_finish_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
+                                            int r, int k, float inv_temperature, float scale, hipStream_t stream) {
+    if (G < 1 || G > kMaxDecodeGroup || S < 1) return hipErrorInvalidValue;
+    const int NP = padded_adapters(N);
+    RouteGroup rg{};
+    FinishGroup fg{};
+    for (int g = 0; g < G; ++g) {
+        if (mem[g].d_out % 8 != 0) return hipErrorInvalidValue;
+        rg.m[g] = {mem[g].gpartial, mem[g].bias, (const bf16_t*)mem[g].A, mem[g].idx, mem[g].w, nullptr};
+        fg.m[g] = {mem[g].partial, (const bf16_t*)mem[g].B, (bf16_t*)mem[g].out, mem[g].d_out};
+    }
+    rg.G = G;
+    fg.nsplit = S;
+    fg.chunks = decode_finish_chunks(T, G);
+    auto go = [&](auto kern) {
+        kern<<<G * T * fg.chunks, kSmallThreads, 0, stream>>>((const bf16_t*)x, nullptr, 0, nullptr, nullptr, T, d_in, N,
+                                                              NP, k, inv_temperature, scale, nullptr, nullptr, nullptr, 0,
+                                                              nullptr, S, nullptr, rg, fg);
+        return hipGetLastError();
+    };
+    if (r == 8) return go(route_shrink_small_kernel<1, true>);
+    if (r == 16) return go(route_shrink_small_kernel<2, true>);
+    if (r == 32) return go(route_shrink_small_kernel<4, true>);
     return hipErrorInvalidValue;
 }
 
