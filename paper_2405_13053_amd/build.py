@@ -7,6 +7,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libmeteora.so")
+DIAG = os.path.join(HERE, "mfma_ceiling")   # measurement tool, see csrc/diag/mfma_ceiling.hip
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -19,17 +20,25 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every HIP source into one shared library; always recompiles."""
-    tmp = LIB + f".tmp{os.getpid()}"
-    cmd = ["hipcc", *HIPCC_FLAGS, "-o", tmp, *sources()]
+def _hipcc(cmd, verbose):
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every HIP source into one shared library, and the stand-alone measurement tool
+    (csrc/diag/mfma_ceiling.hip -> ./mfma_ceiling); always recompiles."""
+    tmp = LIB + f".tmp{os.getpid()}"
+    _hipcc(["hipcc", *HIPCC_FLAGS, "-o", tmp, *sources()], verbose)
     os.replace(tmp, LIB)
+    tmp = DIAG + f".tmp{os.getpid()}"
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    _hipcc(["hipcc", *flags, "-o", tmp, os.path.join(HERE, "csrc", "diag", "mfma_ceiling.hip")], verbose)
+    os.replace(tmp, DIAG)
     return LIB
 
 
