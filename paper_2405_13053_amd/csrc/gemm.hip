@@ -203,10 +203,16 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
                                                                                    a.out, a.accumulate);
     } else if (dma_ok && ((MI == 4 && NI == 4) || (MI == 2 && NI == 2))) {
         constexpr int M3 = MI == 4 ? 4 : 2;   // the instantiations of the three-deep-ring kernel that exist
-        const hipError_t e1 = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<M3, M3>),
-                                               gemm_w3_lds_bytes<M3, M3>());
+        // the epilogue form is a compile-time parameter of this kernel: plain store (the layer's GEMM) or accumulate
+        auto go = [&](auto kern) -> hipError_t {
+            const hipError_t e1 = ensure_lds_limit(reinterpret_cast<const void*>(kern), gemm_w3_lds_bytes<M3, M3>());
+            if (e1 != hipSuccess) return e1;
+            kern<<<a.tiles_m * a.tiles_n, 256, gemm_w3_lds_bytes<M3, M3>(), stream>>>(a);
+            return hipSuccess;
+        };
+        const hipError_t e1 = a.accumulate ? go(&gemm_mfma_w3_kernel<M3, M3, kEpiAccumulate>)
+                                           : go(&gemm_mfma_w3_kernel<M3, M3, kEpiStore>);
         if (e1 != hipSuccess) return e1;
-        gemm_mfma_w3_kernel<M3, M3><<<a.tiles_m * a.tiles_n, 256, gemm_w3_lds_bytes<M3, M3>(), stream>>>(a);
     } else if (dma_ok) {
         gemm_mfma_dma_kernel<MI, NI><<<a.tiles_m * a.tiles_n, 256, smem, stream>>>(a);
     } else {
@@ -242,7 +248,7 @@ int gemm_dense_splits(int T, int d_in, int rows) {
 template <int MI, int NI>
 static hipError_t launch_dense(GemmArgs a, hipStream_t stream) {   // three-deep W ring, fp32 split-K tiles
     constexpr int smem = gemm_w3_lds_bytes<MI, NI>();
-    auto kern = &gemm_mfma_w3_kernel<MI, NI>;
+    auto kern = &gemm_mfma_w3_kernel<MI, NI, kEpiPartial>;
     const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(kern), smem);
     if (ea != hipSuccess) return ea;
     a.tiles_m = ceil_div(a.T, MI * 64);
@@ -279,11 +285,11 @@ hipError_t launch_gemm_dense_splitk_multi(const void* x, const DenseOperand* ops
     a.nseg = n_ops;
     a.W = a.seg[0].W; a.d_out = a.seg[0].rows; a.partial = a.seg[0].partial;   // replaced per workgroup
     constexpr int smem = gemm_w3_lds_bytes<2, 2>();
-    const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 2>), smem);
+    const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 2, kEpiPartial>), smem);
     if (ea != hipSuccess) return ea;
     a.tiles_m = ceil_div(T, 128);
     a.tiles_n = tile0;
-    gemm_mfma_w3_kernel<2, 2><<<dim3(a.tiles_m * a.tiles_n, S), 256, smem, stream>>>(a);
+    gemm_mfma_w3_kernel<2, 2, kEpiPartial><<<dim3(a.tiles_m * a.tiles_n, S), 256, smem, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -359,12 +365,15 @@ hipError_t gemm_init_kernels() {
     hipError_t e = init_tile_kernels<4, 4>();
     if (e == hipSuccess) e = init_tile_kernels<2, 2>();
     if (e == hipSuccess) e = init_tile_kernels<1, 1>();
-    if (e == hipSuccess)
-        e = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<4, 4>), gemm_w3_lds_bytes<4, 4>());
-    if (e == hipSuccess)
-        e = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 2>), gemm_w3_lds_bytes<2, 2>());
-    if (e == hipSuccess)
-        e = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 5>), gemm_w3_lds_bytes<2, 5>());
+    auto lim = [&](auto kern, int bytes) {
+        if (e == hipSuccess) e = ensure_lds_limit(reinterpret_cast<const void*>(kern), bytes);
+    };
+    lim(&gemm_mfma_w3_kernel<4, 4, kEpiStore>, gemm_w3_lds_bytes<4, 4>());
+    lim(&gemm_mfma_w3_kernel<4, 4, kEpiAccumulate>, gemm_w3_lds_bytes<4, 4>());
+    lim(&gemm_mfma_w3_kernel<2, 2, kEpiStore>, gemm_w3_lds_bytes<2, 2>());
+    lim(&gemm_mfma_w3_kernel<2, 2, kEpiAccumulate>, gemm_w3_lds_bytes<2, 2>());
+    lim(&gemm_mfma_w3_kernel<2, 2, kEpiPartial>, gemm_w3_lds_bytes<2, 2>());
+    lim(&gemm_mfma_w3_kernel<2, 5, kEpiPartial>, gemm_w3_lds_bytes<2, 5>());
     return e;
 }
 

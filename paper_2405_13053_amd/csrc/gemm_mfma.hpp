@@ -346,15 +346,21 @@ __device__ __forceinline__ void tile_of_workgroup(int wg, int tiles_m, int tiles
 }
 
 // Epilogue shared by the pipelined kernels: store a workgroup's accumulators.
-template <int MI, int NI>
+// EPI fixes at compile time which of the three forms a kernel carries (kEpiAny: decided at run time).  With one form
+// the accumulators leave their registers block row by block row as they are converted; with all three behind
+// run-time branches the compiler first copies every accumulator out (and spills) before it branches.
+constexpr int kEpiAny = -1, kEpiStore = 0, kEpiAccumulate = 1, kEpiPartial = 2;
+template <int MI, int NI, int EPI = kEpiAny>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[MI][NI], unsigned char* smem_raw, int m0,
                                               int n0, int wm, int wn, int wave, int lane) {
     const int lrow = lane & 31, khalf = lane >> 5;
+    const bool is_partial = EPI == kEpiAny ? a.partial != nullptr : EPI == kEpiPartial;
+    const bool is_store = EPI == kEpiAny ? (a.partial == nullptr && !a.accumulate) : EPI == kEpiStore;
     // Epilogue.  A lane holds 4 consecutive columns per block row, so direct stores are 8-byte pieces
     // of 32 different rows per instruction; when the output is simply written (no split-K partials,
     // no accumulate) the bf16 tile is staged in this wavefront's own LDS region and stored as
     // 16-byte pieces that cover whole 128-byte lines.
-    if (a.partial == nullptr && !a.accumulate) {
+    if (is_store) {
         constexpr int EST = gemm_epilogue_stride<NI>();   // bytes per staged row
         __syncthreads();                                   // every wavefront is done with the operand tiles
         unsigned char* ep = smem_raw + wave * (MI * 32) * EST;
@@ -388,7 +394,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[M
         return;
     }
 
-    if (a.partial != nullptr) {
+    if (is_partial) {
         // fp32 split-K tile: same staging, one block row at a time, so the stores are 16-byte pieces of whole rows
         constexpr int PST = gemm_partial_stride<NI>();
         __syncthreads();
@@ -650,7 +656,7 @@ __device__ __forceinline__ void sgb_reads(std::integer_sequence<int, I...>) {
     ((METEORA_SGB(0x008, 1), METEORA_SGB(0x100, 1), sgb_mfma<MPR - 1>(), sgb_vmem<pieces_after_read(I, NPC, NR)>()), ...);
 }
 
-template <int MI, int NI>
+template <int MI, int NI, int EPI = kEpiAny>
 __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) {
     GemmArgs a = a_in;
     constexpr int BM = MI * 64, BN = NI * 64;
@@ -839,7 +845,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) 
     for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{}, Rt{});
     for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{}, Rt{});
 
-    gemm_epilogue<MI, NI>(a, acc, smem_raw, m0, n0, wm, wn, wave, lane);
+    gemm_epilogue<MI, NI, EPI>(a, acc, smem_raw, m0, n0, wm, wn, wave, lane);
 }
 
 }  // namespace meteora
