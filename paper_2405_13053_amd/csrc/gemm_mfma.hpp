@@ -282,6 +282,19 @@ __device__ __forceinline__ void mma_frags(f32x16 (&acc)[MI][NI], const Frags<MI,
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.w[ni], f.x[mi], acc[mi][ni], 0, 0, 0);
 }
 
+// The first k-step of a tile's contraction: the accumulators start from the MFMA's own zero C operand instead of
+// being cleared beforehand (256 register writes per lane in the 256 x 256 kernel, which would sit between the
+// arrival of the first tile and the first MFMA).
+template <int MI, int NI>
+__device__ __forceinline__ void mma_frags_first(f32x16 (&acc)[MI][NI], const Frags<MI, NI>& f) {
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.w[ni], f.x[mi], zero, 0, 0, 0);
+}
+
 // A [rows x 64-element-tiles] operand as the global->LDS loads see it.  An instruction moves 8 rows
 // (8 lanes x 16 B per 128-byte tile row); lane (rsub, p) fetches the chunk whose swizzled position
 // (see swz) is p, so the LDS image is the swizzled layout.  Wavefront `wave` moves rows (j*4 + wave)*8 .. +8 of the tile
@@ -756,8 +769,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) 
     // REQ: 0 = tile it+2 is a main tile, 1 = it is an extension tile, 2 = there is none (last two tiles)
     // PH: it % 6 when it is known at compile time (the unrolled main loop: every slot address is then a
     // constant and no address arithmetic sits between two tiles), -1 otherwise
-    auto tile_step = [&](int it, auto req, auto ph) {
+    // first: the tile's first k-step starts the accumulators (tile 0 of the unrolled form)
+    auto tile_step = [&](int it, auto req, auto ph, auto first) {
         constexpr int REQ = decltype(req)::value, PH = decltype(ph)::value;
+        constexpr bool FIRST = decltype(first)::value;
         using IsExt = std::integral_constant<bool, REQ == 1>;
         auto xsl = [&](int d) {   // x-slot / W-slot of tile it + d
             if constexpr (PH >= 0) return smem + ((PH + d) & 1) * kXElems;
@@ -774,7 +789,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) 
         // phases 1-3: MI*NI MFMAs of k-step ks-1, the fragment reads of k-step ks one per MFMA from the start of
         // the phase, and W pieces [P0, P0 + NPC) of tile it+2 spread between the reads (program order = the
         // order the LDS accesses keep)
-        auto phase = [&](Frags<MI, NI>& fnext, const Frags<MI, NI>& fcur, int ks, auto p0, auto npc) {
+        auto phase = [&](Frags<MI, NI>& fnext, const Frags<MI, NI>& fcur, int ks, auto p0, auto npc, auto start) {
             constexpr int P0 = decltype(p0)::value, NPC = REQ < 2 ? decltype(npc)::value : 0;
             int issued = 0;
 #pragma unroll
@@ -785,14 +800,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) 
                     for (int c = 0; c < pieces_after_read(i, NPC, NR); ++c) request_w(wreq, it + 2, P0 + issued++, IsExt{});
                 }
             }
-            mma_frags<MI, NI>(acc, fcur);
+            if constexpr (decltype(start)::value) mma_frags_first<MI, NI>(acc, fcur);
+            else mma_frags<MI, NI>(acc, fcur);
             sgb_reads<1, NPC, NR>(std::make_integer_sequence<int, NR>{});
             sgb_mfma<MI * NI - NR>();
             __builtin_amdgcn_sched_barrier(0);
         };
-        phase(f1, f0, 1, std::integral_constant<int, 0>{}, std::integral_constant<int, PW1>{});
-        phase(f0, f1, 2, std::integral_constant<int, PW1>{}, std::integral_constant<int, PW2>{});
-        phase(f1, f0, 3, std::integral_constant<int, PW1 + PW2>{}, std::integral_constant<int, PW3>{});
+        phase(f1, f0, 1, std::integral_constant<int, 0>{}, std::integral_constant<int, PW1>{}, std::bool_constant<FIRST>{});
+        phase(f0, f1, 2, std::integral_constant<int, PW1>{}, std::integral_constant<int, PW2>{}, std::false_type{});
+        phase(f1, f0, 3, std::integral_constant<int, PW1 + PW2>{}, std::integral_constant<int, PW3>{}, std::false_type{});
         // tile it+1 (x requested one tile ago, W before that) must have landed, and every wavefront's reads of
         // tile it must be complete; the W pieces of tile it+2 just issued may still be in flight
         // (a plain s_barrier: __syncthreads() carries a fence, for which the compiler waits for every load)
@@ -830,20 +846,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) 
     };
     using Req0 = std::integral_constant<int, 0>;
     using Rt = std::integral_constant<int, -1>;
+    using No = std::false_type;
     int it = 0;
     if constexpr (MI == 4 && NI == 4) {   // six tiles per trip: the period of the 2-slot and 3-slot rings
-        for (; it + 7 < nk_main; it += 6) {
-            tile_step(it, Req0{}, std::integral_constant<int, 0>{});
-            tile_step(it + 1, Req0{}, std::integral_constant<int, 1>{});
-            tile_step(it + 2, Req0{}, std::integral_constant<int, 2>{});
-            tile_step(it + 3, Req0{}, std::integral_constant<int, 3>{});
-            tile_step(it + 4, Req0{}, std::integral_constant<int, 4>{});
-            tile_step(it + 5, Req0{}, std::integral_constant<int, 5>{});
+        if (nk_main > 8) {
+            // tile 0 on its own: its first k-step starts the accumulators; the trips then begin at tile 1
+            tile_step(0, Req0{}, std::integral_constant<int, 0>{}, std::true_type{});
+            for (it = 1; it + 7 < nk_main; it += 6) {
+                tile_step(it, Req0{}, std::integral_constant<int, 1>{}, No{});
+                tile_step(it + 1, Req0{}, std::integral_constant<int, 2>{}, No{});
+                tile_step(it + 2, Req0{}, std::integral_constant<int, 3>{}, No{});
+                tile_step(it + 3, Req0{}, std::integral_constant<int, 4>{}, No{});
+                tile_step(it + 4, Req0{}, std::integral_constant<int, 5>{}, No{});
+                tile_step(it + 5, Req0{}, std::integral_constant<int, 0>{}, No{});
+            }
         }
     }
-    for (; it + 2 < nk_main; ++it) tile_step(it, Req0{}, Rt{});
-    for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{}, Rt{});
-    for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{}, Rt{});
+    for (; it + 2 < nk_main; ++it) tile_step(it, Req0{}, Rt{}, No{});
+    for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{}, Rt{}, No{});
+    for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{}, Rt{}, No{});
 
     gemm_epilogue<MI, NI, EPI>(a, acc, smem_raw, m0, n0, wm, wn, wave, lane);
 }
