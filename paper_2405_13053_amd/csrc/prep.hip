@@ -105,9 +105,26 @@ __device__ __forceinline__ void wcat_tile(const float* __restrict__ W_gate, cons
     __shared__ uint16_t t[64 * LD];   // t[i][row]
     const int tiles_i = d_in / 64;
     const int i0 = (tile % tiles_i) * 64, R0 = (tile / tiles_i) * 64;
+    // Rows of the A region come in groups of 8 (one adapter's columns q0..q0+7 when r % 8 == 0): A[a][i][q0..] is one
+    // 16-byte load, and consecutive threads take consecutive i, so a wavefront reads 1 KB of A contiguously.
+    // Everything else (the gate terms, ranks that are no multiple of 8, the zero rows) goes element by element,
+    // consecutive threads along the row index (contiguous in W_gate).
+    const bool vec = r % 8 == 0;
+    for (int item = tid; item < 8 * 64; item += 256) {
+        const int g = item >> 6, ii = item & 63;
+        const int Rg = R0 + g * 8;
+        if (vec && Rg >= 3 * NP && Rg + 8 <= 3 * NP + N * r) {
+            const int c = Rg - 3 * NP, a = c / r, q0 = c - a * r;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(A + ((size_t)a * d_in + i0 + ii) * r + q0);
+            uint32_t* dst = reinterpret_cast<uint32_t*>(&t[ii * LD + g * 8]);
+            dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
+        }
+    }
     for (int e = tid; e < 64 * 64; e += 256) {
         const int rr = e & 63, ii = e >> 6;
         const int R = R0 + rr, i = i0 + ii;
+        const int Rg = R0 + (rr & ~7);
+        if (vec && Rg >= 3 * NP && Rg + 8 <= 3 * NP + N * r) continue;   // written by the loop above
         uint16_t v = 0;
         if (R < 3 * NP) {
             const int term = R / NP, j = R - term * NP;
