@@ -21,7 +21,7 @@ hipError_t bucket_init_scratch();
 // stacked B -> its transpose Bt[d_out, N*r rounded up to 64] (zero-padded) for the GEMM's K-extension.
 // Any pair (W_gate, wsplit) / (A, apack) / (B, btrans) may be NULL to skip it; sizes are gate_wsplit_bytes,
 // shrink_apack_bytes and prep_btrans_bytes (0 = that operand is not packed for this dtype/rank: pass NULL).
-// wcat (optional, needs W_gate and A, d_in % 64 == 0): Wcat[prep_wcat_rows, d_in] bf16 for the dense routing path,
+// wcat (optional, needs W_gate and A, d_in % 64 == 0, r % 8 == 0): Wcat[prep_wcat_rows, d_in] bf16 for the dense routing path,
 // rows = hi | mid | lo terms of the gate columns (padded_adapters(N) rows each), then column q of A_a as row a*r+q.
 size_t prep_btrans_bytes(int d_out, int N, int r, bool bf16);
 int prep_wcat_rows(int N, int r);

@@ -105,39 +105,31 @@ __device__ __forceinline__ void wcat_tile(const float* __restrict__ W_gate, cons
     __shared__ uint16_t t[64 * LD];   // t[i][row]
     const int tiles_i = d_in / 64;
     const int i0 = (tile % tiles_i) * 64, R0 = (tile / tiles_i) * 64;
-    // Rows of the A region come in groups of 8 (one adapter's columns q0..q0+7 when r % 8 == 0): A[a][i][q0..] is one
-    // 16-byte load, and consecutive threads take consecutive i, so a wavefront reads 1 KB of A contiguously.
-    // Everything else (the gate terms, ranks that are no multiple of 8, the zero rows) goes element by element,
-    // consecutive threads along the row index (contiguous in W_gate).
-    const bool vec = r % 8 == 0;
+    // Rows come in groups of 8 that never straddle a region (NP, r and the region starts are multiples of 8): a group
+    // of gate rows is 8 consecutive columns j of one term; a group of A rows is columns q0..q0+7 of one adapter,
+    // one 16-byte load per i, consecutive threads along i so that a wavefront reads 1 KB of A contiguously.
+    // All index arithmetic is per group, i.e. uniform across the 64 threads that share it.
     for (int item = tid; item < 8 * 64; item += 256) {
         const int g = item >> 6, ii = item & 63;
-        const int Rg = R0 + g * 8;
-        if (vec && Rg >= 3 * NP && Rg + 8 <= 3 * NP + N * r) {
-            const int c = Rg - 3 * NP, a = c / r, q0 = c - a * r;
-            const u32x4 v = *reinterpret_cast<const u32x4*>(A + ((size_t)a * d_in + i0 + ii) * r + q0);
-            uint32_t* dst = reinterpret_cast<uint32_t*>(&t[ii * LD + g * 8]);
-            dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
-        }
-    }
-    for (int e = tid; e < 64 * 64; e += 256) {
-        const int rr = e & 63, ii = e >> 6;
-        const int R = R0 + rr, i = i0 + ii;
-        const int Rg = R0 + (rr & ~7);
-        if (vec && Rg >= 3 * NP && Rg + 8 <= 3 * NP + N * r) continue;   // written by the loop above
-        uint16_t v = 0;
-        if (R < 3 * NP) {
-            const int term = R / NP, j = R - term * NP;
-            if (j < N) {
-                uint16_t h, m, l;
-                split3(W_gate[(size_t)i * N + j], h, m, l);
-                v = term == 0 ? h : (term == 1 ? m : l);
+        const int Rg = R0 + g * 8, i = i0 + ii;
+        union { uint16_t h[8]; uint32_t w[4]; u32x4 v; } p;
+        p.v = u32x4{0u, 0u, 0u, 0u};
+        if (Rg < 3 * NP) {
+            const int term = Rg / NP, j0 = Rg - term * NP;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+                if (j0 + jj < N) {
+                    uint16_t h, m, l;
+                    split3(W_gate[(size_t)i * N + j0 + jj], h, m, l);
+                    p.h[jj] = term == 0 ? h : (term == 1 ? m : l);
+                }
             }
-        } else if (R < 3 * NP + N * r) {
-            const int c = R - 3 * NP, a = c / r, q = c - a * r;
-            v = A[((size_t)a * d_in + i) * r + q];
+        } else if (Rg < 3 * NP + N * r) {
+            const int c = Rg - 3 * NP, a = c / r, q0 = c - a * r;
+            p.v = *reinterpret_cast<const u32x4*>(A + ((size_t)a * d_in + i) * r + q0);
         }
-        t[ii * LD + rr] = v;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&t[ii * LD + g * 8]);
+        dst[0] = p.w[0]; dst[1] = p.w[1]; dst[2] = p.w[2]; dst[3] = p.w[3];
     }
     __syncthreads();
     const int rr = tid >> 2, iq = (tid & 3) * 16;
@@ -196,7 +188,7 @@ hipError_t launch_prep(const float* W_gate, void* wsplit, const void* A, void* a
     const int bblocks = (B && btrans) ? (ext_stride / 64) * ceil_div(d_out, 64) : 0;
     const int wblocks = ceil_div(wfrags, 4);
     const int cat_rows = prep_wcat_rows(N, r);
-    if (wcat && (!W_gate || !A || d_in % 64 != 0)) return hipErrorInvalidValue;
+    if (wcat && (!W_gate || !A || d_in % 64 != 0 || r % 8 != 0)) return hipErrorInvalidValue;
     const int cblocks = wcat ? ceil_div(cat_rows, 64) * (d_in / 64) : 0;
     const int64_t blocks = (int64_t)bblocks + cblocks + wblocks + ceil_div64(afrags, 4);
     if (blocks == 0) return hipSuccess;
