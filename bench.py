@@ -379,7 +379,7 @@ def summarize_pmc(fetch_dir, write_dir):
         kernels[k] = {"dispatches": max(len(f), len(w)), "FETCH_SIZE_raw": fa, "WRITE_SIZE_raw": wa,
                       "read_bytes": fa * fs * 1024, "written_bytes": wa * wsc * 1024,
                       "bytes": (fa * fs + wa * wsc) * 1024}
-    gemm = [k for k in kernels if "gemm_mfma_w3_kernel<4, 4>" in k or "gemm_mfma_w3_kernel<4,4>" in k]
+    gemm = [k for k in kernels if "gemm_mfma_w3_kernel<4, 4" in k or "gemm_mfma_w3_kernel<4,4" in k]
     try:
         head = subprocess.check_output(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], text=True).strip()
     except Exception:
