@@ -9,7 +9,7 @@ not modelled, every layer gets an input of its own shape), so the 14 GB of base 
 HBM once per step as in real decoding.  It reports the step eagerly enqueued (224 calls of
 meteora_linear_forward_packed) and replayed from ONE captured HIP graph, which removes the host-side
 launch cost when it dominates.  --group sends the layers of a block that share an input (q/k/v, gate/up)
-through meteora_linear_forward_group, which runs each group in three launches.  Prints one JSON line.
+through meteora_linear_forward_group, which runs each group in two launches.  Prints one JSON line.
 
     python bench_decode.py [--tokens 64] [--blocks 32] [--steps 20] [--warmup 3] [--group]
 """

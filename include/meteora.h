@@ -225,8 +225,8 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
  * meteora_linear_forward_packed call per member (same routing; outputs equal to bf16 accuracy, the
  * split-K sums may run in another order).  For decode-sized batches (T <= 64) and for batches of a few
  * hundred tokens whose members have few output tiles in all (at most 320 tiles of 128 x 128, routing
- * products included), with bf16, packed weights and at most 4 members, the whole group runs in three
- * launches instead of three per layer; otherwise the members run one after the other.
+ * products included), with bf16, packed weights and at most 4 members, the whole group runs in two
+ * (decode) or three launches instead of that many per layer; otherwise the members run one after the other.
  *   members  host array of G descriptors; every pointer in it is a device pointer with the meaning and
  *            alignment it has in meteora_linear_forward_packed (packed may be NULL: that member is then
  *            repacked into the workspace on every call, and the group runs member by member).

@@ -22,8 +22,8 @@ bool shape_ok(int T, int d_in, int d_out, int N, int r, int k) {
     return T >= 0 && d_in >= 1 && d_out >= 1 && N >= 1 && r >= 1 && k >= 1 && k <= N;
 }
 
-// Decode in three launches (gate logits inside the GEMM's launch, routing + shrink, reduce + expand): the split-K
-// shapes whose adapters also have the Wcat operand.
+// Decode in two launches (gate logits and every adapter's shrink inside the GEMM's launch, then routing + reduce +
+// expand): the split-K shapes whose adapters also have the Wcat operand.
 bool decode_fused_applies(int T, int d_in, int d_out, int N, int r, bool bf16) {
     return route_small_applies(T, r, bf16) && gemm_splitk_splits(T, d_in, d_out, bf16) > 0 &&
            route_dense_possible(d_in, N, r, bf16);
@@ -78,7 +78,7 @@ WsLayout ws_layout(int T, int d_in, int d_out, int N, int r, int k, bool bf16) {
     const int S_mid = dense_midsplit_splits(T, d_in, d_out, N, r, bf16);
     L.dpart = take(S_mid > 0 ? (size_t)S_mid * T * prep_wcat_rows(N, r) * sizeof(float)
                              : route_dense_part_bytes(T, d_in, N, r, bf16));
-    L.gpart = take(decode3 ? (size_t)gemm_splitk_splits(T, d_in, d_out, bf16) * T * 3 * NP * sizeof(float) : 0);
+    L.gpart = take(decode3 ? (size_t)gemm_splitk_splits(T, d_in, d_out, bf16) * T * prep_wcat_rows(N, r) * sizeof(float) : 0);
     L.spart = take((size_t)S_mid * T * d_out * sizeof(float));
     L.total = off;
     return L;
@@ -254,10 +254,9 @@ int meteora_workspace_regions(int T, int d_in, int d_out, int N, int r, int k, m
         if (dense || decode3) wr("wcat", prep_wcat_bytes(d_in, N, r, bf16));
     }
     if (decode3) {
-        const int S = gemm_group_splits(T, d_in, &d_out, 1, 3 * NP);
+        const int S = gemm_group_splits(T, d_in, &d_out, 1, CR);
         wr("splitk", (size_t)S * T * d_out * sizeof(float));
-        wr("gpart", (size_t)S * T * 3 * NP * sizeof(float));
-        wr("h32", pairs * r * sizeof(float));
+        wr("gpart", (size_t)S * T * CR * sizeof(float));
     } else if (dense) {
         if (const int S = dense_midsplit_splits(T, d_in, d_out, N, r, bf16)) {
             wr("spart", (size_t)S * T * d_out * sizeof(float));
@@ -524,15 +523,15 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
         // shrink of the selected adapters token by token; then the split-K reduction, which adds the expand
         const DecodeMember mem{W, pk.wcat, gate_bias, A, B, d_out, at<float>(ws, L.splitk), at<float>(ws, L.gpart),
                                at<float>(ws, L.h32), idx, w, out};
-        const int gate_rows = 3 * padded_adapters(N);
+        const int gate_rows = prep_wcat_rows(N, r);   // the gate terms and every adapter's shrink columns
         const int S = gemm_group_splits(T, d_in, &d_out, 1, gate_rows);
         {
             StageScope sc(ST_GEMM, st, tslot);
             METEORA_HIP(launch_gemm_decode_main(x, &mem, 1, gate_rows, S, T, d_in, st));
         }
-        // top-k, softmax, the shrink of the selected adapters, then the split-K reduction with the expand: one launch
+        // top-k, softmax, then the split-K reduction with the expand from the selected adapters' shrink tiles: one launch
         StageScope sc(ST_SHRINK, st, tslot);
-        METEORA_HIP(launch_route_shrink_finish_group(x, &mem, 1, S, T, d_in, N, r, k, inv_temperature, scale, st));
+        METEORA_HIP(launch_decode_tail_group(&mem, 1, S, T, N, r, k, gate_rows, inv_temperature, scale, st));
         return METEORA_OK;
     }
     if (dense) {
@@ -600,7 +599,7 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
 // ---- a group of layers that share x ----------------------------------------------------------------------------
 namespace {
 
-// Fused form: decode-sized batch, every member on the three-launch path with packed weights.
+// Fused form: decode-sized batch, every member on the two-launch path with packed weights.
 bool group_fused(const meteora_group_member* m, int G, int T, int d_in, int N, int r, bool bf16) {
     if (G < 2 || G > kMaxDecodeGroup) return false;
     for (int g = 0; g < G; ++g)
@@ -663,7 +662,7 @@ extern "C" size_t meteora_group_workspace_bytes(const int* d_out, int G, int T, 
         fused = fused && decode_fused_applies(T, d_in, d_out[g], N, r, bf16);
     }
     if (fused) {
-        const int gate_rows = 3 * padded_adapters(N);
+        const int gate_rows = prep_wcat_rows(N, r);
         const size_t f = group_layout(d_out, G, T, d_in, N, r, k, gemm_group_splits(T, d_in, d_out, G, gate_rows),
                                       gate_rows).total + 256;
         need = f > need ? f : need;
@@ -744,7 +743,7 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
         }
         return METEORA_OK;
     }
-    const int gate_rows = 3 * padded_adapters(N);
+    const int gate_rows = prep_wcat_rows(N, r);
     const GroupLayout L = group_layout(d_outs, G, T, d_in, N, r, k, gemm_group_splits(T, d_in, d_outs, G, gate_rows),
                                        gate_rows);
     DecodeMember mem[kMaxDecodeGroup];
@@ -762,7 +761,7 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
         METEORA_HIP(launch_gemm_decode_main(x, mem, G, gate_rows, L.S, T, d_in, st));
     }
     StageScope sc(ST_SHRINK, st, tslot);
-    METEORA_HIP(launch_route_shrink_finish_group(x, mem, G, L.S, T, d_in, N, r, k, inv_temperature, scale, st));
+    METEORA_HIP(launch_decode_tail_group(mem, G, L.S, T, N, r, k, gate_rows, inv_temperature, scale, st));
     return METEORA_OK;
 }
 

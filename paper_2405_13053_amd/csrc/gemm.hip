@@ -293,10 +293,10 @@ hipError_t launch_gemm_dense_splitk_multi(const void* x, const DenseOperand* ops
     return hipGetLastError();
 }
 
-// Decode in three launches: (1) the main K splits of x * W^T with the gate-term rows of Wcat as extra column
-// tiles (fp32 tiles into `partial` and `gpartial`), (2) routing and shrink on the gate tiles (route_small.hip),
-// (3) reduce + expand.  A group of G layers that share x runs through the same three launches: the column tiles
-// of all their W and gate terms form one grid, all with the same number S of K splits.
+// Decode in two launches: (1) the main K splits of x * W^T with the rows of Wcat as extra column
+// tiles (fp32 tiles into `partial` and `gpartial`), (2) routing on the gate tiles, then the reduction with the
+// expand from the shrink tiles (route_small.hip).  A group of G layers that share x runs through the same two
+// launches: the column tiles of all their W and Wcat form one grid, all with the same number S of K splits.
 int gemm_group_splits(int T, int d_in, const int* d_out, int G, int gate_rows) {
     if (T < 1 || T > 64 || d_in % kGemmBK != 0) return 0;
     const int nk = d_in / kGemmBK;

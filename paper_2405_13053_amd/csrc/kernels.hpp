@@ -44,15 +44,12 @@ hipError_t launch_gate_topk(const float* partials, int KS, const float* bias, in
 // ---- small batches (T <= 64, bf16, r in {8, 16, 32}): top-k + softmax and the shrink of the selected
 // adapters in one launch, one workgroup per token; consumes launch_gate_logits' partials and writes
 // topk_idx, topk_w and every column of the token's row of hdense.  Replaces launch_gate_topk,
-// launch_bucket and launch_shrink for the whole-layer call.
-// gpart (optional): take the logits from launch_gemm_decode_main's gate tiles gpart[GS][T][3 * padded_adapters(N)]
-// instead of `partials`; hs (optional): write hs[T,k,r] = scale * w * h in fp32 instead of the rows of hdense.
+// launch_bucket and launch_shrink for the whole-layer call (shapes the two-launch decode form below does not take).
 bool route_small_applies(int T, int r, bool bf16);
 hipError_t launch_route_shrink_small(const void* x, const float* partials, int KS, const float* bias, const void* A,
                                      int T, int d_in, int N, int r, int k, float inv_temperature, float scale,
                                      int32_t* topk_idx, float* topk_w, void* hdense, int ext_stride,
-                                     hipStream_t stream, const float* gpart = nullptr, int GS = 0,
-                                     float* hs = nullptr);
+                                     hipStream_t stream);
 
 // ---- mid-sized batches (64 < T <= kRouteDenseMaxTokens, bf16, r % 8 == 0, d_in % 64 == 0): one MFMA launch
 // computes the split-bf16 gate logits and x * A_i of every adapter as fp32 K-split partials
@@ -117,17 +114,19 @@ hipError_t launch_expand(const float* h32, const void* B, const int32_t* topk_id
                          int T, int d_out, int N, int r, int k, float scale, bool bf16, void* out,
                          int accumulate, hipStream_t stream);
 
-// ---- decode-sized batches in three launches (T <= 64, bf16, r % 8 == 0, Wcat packed), for one layer or for a
+// ---- decode-sized batches in two launches (T <= 64, bf16, r in {8, 16, 32}, Wcat packed), for one layer or for a
 // group of up to kMaxDecodeGroup layers that share x (q/k/v, gate/up):
 // launch_gemm_decode_main: the main K splits of x * W_g^T as fp32 tiles partial_g[S][T][d_out_g], and in the same
-//   launch the gate-term rows of each Wcat_g (its first gate_rows = 3 * padded_adapters(N) rows) as
+//   launch x * Wcat_g^T (gate_rows = prep_wcat_rows(N, r): the gate terms and every adapter's shrink columns) as
 //   gpartial_g[S][T][gate_rows]; S = gemm_group_splits(...) for every member;
-// launch_route_shrink_small_group (route_small.hip): top-k, softmax, shrink -> idx_g, w_g, hs_g[T,k,r] = scale*w*h;
-// launch_gemm_decode_finish: out_g = bf16(sum of the S tiles in order + sum_slot hs_g * B_g[idx_g]).
+// launch_decode_tail_group (route_small.hip): top-k, softmax -> idx_g, w_g, and
+//   out_g = bf16(sum of the S tiles in order + sum_slot (scale * w * h from the shrink tiles) * B_g[idx_g]).
+// launch_gemm_decode_finish: the reduction with the expand alone, from hs_g[T,k,r] = scale * w * h (the few-tile
+//   form of mid-sized batches below).
 constexpr int kMaxDecodeGroup = 4;
 struct DecodeMember {
     const void* W;        // [d_out, d_in]
-    const void* wg3;      // gate-term rows of Wcat
+    const void* wg3;      // Wcat
     const float* bias;    // gate bias or NULL
     const void* A;        // [N, d_in, r]
     const void* B;        // [N, r, d_out]
@@ -143,14 +142,9 @@ int gemm_splitk_splits(int T, int d_in, int d_out, bool bf16);
 int gemm_group_splits(int T, int d_in, const int* d_out, int G, int gate_rows);   // 0: the shapes are not split
 hipError_t launch_gemm_decode_main(const void* x, const DecodeMember* mem, int G, int gate_rows, int S, int T,
                                    int d_in, hipStream_t stream);
-hipError_t launch_route_shrink_small_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
-                                           int r, int k, float inv_temperature, float scale, hipStream_t stream);
 hipError_t launch_gemm_decode_finish(const DecodeMember* mem, int G, int S, int T, int k, int r, hipStream_t stream);
-// launch_route_shrink_small_group and launch_gemm_decode_finish in ONE launch: every token's row is cut into
-// stretches, one workgroup each, which repeat the token's routing and shrink and then reduce and expand their
-// stretch (same bits as the two launches; mem[g].hs is not written)
-hipError_t launch_route_shrink_finish_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
-                                            int r, int k, float inv_temperature, float scale, hipStream_t stream);
+hipError_t launch_decode_tail_group(const DecodeMember* mem, int G, int S, int T, int N, int r, int k, int gate_rows,
+                                    float inv_temperature, float scale, hipStream_t stream);
 // The same three launches for batches of a few hundred tokens with few output tiles: launch_gemm_dense_splitk_multi over
 // every W_g and Wcat_g (gpartial_g then holds [S][T][prep_wcat_rows]), this selection for all members, the finish above.
 hipError_t launch_route_dense_select_group(const DecodeMember* mem, int G, int S, int T, int N, int r, int k,

@@ -8,128 +8,34 @@
 #include "common.hpp"
 #include "kernels.hpp"
 #include "topk_key.hpp"
+#include "dense_logits.hpp"
 
 namespace meteora {
 
 constexpr int kSmallThreads = 1024;   // 16 wavefronts per token: the shrink is latency-bound, so many short loops
 constexpr int kSmallWaves = kSmallThreads / 64;
 
-// A group of layers that share x (same T, d_in, N, r, k): workgroup b serves token b % T of member b / T.
-struct RouteGroup {
-    struct Member {
-        const float* gpart;
-        const float* bias;
-        const bf16_t* A;
-        int32_t* idx;
-        float* w;
-        float* hs;
-    } m[kMaxDecodeGroup];
-    int G;   // 0: the kernel's own pointer arguments describe the one layer
-};
-
-// The rest of a decode-sized layer call in the same launch (FINISH): once a token's shrink values are known its
-// workgroup also adds the K-split tiles of the base projection for a stretch of the token's output row, in split
-// order, adds the expand of Eq. 2 from the shrink values it holds in LDS, and rounds once:
-//   out[t, c] = bf16( sum_s partial[s][t][c] + sum_slot sum_q (scale * w * h)[slot][q] * B[a_slot][q][c] ).
-// A token's row is cut into `chunks` stretches, one workgroup each (blockIdx = (member * T + token) * chunks +
-// chunk), so that the launch fills the chip; the workgroups of a token repeat its routing and shrink (a few hundred
-// KB from L2 each) instead of waiting for one another.  Arithmetic and order are those of
-// gemm_splitk_reduce_expand_kernel.
-struct FinishGroup {
-    struct Member {
-        const float* partial;   // [S][T][d_out]
-        const bf16_t* B;        // [N, r, d_out]
-        bf16_t* out;            // [T, d_out]
-        int d_out;
-    } m[kMaxDecodeGroup];
-    int nsplit, chunks;         // chunks == 0: no finish stage
-};
-
-template <int R8, bool FINISH = false>   // R8 = r / 8: 16-byte pieces per row of A_a
+template <int R8>   // R8 = r / 8: 16-byte pieces per row of A_a
 __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
-    const bf16_t* __restrict__ x, const float* __restrict__ partials, int KS, const float* bias_in,
-    const bf16_t* A_in, int T, int d_in, int N, int NP, int k, float inv_temperature, float scale,
-    int32_t* idx_in, float* w_in, bf16_t* __restrict__ hdense, int ext_stride,
-    const float* gpart_in, int GS, float* hs_in, const RouteGroup rg, const FinishGroup fg) {
+    const bf16_t* __restrict__ x, const float* __restrict__ partials, int KS, const float* __restrict__ bias,
+    const bf16_t* __restrict__ A, int T, int d_in, int N, int NP, int k, float inv_temperature, float scale,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, bf16_t* __restrict__ hdense, int ext_stride) {
     constexpr int r = R8 * 8;
     constexpr int ROWS = 8 / R8;   // rows of A_a per slot whose loads are in flight together
     __shared__ int sel_idx[kMaxTopK];
     __shared__ float sel_w[kMaxTopK];
     __shared__ float red[kSmallWaves][kMaxTopK][r];
-    __shared__ float gsum[2][kSmallWaves][kMaxAdapters];   // per-split logit terms, double-buffered over rounds
-    float glog = 0.f;
-    int t = blockIdx.x, member = 0, chunk = 0;
-    if constexpr (FINISH) {
-        chunk = blockIdx.x % fg.chunks;
-        t = blockIdx.x / fg.chunks;
-    }
-    const float* __restrict__ bias = bias_in;
-    const bf16_t* __restrict__ A = A_in;
-    int32_t* __restrict__ topk_idx = idx_in;
-    float* __restrict__ topk_w = w_in;
-    const float* __restrict__ gpart = gpart_in;
-    float* __restrict__ hs = hs_in;
-    if (rg.G > 0) {   // uniform
-        const int g = t / T;
-        t = t - g * T;
-        member = g;
-        bias = rg.m[g].bias; A = rg.m[g].A; topk_idx = rg.m[g].idx; topk_w = rg.m[g].w;
-        gpart = rg.m[g].gpart; hs = rg.m[g].hs;
-    }
+    const int t = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-
-    // FINISH: the K-split tiles of this thread's first 8 output columns do not depend on the routing: their loads
-    // (the first 8 splits) go out now and are added, in split order, once the top-k is done, so that their latency
-    // hides behind the logit fetch and the ranking
-    f32x4 pre0[8], pre1[8];
-    f32x4 pre_lo = {0.f, 0.f, 0.f, 0.f}, pre_hi = {0.f, 0.f, 0.f, 0.f};
-    int fin_first = 0, fin_end = 0;
-    if constexpr (FINISH) {
-        const int c8 = fg.m[member].d_out / 8, per = (c8 + fg.chunks - 1) / fg.chunks;
-        fin_first = chunk * per + threadIdx.x;
-        fin_end = min(c8, (chunk + 1) * per);
-        if (fin_first < fin_end) {
-            const float* base = fg.m[member].partial + (size_t)t * fg.m[member].d_out + fin_first * 8;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const float* src = base + (size_t)min(u, fg.nsplit - 1) * T * fg.m[member].d_out;
-                pre0[u] = *reinterpret_cast<const f32x4*>(src);
-                pre1[u] = *reinterpret_cast<const f32x4*>(src + 4);
-            }
-        }
-    }
 
     // this token's row of the dense expand operand starts as zeros
     if (hdense != nullptr) {
         u32x4* row = reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride);
         for (int i = threadIdx.x; i < ext_stride / 8; i += kSmallThreads) row[i] = u32x4{0u, 0u, 0u, 0u};
     }
-    // Logits from the split-K tiles of the gate-term rows: wavefront w fetches split w, w + 16, ... (every wavefront
-    // has its loads out at once), (lo + mid) + hi within a split; wavefront 0 then adds the splits in order.
-    if (gpart != nullptr) {
-        const int GR = 3 * NP;
-        for (int s0 = 0; s0 < GS; s0 += kSmallWaves) {
-            const int sp = s0 + wave;
-            float v = 0.f;
-            if (sp < GS && lane < N) {
-                const float* src = gpart + ((size_t)sp * T + t) * GR + lane;
-                const float hi = src[0], mid = src[NP], lo = src[2 * NP];
-                v = (lo + mid) + hi;
-            }
-            if (lane < kMaxAdapters) gsum[s0 / kSmallWaves & 1][wave][lane] = v;
-            __syncthreads();
-            if (wave == 0) {
-                const int n = min(kSmallWaves, GS - s0);
-                for (int u = 0; u < n; ++u) glog += gsum[s0 / kSmallWaves & 1][u][lane];
-            }
-        }
-    }
     if (wave == 0) {   // top-k and softmax: lane = adapter
         float g = 0.f;
-        if (lane < N && gpart != nullptr) {
-            g = glog + (bias != nullptr ? bias[lane] : 0.f);
-            if (g == 0.f) g = 0.f;
-        } else if (lane < N) {
+        if (lane < N) {
             for (int s0 = 0; s0 < KS; s0 += 16) {   // K-slices in order, 16 loads in flight
                 float v[16];
 #pragma unroll
@@ -147,20 +53,11 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
         if (lane < k) {
             sel_idx[lane] = my_i[0];
             sel_w[lane] = my_w[0];
-            if (chunk == 0) {   // the workgroups of a token compute the same routing: one of them reports it
-                topk_idx[(size_t)t * k + lane] = my_i[0];
-                topk_w[(size_t)t * k + lane] = my_w[0];
-            }
+            topk_idx[(size_t)t * k + lane] = my_i[0];
+            topk_w[(size_t)t * k + lane] = my_w[0];
         }
     }
     __syncthreads();
-    if constexpr (FINISH) {
-        if (fin_first < fin_end) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (u < fg.nsplit) { pre_lo += pre0[u]; pre_hi += pre1[u]; }
-        }
-    }
 
     // shrink: thread `tid` takes rows tid, tid + 1024, ... of A_a (r bf16 = R8 16-byte pieces each); two slots
     // at a time so that both adapters' loads are in flight together
@@ -238,72 +135,193 @@ __global__ __launch_bounds__(kSmallThreads) void route_shrink_small_kernel(
         }
     }
     __syncthreads();
-    __shared__ float hsl[kMaxTopK * r];   // scale * w * h of this token (FINISH)
     for (int e = threadIdx.x; e < k * r; e += kSmallThreads) {
         const int slot = e / r, q = e - slot * r;
         float h = 0.f;
 #pragma unroll
         for (int wv = 0; wv < kSmallWaves; ++wv) h += red[wv][slot][q];   // fixed order
-        const float v = scale * sel_w[slot] * h;
-        if constexpr (FINISH) {
-            hsl[e] = v;
-            if (hs != nullptr && chunk == 0) hs[((size_t)t * k + slot) * r + q] = v;
-        } else {
-            if (hs != nullptr) hs[((size_t)t * k + slot) * r + q] = v;
-            else hdense[(size_t)t * ext_stride + sel_idx[slot] * r + q] = from_float<bf16_t>(v);
+        hdense[(size_t)t * ext_stride + sel_idx[slot] * r + q] = from_float<bf16_t>(scale * sel_w[slot] * h);
+    }
+}
+
+// A group of layers that share x (same T, N, r, k, number of K splits): the operands of the decode tail per member.
+struct RouteGroup {
+    struct Member {
+        const float* gpart;   // [S][T][rows of Wcat]
+        const float* bias;
+        int32_t* idx;
+        float* w;
+    } m[kMaxDecodeGroup];
+};
+struct FinishGroup {
+    struct Member {
+        const float* partial;   // [S][T][d_out]
+        const bf16_t* B;        // [N, r, d_out]
+        bf16_t* out;            // [T, d_out]
+        int d_out;
+    } m[kMaxDecodeGroup];
+    int nsplit, chunks;         // K splits; stretches of kTailThreads * 8 columns per row of the widest member
+};
+
+// ------------------------------------------------------------------------------------------------------------
+// Decode tail: everything of a decode-sized layer call after the one launch that streams W.  That launch computes,
+// as fp32 K-split tiles, x * W^T and x * Wcat^T, the latter being the gate terms (Sec. 3.1) AND the shrink x * A_i
+// of EVERY adapter (N * r columns: 4% more rows to stream than W alone at N = 28, r = 8, 5120 -> 5120).  What is
+// left per token is a chain of two memory round trips, taken here by independent wavefronts with no LDS and no
+// barrier: (1) the gate tiles -> logits, top-k, softmax (Eq. 3); (2) the selected adapters' shrink tiles and rows
+// of B -> out = bf16( sum of the projection's split tiles + sum_slot sum_q (scale * w * h) * B ), Eq. 2 with one
+// rounding.  A wavefront owns 64 x 8 consecutive output columns of one token and repeats the token's routing
+// (a few hundred bytes) instead of waiting for another wavefront.  The routing is the routine every path shares.
+// ------------------------------------------------------------------------------------------------------------
+
+// one wavefront per workgroup (measured: 64, 128 and 256 threads per workgroup time the same)
+constexpr int kTailThreads = 64;
+
+template <int R8>   // r = 8 * R8
+__global__ __launch_bounds__(kTailThreads) void decode_tail_kernel(int T, int N, int CR, int k, float inv_temperature,
+                                                                   float scale, const RouteGroup rg,
+                                                                   const FinishGroup fg) {
+    constexpr int r = R8 * 8, NP = 32;
+    constexpr int SLOTS = 64 / r;   // slots whose shrink values a wavefront holds at a time, one value per lane
+    const int lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x % fg.chunks;
+    int t = blockIdx.x / fg.chunks;
+    const int member = t / T;
+    t -= member * T;
+    const int d_out = fg.m[member].d_out, c8 = d_out / 8, nsplit = fg.nsplit;
+    if (chunk * kTailThreads >= c8) return;   // a narrower member of the group: nothing in this stretch
+    const int gi = chunk * kTailThreads + threadIdx.x;
+    const bool active = gi < c8;              // lanes past the row's end work on its last columns and do not store
+    const int c = (active ? gi : c8 - 1) * 8;
+    const float* __restrict__ gpart = rg.m[member].gpart;
+    const bf16_t* __restrict__ B = fg.m[member].B;
+    const float* partial = fg.m[member].partial + (size_t)t * d_out + c;
+    const size_t pstride = (size_t)T * d_out;
+
+    // the projection's split tiles do not depend on the routing: the first 8 go out first
+    f32x4 pre0[8], pre1[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const float* src = partial + (size_t)min(u, nsplit - 1) * pstride;
+        pre0[u] = *reinterpret_cast<const f32x4*>(src);
+        pre1[u] = *reinterpret_cast<const f32x4*>(src + 4);
+    }
+    float g[1];
+    const int lt[1] = {0};
+    dense_logits<NP, 1, 8>(gpart, nsplit, CR, rg.m[member].bias, T, N, t, lt, lane & (NP - 1), g);
+    int sel_i[1];
+    float sel_w[1];
+    wave_topk_softmax<NP, 1>(g, lane, N, k, inv_temperature, sel_i, sel_w);   // lane s < k: the s-th choice
+    if (chunk == 0 && threadIdx.x < k) {   // the wavefronts of a token compute the same routing: one reports it
+        rg.m[member].idx[(size_t)t * k + lane] = sel_i[0];
+        rg.m[member].w[(size_t)t * k + lane] = sel_w[0];
+    }
+    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        if (u < nsplit) { lo += pre0[u]; hi += pre1[u]; }
+    for (int s0 = 8; s0 < nsplit; s0 += 8) {   // tiles in order, 8 tiles' loads in flight
+        f32x4 v0[8], v1[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float* src = partial + (size_t)min(s0 + u, nsplit - 1) * pstride;
+            v0[u] = *reinterpret_cast<const f32x4*>(src);
+            v1[u] = *reinterpret_cast<const f32x4*>(src + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < nsplit) { lo += v0[u]; hi += v1[u]; }
+    }
+
+    auto load_rows = [&](int slot, int q0, u32x4 (&b)[8]) {   // 8 rows of B of the slot's adapter, this lane's columns
+        const int a = __builtin_amdgcn_readlane(sel_i[0], slot);
+        const bf16_t* Ba = B + ((size_t)a * r + q0) * d_out + c;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) b[u] = *reinterpret_cast<const u32x4*>(Ba + (size_t)u * d_out);
+    };
+    for (int s0 = 0; s0 < k; s0 += SLOTS) {
+        const int ns = min(SLOTS, k - s0);
+        // lane e holds scale * w * h of slot s0 + e / r, component e % r: the shrink tiles of that adapter's columns
+        // of Wcat, added in split order
+        const int my_slot = min(s0 + lane / r, k - 1);
+        const int a_e = __shfl(sel_i[0], my_slot);
+        const float w_e = __shfl(sel_w[0], my_slot);
+        const float* hsrc = gpart + (size_t)t * CR + 3 * NP + a_e * r + (lane & (r - 1));
+        float hv8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) hv8[u] = hsrc[(size_t)min(u, nsplit - 1) * T * CR];
+        u32x4 bcur[8];
+        load_rows(s0, 0, bcur);   // the first rows of B are under way while the shrink tiles arrive
+        float h = 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (u < nsplit) h += hv8[u];
+        for (int p0 = 8; p0 < nsplit; p0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = hsrc[(size_t)min(p0 + u, nsplit - 1) * T * CR];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (p0 + u < nsplit) h += v[u];
+        }
+        const float hv = scale * w_e * h;
+        const int ngroups = ns * R8;
+        for (int j = 0; j < ngroups; ++j) {   // (slot, 8 rows) pieces; the next piece's loads go out before this one's FMAs
+            u32x4 bnext[8];
+            const bool more = j + 1 < ngroups;
+            if (more) load_rows(s0 + (j + 1) / R8, ((j + 1) % R8) * 8, bnext);
+            const int e0 = (j / R8) * r + (j % R8) * 8;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float hq = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(hv), e0 + u));
+                lo[0] = fmaf(hq, bf16_bits_to_float(bcur[u][0] & 0xffffu), lo[0]);
+                lo[1] = fmaf(hq, bf16_bits_to_float(bcur[u][0] >> 16), lo[1]);
+                lo[2] = fmaf(hq, bf16_bits_to_float(bcur[u][1] & 0xffffu), lo[2]);
+                lo[3] = fmaf(hq, bf16_bits_to_float(bcur[u][1] >> 16), lo[3]);
+                hi[0] = fmaf(hq, bf16_bits_to_float(bcur[u][2] & 0xffffu), hi[0]);
+                hi[1] = fmaf(hq, bf16_bits_to_float(bcur[u][2] >> 16), hi[1]);
+                hi[2] = fmaf(hq, bf16_bits_to_float(bcur[u][3] & 0xffffu), hi[2]);
+                hi[3] = fmaf(hq, bf16_bits_to_float(bcur[u][3] >> 16), hi[3]);
+            }
+            if (more) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) bcur[u] = bnext[u];
+            }
         }
     }
-    if constexpr (FINISH) {
-        __syncthreads();
-        const float* __restrict__ partial = fg.m[member].partial;
-        const bf16_t* __restrict__ B = fg.m[member].B;
-        bf16_t* __restrict__ out = fg.m[member].out;
-        const int d_out = fg.m[member].d_out, nsplit = fg.nsplit;
-        for (int gi = fin_first; gi < fin_end; gi += kSmallThreads) {   // 8 consecutive columns
-            const int c = gi * 8;
-            // the first stretch of this thread starts from the sums of the splits fetched at the top
-            const bool first = gi == fin_first;
-            f32x4 lo = first ? pre_lo : f32x4{0.f, 0.f, 0.f, 0.f}, hi = first ? pre_hi : f32x4{0.f, 0.f, 0.f, 0.f};
-            for (int s0 = first ? 8 : 0; s0 < nsplit; s0 += 8) {   // tiles in order, 8 tiles' loads in flight
-                f32x4 v0[8], v1[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const float* src = partial + ((size_t)min(s0 + u, nsplit - 1) * T + t) * d_out + c;
-                    v0[u] = *reinterpret_cast<const f32x4*>(src);
-                    v1[u] = *reinterpret_cast<const f32x4*>(src + 4);
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (s0 + u < nsplit) { lo += v0[u]; hi += v1[u]; }
-            }
-            for (int slot = 0; slot < k; ++slot) {
-                const bf16_t* Ba = B + (size_t)sel_idx[slot] * r * d_out + c;
-                const float* h = hsl + slot * r;
-#pragma unroll
-                for (int q0 = 0; q0 < r; q0 += 8) {   // 8 rows of B in flight
-                    u32x4 b[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) b[u] = *reinterpret_cast<const u32x4*>(Ba + (size_t)(q0 + u) * d_out);
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const float hv = h[q0 + u];
-                        lo[0] = fmaf(hv, bf16_bits_to_float(b[u][0] & 0xffffu), lo[0]);
-                        lo[1] = fmaf(hv, bf16_bits_to_float(b[u][0] >> 16), lo[1]);
-                        lo[2] = fmaf(hv, bf16_bits_to_float(b[u][1] & 0xffffu), lo[2]);
-                        lo[3] = fmaf(hv, bf16_bits_to_float(b[u][1] >> 16), lo[3]);
-                        hi[0] = fmaf(hv, bf16_bits_to_float(b[u][2] & 0xffffu), hi[0]);
-                        hi[1] = fmaf(hv, bf16_bits_to_float(b[u][2] >> 16), hi[1]);
-                        hi[2] = fmaf(hv, bf16_bits_to_float(b[u][3] & 0xffffu), hi[2]);
-                        hi[3] = fmaf(hv, bf16_bits_to_float(b[u][3] >> 16), hi[3]);
-                    }
-                }
-            }
-            u32x4 pk;
-            pk[0] = pack_bf16x2(lo[0], lo[1]); pk[1] = pack_bf16x2(lo[2], lo[3]);
-            pk[2] = pack_bf16x2(hi[0], hi[1]); pk[3] = pack_bf16x2(hi[2], hi[3]);
-            *reinterpret_cast<u32x4*>(out + (size_t)t * d_out + c) = pk;
-        }
+    if (active) {
+        u32x4 pk;
+        pk[0] = pack_bf16x2(lo[0], lo[1]); pk[1] = pack_bf16x2(lo[2], lo[3]);
+        pk[2] = pack_bf16x2(hi[0], hi[1]); pk[3] = pack_bf16x2(hi[2], hi[3]);
+        *reinterpret_cast<u32x4*>(fg.m[member].out + (size_t)t * d_out + c) = pk;
     }
+}
+
+// gate_rows = every row of Wcat: the split tiles mem[g].gpartial hold the gate terms and all adapters' shrink.
+hipError_t launch_decode_tail_group(const DecodeMember* mem, int G, int S, int T, int N, int r, int k, int gate_rows,
+                                    float inv_temperature, float scale, hipStream_t stream) {
+    if (G < 1 || G > kMaxDecodeGroup || S < 1 || padded_adapters(N) != 32 || gate_rows != prep_wcat_rows(N, r))
+        return hipErrorInvalidValue;
+    RouteGroup rg{};
+    FinishGroup fg{};
+    int widest = 0;
+    for (int g = 0; g < G; ++g) {
+        if (mem[g].d_out % 8 != 0 || mem[g].d_out < 8) return hipErrorInvalidValue;
+        rg.m[g] = {mem[g].gpartial, mem[g].bias, mem[g].idx, mem[g].w};
+        fg.m[g] = {mem[g].partial, (const bf16_t*)mem[g].B, (bf16_t*)mem[g].out, mem[g].d_out};
+        widest = mem[g].d_out > widest ? mem[g].d_out : widest;
+    }
+    fg.nsplit = S;
+    fg.chunks = ceil_div(widest / 8, kTailThreads);
+    const unsigned grid = (unsigned)G * T * fg.chunks;
+    auto go = [&](auto kern) {
+        kern<<<grid, kTailThreads, 0, stream>>>(T, N, gate_rows, k, inv_temperature, scale, rg, fg);
+        return hipGetLastError();
+    };
+    if (r == 8) return go(decode_tail_kernel<1>);
+    if (r == 16) return go(decode_tail_kernel<2>);
+    if (r == 32) return go(decode_tail_kernel<4>);
+    return hipErrorInvalidValue;
 }
 
 bool route_small_applies(int T, int r, bool bf16) { return bf16 && T <= 64 && (r == 8 || r == 16 || r == 32); }
@@ -311,71 +329,16 @@ bool route_small_applies(int T, int r, bool bf16) { return bf16 && T <= 64 && (r
 hipError_t launch_route_shrink_small(const void* x, const float* partials, int KS, const float* bias, const void* A,
                                      int T, int d_in, int N, int r, int k, float inv_temperature, float scale,
                                      int32_t* topk_idx, float* topk_w, void* hdense, int ext_stride,
-                                     hipStream_t stream, const float* gpart, int GS, float* hs) {
+                                     hipStream_t stream) {
     const int NP = padded_adapters(N);
     auto go = [&](auto kern) {
         kern<<<T, kSmallThreads, 0, stream>>>((const bf16_t*)x, partials, KS, bias, (const bf16_t*)A, T, d_in, N, NP, k,
-                                    inv_temperature, scale, topk_idx, topk_w, (bf16_t*)hdense, ext_stride, gpart,
-                                    GS, hs, RouteGroup{}, FinishGroup{});
+                                              inv_temperature, scale, topk_idx, topk_w, (bf16_t*)hdense, ext_stride);
         return hipGetLastError();
     };
     if (r == 8) return go(route_shrink_small_kernel<1>);
     if (r == 16) return go(route_shrink_small_kernel<2>);
     if (r == 32) return go(route_shrink_small_kernel<4>);
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_route_shrink_small_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
-                                           int r, int k, float inv_temperature, float scale, hipStream_t stream) {
-    if (G < 1 || G > kMaxDecodeGroup) return hipErrorInvalidValue;
-    const int NP = padded_adapters(N);
-    RouteGroup rg{};
-    for (int g = 0; g < G; ++g)
-        rg.m[g] = {mem[g].gpartial, mem[g].bias, (const bf16_t*)mem[g].A, mem[g].idx, mem[g].w, mem[g].hs};
-    rg.G = G;
-    auto go = [&](auto kern) {
-        kern<<<G * T, kSmallThreads, 0, stream>>>((const bf16_t*)x, nullptr, 0, nullptr, nullptr, T, d_in, N, NP, k,
-                                                  inv_temperature, scale, nullptr, nullptr, nullptr, 0, nullptr, S,
-                                                  nullptr, rg, FinishGroup{});
-        return hipGetLastError();
-    };
-    if (r == 8) return go(route_shrink_small_kernel<1>);
-    if (r == 16) return go(route_shrink_small_kernel<2>);
-    if (r == 32) return go(route_shrink_small_kernel<4>);
-    return hipErrorInvalidValue;
-}
-
-// Routing, shrink, split-K reduction and expand of decode-sized calls in one launch (the FINISH form of the kernel):
-// replaces launch_route_shrink_small_group followed by launch_gemm_decode_finish, with the same results bit for bit.
-int decode_finish_chunks(int T, int G) {
-    // about one workgroup per CU (a workgroup is 16 wavefronts): 256 / (G * T), at least 1, at most 16
-    int ch = 256 / (G * T > 0 ? G * T : 1);
-    return ch < 1 ? 1 : (ch > 16 ? 16 : ch);
-}
-
-hipError_t launch_route_shrink_finish_group(const void* x, const DecodeMember* mem, int G, int S, int T, int d_in, int N,
-                                            int r, int k, float inv_temperature, float scale, hipStream_t stream) {
-    if (G < 1 || G > kMaxDecodeGroup || S < 1) return hipErrorInvalidValue;
-    const int NP = padded_adapters(N);
-    RouteGroup rg{};
-    FinishGroup fg{};
-    for (int g = 0; g < G; ++g) {
-        if (mem[g].d_out % 8 != 0) return hipErrorInvalidValue;
-        rg.m[g] = {mem[g].gpartial, mem[g].bias, (const bf16_t*)mem[g].A, mem[g].idx, mem[g].w, nullptr};
-        fg.m[g] = {mem[g].partial, (const bf16_t*)mem[g].B, (bf16_t*)mem[g].out, mem[g].d_out};
-    }
-    rg.G = G;
-    fg.nsplit = S;
-    fg.chunks = decode_finish_chunks(T, G);
-    auto go = [&](auto kern) {
-        kern<<<G * T * fg.chunks, kSmallThreads, 0, stream>>>((const bf16_t*)x, nullptr, 0, nullptr, nullptr, T, d_in, N,
-                                                              NP, k, inv_temperature, scale, nullptr, nullptr, nullptr, 0,
-                                                              nullptr, S, nullptr, rg, fg);
-        return hipGetLastError();
-    };
-    if (r == 8) return go(route_shrink_small_kernel<1, true>);
-    if (r == 16) return go(route_shrink_small_kernel<2, true>);
-    if (r == 32) return go(route_shrink_small_kernel<4, true>);
     return hipErrorInvalidValue;
 }
 

@@ -238,12 +238,12 @@ def test_packed_weights_serve_many_batches():
 
 SMALL_BATCH_SHAPES = [
     LS(1, 512, 256, 28, 8, 2, 2.0, "bf16", "uniform", "T=1"),
-    LS(64, 1024, 776, 12, 16, 3, 1.5, "bf16", "zipf", "T=64-r16-k3-bias-three-launch"),
+    LS(64, 1024, 776, 12, 16, 3, 1.5, "bf16", "zipf", "T=64-r16-k3-bias-two-launch"),
     LS(40, 4096, 1032, 28, 8, 2, 2.0, "bf16", "uniform", "T=40-ragged-tiles"),
     LS(7, 264, 136, 5, 16, 1, 1.0, "bf16", "zipf", "T=7-r16-top1-ragged"),
     LS(64, 1024, 520, 64, 32, 8, 0.5, "bf16", "uniform", "T=64-N64-r32-k8"),
     LS(33, 5120, 264, 28, 8, 2, 2.0, "bf16", "zipf", "T=33-decode-shape"),
-    LS(48, 1024, 520, 28, 16, 2, 2.0, "bf16", "uniform", "T=48-r16-N28-three-launch"),
+    LS(48, 1024, 520, 28, 16, 2, 2.0, "bf16", "uniform", "T=48-r16-N28-two-launch"),
 ]
 
 
@@ -418,7 +418,7 @@ def _group_case(T, d_in, d_outs, N, r, k, routing, seed):
 
 
 @pytest.mark.parametrize("T,d_in,d_outs,N,r,k,routing,packed", [
-    (33, 1024, (520, 136, 136), 28, 8, 2, "uniform", True),      # q/k/v-like, three launches for the group
+    (33, 1024, (520, 136, 136), 28, 8, 2, "uniform", True),      # q/k/v-like, two launches for the group
     (64, 4096, (1032, 1032), 12, 16, 3, "zipf", True),           # gate/up-like, r = 16, bias
     (8, 512, (256, 264, 136, 72), 28, 8, 2, "uniform", True),    # four members
     (33, 1024, (520, 136), 28, 8, 2, "uniform", False),          # not packed: member by member
@@ -451,7 +451,7 @@ def test_group_call_matches_oracle_and_single_calls(T, d_in, d_outs, N, r, k, ro
 
 
 # ------------------------------------------------ temperature (App. A.6) and the top-1 strategy (App. A.1)
-# one shape per launch sequence of the whole-layer call: decode (three launches), a few hundred tokens with the
+# one shape per launch sequence of the whole-layer call: decode (two launches), a few hundred tokens with the
 # projection split along K, dense routing in front of the fused GEMM, bucketed (rank 12 is no multiple of 8), fp32
 SEQUENCE_SHAPES = [
     LS(48, 1024, 520, 28, 8, 2, 2.0, "bf16", "uniform", "decode"),
@@ -487,7 +487,7 @@ def test_linear_forward_top1(shape):
 
 
 def test_group_call_with_temperature():
-    """The grouped call passes the temperature on to every member (decode-sized group, three launches)."""
+    """The grouped call passes the temperature on to every member (decode-sized group, two launches)."""
     shapes, all_ops, members, x, rows = _group_case(33, 1024, (520, 136), 28, 8, 2, "uniform", seed=53)
     for mb in members:
         mb["packed"] = m.pack_weights(mb["W_gate"], mb["A"], mb["B"])
