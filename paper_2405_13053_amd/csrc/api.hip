@@ -34,8 +34,9 @@ bool decode_fused_applies(int T, int d_in, int d_out, int N, int r, bool bf16) {
 // LoRA expand, as for decode.  Returns the number of K splits, 0 = the fused GEMM runs instead.
 int dense_midsplit_splits(int T, int d_in, int d_out, int N, int r, bool bf16) {
     // measured on 4096 -> 4096 and 4096 -> 14336, T = 65 ... 2048: the split form wins up to about 160 output tiles
-    // of 128 x 128 (35.7 against 56.1 us at T = 65, 53.0 against 60.1 at T = 512 for 4096 -> 4096), beyond that the
-    // fp32 tiles it writes and reads back cost more than the idle CUs
+    // of 128 x 128 (19.0 against 56.1 us at T = 65, 44.6 against 60.1 at T = 512, 50.9 at T = 640, but 58.2 against
+    // 52.9 at T = 768 for 4096 -> 4096), beyond that the fp32 tiles it writes and reads back cost more than the
+    // idle CUs
     const int64_t tiles = (int64_t)ceil_div(T, 128) * ceil_div(d_out, 128);
     if (!route_dense_applies(T, d_in, N, r, bf16) || tiles > 160 || d_out % 8 != 0 || !gemm_dense_splitk_ok(T, d_in, d_out))
         return 0;
@@ -261,7 +262,7 @@ int meteora_workspace_regions(int T, int d_in, int d_out, int N, int r, int k, m
         if (const int S = dense_midsplit_splits(T, d_in, d_out, N, r, bf16)) {
             wr("spart", (size_t)S * T * d_out * sizeof(float));
             wr("dpart", (size_t)S * T * CR * sizeof(float));
-            wr("h32", pairs * r * sizeof(float));
+            if (!decode_tail_applies(r)) wr("h32", pairs * r * sizeof(float));
         } else {
             wr("dpart", (size_t)gemm_dense_splits(T, d_in, CR) * T * CR * sizeof(float));
             wr("hdense", (size_t)T * L.ext_stride * sizeof(uint16_t));
@@ -540,11 +541,16 @@ meteora_status meteora_linear_forward_packed(const void* x, const void* W, const
             // few output tiles: x * W^T and x * Wcat^T as fp32 K-split tiles of one launch, selection, then the
             // reduction with the expand (the decode sequence with 128 x 128 tiles and the dense selection)
             float* hs = at<float>(ws, L.h32);
-            DecodeMember mem{W, nullptr, gate_bias, A, B, d_out, at<float>(ws, L.spart), nullptr, hs, idx, w, out};
+            DecodeMember mem{W, nullptr, gate_bias, A, B, d_out, at<float>(ws, L.spart), dpart, hs, idx, w, out};
             {
                 StageScope sc(ST_GEMM, st, tslot);
                 const DenseOperand two[2] = {{W, d_out, mem.partial}, {pk.wcat, prep_wcat_rows(N, r), dpart}};
                 METEORA_HIP(launch_gemm_dense_splitk_multi(x, two, 2, S, T, d_in, st));
+            }
+            if (decode_tail_applies(r)) {   // selection, reduction and expand in one launch, as for decode
+                StageScope sc(ST_SHRINK, st, tslot);
+                METEORA_HIP(launch_decode_tail_group(&mem, 1, S, T, N, r, k, prep_wcat_rows(N, r), inv_temperature, scale, st));
+                return METEORA_OK;
             }
             {
                 StageScope sc(ST_GATE_TOPK, st, tslot);
@@ -723,6 +729,11 @@ extern "C" meteora_status meteora_linear_forward_group(const void* x, const mete
         {
             StageScope sc(ST_GEMM, st, tslot);
             METEORA_HIP(launch_gemm_dense_splitk_multi(x, ops, 2 * G, S, T, d_in, st));
+        }
+        if (decode_tail_applies(r)) {
+            StageScope sc(ST_SHRINK, st, tslot);
+            METEORA_HIP(launch_decode_tail_group(mem, G, S, T, N, r, k, cat_rows, inv_temperature, scale, st));
+            return METEORA_OK;
         }
         {
             StageScope sc(ST_GATE_TOPK, st, tslot);

@@ -228,7 +228,7 @@ static hipError_t launch_mfma(GemmArgs a, hipStream_t stream) {
 // Up to 4096 tokens: 128 x 128 tiles, two workgroups per CU (one computes while the other waits for its
 // loads), about 384 workgroups; above: 128 x 320 tiles (x is read once), one workgroup per CU.  Both with
 // the three-deep W ring.  Measured on T = 4096 and 8192, d_in = 4096 and 14336.
-static bool dense_small_tiles(int T) { static const char* e = getenv("METEORA_EXP_WIDE"); return e ? T <= atoi(e) : T <= 4096; }
+static bool dense_small_tiles(int T) { return T <= 4096; }
 
 bool gemm_dense_splitk_ok(int T, int d_in, int rows) {
     const uint64_t widest = (uint64_t)d_in * 2;

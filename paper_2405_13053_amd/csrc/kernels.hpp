@@ -143,6 +143,7 @@ int gemm_group_splits(int T, int d_in, const int* d_out, int G, int gate_rows); 
 hipError_t launch_gemm_decode_main(const void* x, const DecodeMember* mem, int G, int gate_rows, int S, int T,
                                    int d_in, hipStream_t stream);
 hipError_t launch_gemm_decode_finish(const DecodeMember* mem, int G, int S, int T, int k, int r, hipStream_t stream);
+bool decode_tail_applies(int r);   // ranks the tail's kernel is built for
 hipError_t launch_decode_tail_group(const DecodeMember* mem, int G, int S, int T, int N, int r, int k, int gate_rows,
                                     float inv_temperature, float scale, hipStream_t stream);
 // The same three launches for batches of a few hundred tokens with few output tiles: launch_gemm_dense_splitk_multi over

@@ -297,6 +297,8 @@ __global__ __launch_bounds__(kTailThreads) void decode_tail_kernel(int T, int N,
     }
 }
 
+bool decode_tail_applies(int r) { return r == 8 || r == 16 || r == 32; }
+
 // gate_rows = every row of Wcat: the split tiles mem[g].gpartial hold the gate terms and all adapters' shrink.
 hipError_t launch_decode_tail_group(const DecodeMember* mem, int G, int S, int T, int N, int r, int k, int gate_rows,
                                     float inv_temperature, float scale, hipStream_t stream) {
