@@ -26,7 +26,7 @@ __device__ unsigned mix(unsigned x) {
 // RANDOM: operands uniform in (-1, 1) and (-0.02, 0.02) (like x and W); otherwise ones and zeros.
 // DISTINCT: 4 + 4 different operand registers combined as a 4 x 4 block (like a 128 x 128 wavefront tile);
 // otherwise every MFMA reads the same two registers.
-template <bool RANDOM, bool DISTINCT>
+template <bool RANDOM, bool DISTINCT, int CHAIN = 1>
 __global__ __launch_bounds__(256) void mfma_loop(float* out, int iters) {
     bf16x8 a[4], b[4];
     for (int r = 0; r < 4; ++r)
@@ -39,12 +39,16 @@ __global__ __launch_bounds__(256) void mfma_loop(float* out, int iters) {
     for (int i = 0; i < 16; ++i)
         for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
     for (int it = 0; it < iters; ++it) {
+        // CHAIN consecutive MFMAs accumulate into the same block (the k-steps of a tile taken per block) before the
+        // next block's turn; CHAIN = 1 visits all 16 blocks per k-step
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < 4 / CHAIN; ++r)
 #pragma unroll
             for (int i = 0; i < 16; ++i)
-                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[DISTINCT ? (i & 3) : 0], b[DISTINCT ? (i >> 2) : 0],
-                                                                 acc[i], 0, 0, 0);
+#pragma unroll
+                for (int c = 0; c < CHAIN; ++c)
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[DISTINCT ? ((i + c) & 3) : 0],
+                                                                     b[DISTINCT ? ((i >> 2) ^ c) & 3 : 0], acc[i], 0, 0, 0);
     }
     float s = 0.f;
     for (int i = 0; i < 16; ++i)
@@ -89,7 +93,7 @@ __global__ __launch_bounds__(256) void mfma_loop_16(float* out, int iters) {
         }                                                                             \
     } while (0)
 
-template <bool RANDOM, bool DISTINCT>
+template <bool RANDOM, bool DISTINCT, int CHAIN = 1>
 int run(const char* name, float* out, int iters, int blocks) {
     hipEvent_t e0, e1;
     CHECK(hipEventCreate(&e0));
@@ -98,7 +102,7 @@ int run(const char* name, float* out, int iters, int blocks) {
     float ms = 0.f;
     for (int rep = 0; rep < 4; ++rep) {
         CHECK(hipEventRecord(e0));
-        mfma_loop<RANDOM, DISTINCT><<<blocks, 256>>>(out, iters);
+        mfma_loop<RANDOM, DISTINCT, CHAIN><<<blocks, 256>>>(out, iters);
         CHECK(hipGetLastError());
         CHECK(hipEventRecord(e1));
         CHECK(hipEventSynchronize(e1));
@@ -141,6 +145,11 @@ int main(int argc, char** argv) {
     if (run<true, false>("random operands, one register pair", out, iters, blocks)) return 1;
     if (run<true, true>("random operands, 4 x 4 register block", out, iters, blocks)) return 1;
     if (run<false, true>("constant operands again (clock recovered?)", out, iters, blocks)) return 1;
+    if (run<false, true, 2>("constant, 4 x 4 block, 2 MFMAs per block in a row", out, iters, blocks)) return 1;
+    if (run<true, true, 2>("random, 4 x 4 block, 2 MFMAs per block in a row", out, iters, blocks)) return 1;
+    if (run<false, true, 4>("constant, 4 x 4 block, 4 MFMAs per block in a row", out, iters, blocks)) return 1;
+    if (run<true, true, 4>("random, 4 x 4 block, 4 MFMAs per block in a row", out, iters, blocks)) return 1;
+    if (run<true, true>("random, 4 x 4 block, one per block (again)", out, iters, blocks)) return 1;
     printf("bf16 MFMA 16x16x32 loop, same arithmetic per wavefront (%d x 128 MFMAs)\n", iters);
     if (run16<false>("16x16x32 constant operands, 8 x 8 block", out, iters, blocks)) return 1;
     if (run16<true>("16x16x32 random operands, 8 x 8 block", out, iters, blocks)) return 1;
