@@ -7,7 +7,8 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libmeteora.so")
-DIAG = os.path.join(HERE, "mfma_ceiling")   # measurement tool, see csrc/diag/mfma_ceiling.hip
+# measurement tools, see csrc/diag/*.hip
+DIAG_TOOLS = ("mfma_ceiling", "operand_path_probe")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -30,15 +31,17 @@ def _hipcc(cmd, verbose):
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every HIP source into one shared library, and the stand-alone measurement tool
-    (csrc/diag/mfma_ceiling.hip -> ./mfma_ceiling); always recompiles."""
+    """Compile every HIP source into one shared library, and the stand-alone measurement tools
+    (csrc/diag/<tool>.hip -> ./<tool>); always recompiles."""
     tmp = LIB + f".tmp{os.getpid()}"
     _hipcc(["hipcc", *HIPCC_FLAGS, "-o", tmp, *sources()], verbose)
     os.replace(tmp, LIB)
-    tmp = DIAG + f".tmp{os.getpid()}"
     flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
-    _hipcc(["hipcc", *flags, "-o", tmp, os.path.join(HERE, "csrc", "diag", "mfma_ceiling.hip")], verbose)
-    os.replace(tmp, DIAG)
+    for tool in DIAG_TOOLS:
+        exe = os.path.join(HERE, tool)
+        tmp = exe + f".tmp{os.getpid()}"
+        _hipcc(["hipcc", *flags, "-o", tmp, os.path.join(HERE, "csrc", "diag", tool + ".hip")], verbose)
+        os.replace(tmp, exe)
     return LIB
 
 
