@@ -244,6 +244,11 @@ SMALL_BATCH_SHAPES = [
     LS(64, 1024, 520, 64, 32, 8, 0.5, "bf16", "uniform", "T=64-N64-r32-k8"),
     LS(33, 5120, 264, 28, 8, 2, 2.0, "bf16", "zipf", "T=33-decode-shape"),
     LS(48, 1024, 520, 28, 16, 2, 2.0, "bf16", "uniform", "T=48-r16-N28-two-launch"),
+    # the decode tail's loops: k*r = 256 shrink values per token (four groups of 64 / r slots), a row of 513
+    # 8-column pieces (nine stretches, the last with one active lane), top-1
+    LS(50, 1024, 776, 16, 32, 8, 0.5, "bf16", "zipf", "T=50-N16-r32-k8-tail"),
+    LS(9, 1024, 4104, 28, 8, 8, 1.0, "bf16", "uniform", "T=9-k8-ragged-stretch"),
+    LS(64, 2048, 1544, 28, 8, 1, 2.0, "bf16", "zipf", "T=64-top1-tail"),
 ]
 
 
