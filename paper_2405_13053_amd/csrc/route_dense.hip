@@ -16,17 +16,10 @@
 
 namespace meteora {
 
-// 16 tokens per workgroup: the kernel is two dependent rounds of loads, so it wants every CU busy rather than
-// long workgroups (T = 4096 gives 256 workgroups)
-constexpr int kSelTokens = 16;
-constexpr int kSelTokensPerWave = 4;
-constexpr int kSelThreads = kSelTokens / kSelTokensPerWave * 64;
-
 constexpr int kWcatMaxRows = 640;
 constexpr int kSelNP = 32;   // gate columns per term in Wcat: the path takes N <= 32 only (more adapters exceed its row limit)
 
-// WIDE: twice as many K splits' loads in flight (batches of a few hundred tokens come with up to 8 splits; with 4 or
-// fewer the narrow form is about 1 us faster)
+// WIDE (more than 4 K splits): twice as many splits' loads in flight
 // Members of one launch (blockIdx.y): layers that share x and the shapes T, N, r, k, S, CR, each with its own
 // partial products, bias and outputs.
 struct SelectMembers {
@@ -40,6 +33,12 @@ struct SelectMembers {
     } m[kMaxDecodeGroup];
 };
 
+// Independent wavefronts, no LDS and no barrier: a wavefront ranks two tokens (one per half, NP = 32 lanes each)
+// and writes their rows, a 16-byte piece (8 columns of one adapter, r % 8 == 0) per lane and round.  Two rounds of
+// loads: the gate terms of every K split, then the selected adapters' shrink columns.  (A workgroup form of it — 16
+// tokens per workgroup, the choices handed from the ranking wavefront to the row writers through LDS behind a
+// barrier — took 7.9 us at config 2 and 9.3 us at T = 1024 where this one takes 5.6 and 5.3.)
+constexpr int kSelThreads = 256;
 template <bool WIDE>
 __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(const SelectMembers sm, int S, int CR, int T,
                                                                          int N, int r, int k, float inv_temperature,
@@ -51,65 +50,46 @@ __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(const S
     bf16_t* __restrict__ hdense = sm.m[blockIdx.y].hdense;
     float* __restrict__ hs = sm.m[blockIdx.y].hs;
     constexpr int NP = kSelNP;
-    constexpr int TPP = 64 / NP;                     // tokens ranked per pass
-    constexpr int G = kSelTokensPerWave / TPP;       // passes (groups) per wavefront
-    __shared__ int s_idx[kSelTokens][kMaxTopK];
-    __shared__ float s_w[kSelTokens][kMaxTopK];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int col = lane & (NP - 1), sub = lane / NP;
-    const int t0 = blockIdx.x * kSelTokens;
-
-    float g[G];
-    int lt[G];   // token index inside the workgroup
-#pragma unroll
-    for (int i = 0; i < G; ++i) lt[i] = wave * kSelTokensPerWave + i * TPP + sub;
-    dense_logits<NP, G, WIDE ? 8 : 4>(part, S, CR, bias, T, N, t0, lt, col, g);
-    int sel_i[G];
-    float sel_w[G];
-    wave_topk_softmax<NP, G>(g, lane, N, k, inv_temperature, sel_i, sel_w);
-#pragma unroll
-    for (int i = 0; i < G; ++i) {
-        if (col < k) {
-            s_idx[lt[i]][col] = sel_i[i];
-            s_w[lt[i]][col] = sel_w[i];
-            const int t = t0 + lt[i];
-            if (t < T) {
-                topk_idx[(size_t)t * k + col] = sel_i[i];
-                topk_w[(size_t)t * k + col] = sel_w[i];
-            }
-        }
+    const int lane = threadIdx.x & 63, col = lane & (NP - 1), sub = lane / NP;
+    const int t0 = (blockIdx.x * (kSelThreads / 64) + (threadIdx.x >> 6)) * 2;
+    if (t0 >= T) return;   // the whole wavefront
+    float g[1];
+    const int lt[1] = {sub};
+    dense_logits<NP, 1, WIDE ? 8 : 4>(part, S, CR, bias, T, N, t0, lt, col, g);
+    int sel_i[1];
+    float sel_w[1];
+    wave_topk_softmax<NP, 1>(g, lane, N, k, inv_temperature, sel_i, sel_w);   // lane col = s < k: the s-th choice
+    if (col < k && t0 + sub < T) {
+        topk_idx[(size_t)(t0 + sub) * k + col] = sel_i[0];
+        topk_w[(size_t)(t0 + sub) * k + col] = sel_w[0];
     }
-    __syncthreads();
-
-    // ---- rows of hdense: a thread owns 8 columns (one adapter's, r % 8 == 0) of one token ----
     const int C8 = ext_stride / 8;
-    for (int e = threadIdx.x; e < kSelTokens * C8; e += kSelThreads) {
-        const int tl = e / C8, c0 = (e - tl * C8) * 8;
-        const int t = t0 + tl;
-        if (t >= T) continue;
+    for (int e0 = 0; e0 < 2 * C8; e0 += 64) {   // uniform trip count: every lane takes part in the exchanges
+        const int e = e0 + lane;
+        const bool active = e < 2 * C8;
+        const int th = active ? e / C8 : 0, c0 = active ? (e - th * C8) * 8 : 0;
+        const int t = active ? t0 + th : T;
         const int a = c0 / r;
         bool hit = false;
         float sw = 0.f;
         int slot = 0;
-        if (c0 < N * r)
-            for (int s = 0; s < k; ++s)
-                if (s_idx[tl][s] == a) { hit = true; sw = scale * s_w[tl][s]; slot = s; }
+        for (int s = 0; s < k; ++s) {
+            const int ai = __shfl(sel_i[0], th * NP + s);
+            const float wi = __shfl(sel_w[0], th * NP + s);
+            if (c0 < N * r && ai == a) { hit = true; sw = scale * wi; slot = s; }
+        }
         u32x4 pk = {0u, 0u, 0u, 0u};
-        if (hit) {
+        if (hit && t < T) {
             f32x4 h0 = {0.f, 0.f, 0.f, 0.f}, h1 = {0.f, 0.f, 0.f, 0.f};
             const float* src = part + (size_t)t * CR + 3 * NP + c0;
-            constexpr int HU = WIDE ? 16 : 8;
+            constexpr int HU = WIDE ? 8 : 4;
             for (int s0 = 0; s0 < S; s0 += HU) {   // splits in order, 2 * HU loads in flight
                 f32x4 v0[HU], v1[HU];
 #pragma unroll
                 for (int u = 0; u < HU; ++u) {
-                    v0[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    v1[u] = v0[u];
-                    if (s0 + u < S) {   // uniform: no loads beyond the last split
-                        const float* p = src + (size_t)(s0 + u) * T * CR;
-                        v0[u] = *reinterpret_cast<const f32x4*>(p);
-                        v1[u] = *reinterpret_cast<const f32x4*>(p + 4);
-                    }
+                    const float* p = src + (size_t)min(s0 + u, S - 1) * T * CR;
+                    v0[u] = *reinterpret_cast<const f32x4*>(p);
+                    v1[u] = *reinterpret_cast<const f32x4*>(p + 4);
                 }
 #pragma unroll
                 for (int u = 0; u < HU; ++u)
@@ -123,7 +103,7 @@ __global__ __launch_bounds__(kSelThreads) void route_dense_select_kernel(const S
             pk[0] = pack_bf16x2(sw * h0[0], sw * h0[1]); pk[1] = pack_bf16x2(sw * h0[2], sw * h0[3]);
             pk[2] = pack_bf16x2(sw * h1[0], sw * h1[1]); pk[3] = pack_bf16x2(sw * h1[2], sw * h1[3]);
         }
-        if (hdense != nullptr) *reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride + c0) = pk;
+        if (hdense != nullptr && t < T) *reinterpret_cast<u32x4*>(hdense + (size_t)t * ext_stride + c0) = pk;
     }
 }
 
@@ -153,7 +133,7 @@ hipError_t launch_route_dense_products(const void* x, const void* wcat, int T, i
 static hipError_t launch_select(const SelectMembers& sm, int G, int S, int T, int N, int r, int k,
                                 float inv_temperature, float scale, int ext_stride, hipStream_t stream) {
     const int CR = prep_wcat_rows(N, r);
-    const dim3 grid(ceil_div(T, kSelTokens), G);
+    const dim3 grid(ceil_div(T, 2 * (kSelThreads / 64)), G);
     if (S > 4)
         route_dense_select_kernel<true><<<grid, kSelThreads, 0, stream>>>(sm, S, CR, T, N, r, k, inv_temperature, scale,
                                                                           ext_stride);
