@@ -211,9 +211,9 @@ class Workload:
         decode = "gate_logits" not in stage_us and "bucket" not in stage_us and "shrink" in stage_us and shape.T <= 64
         gemm_us = kernel_us["gemm"]
         if decode:
-            # weight streaming: the launch that reads W (with the gate logits riding in it) against HBM
+            # weight streaming: the launch that reads W (with the routing products riding in it) against HBM
             achieved = alg["gemm"]["bytes"] / (gemm_us * 1e-6) / 1e9
-            roofline = {"kernel": "split-K base projection (streams W once; gate logits in the same launch)",
+            roofline = {"kernel": "split-K base projection (streams W once; gate logits and every adapter's shrink in the same launch)",
                         "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": achieved / PEAK_HBM_GBS, "traffic": None,
                         "algorithmic_bytes": alg["gemm"]["bytes"], "us": gemm_us,
@@ -247,6 +247,8 @@ class Workload:
             d = {"us": round(us, 2)}
             if n == "gate_logits" and dense_route:
                 d["covers"] = "gate logits and LoRA shrink in one launch; gate_topk = top-k, softmax and selection"
+            if n == "shrink" and "gate_logits" not in stage_us and "bucket" not in stage_us:
+                d["covers"] = "the tail launch: top-k, softmax, split-K reduction and LoRA expand"
             if key and key in alg:
                 t = kernel_us[n] * 1e-6
                 d["GB/s"] = round(alg[key]["bytes"] / t / 1e9, 1)
