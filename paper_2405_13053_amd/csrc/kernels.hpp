@@ -51,11 +51,13 @@ hipError_t launch_route_shrink_small(const void* x, const float* partials, int K
                                      int32_t* topk_idx, float* topk_w, void* hdense, int ext_stride,
                                      hipStream_t stream);
 
-// ---- mid-sized batches (64 < T <= kRouteDenseMaxTokens, bf16, r % 8 == 0, d_in % 64 == 0): one MFMA launch
+// ---- batches of more than 64 tokens (bf16, r % 8 == 0, d_in % 64 == 0, at most 640 rows of Wcat): one MFMA launch
 // computes the split-bf16 gate logits and x * A_i of every adapter as fp32 K-split partials
-// part[splits][T][prep_wcat_rows], then one launch per 64 tokens adds the splits, ranks (Sec. 3.1, Eq. 3) and
-// writes topk_idx, topk_w and every column of the tokens' rows of hdense.  Replaces launch_gate_logits,
-// launch_gate_topk, launch_bucket and launch_shrink for the whole-layer call.
+// part[splits][T][prep_wcat_rows], then a launch of independent wavefronts adds the splits, ranks (Sec. 3.1, Eq. 3)
+// and writes topk_idx, topk_w and every column of the tokens' rows of hdense.  Replaces launch_gate_logits,
+// launch_gate_topk, launch_bucket and launch_shrink for the whole-layer call.  Up to kRouteDenseMaxTokens always;
+// beyond, with up to 320 rows of Wcat always, with more where the products' tiles fill the CUs
+// (route_dense_applies).
 constexpr int kRouteDenseMaxTokens = 8192;
 bool route_dense_possible(int d_in, int N, int r, bool bf16);            // whatever T: is Wcat worth packing
 bool route_dense_applies(int T, int d_in, int N, int r, bool bf16);

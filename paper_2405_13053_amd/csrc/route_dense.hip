@@ -114,9 +114,18 @@ bool route_dense_possible(int d_in, int N, int r, bool bf16) {
     return bf16 && r % 8 == 0 && d_in % 64 == 0 && padded_adapters(N) == kSelNP && prep_wcat_rows(N, r) <= kWcatMaxRows;
 }
 
+// Measured against the bucketed sequence (gate logits, top-k, scatter, whole-K shrink) on 4096 -> 4096 and
+// 14336 -> 4096 at T = 12000 ... 65536: with 320 rows of Wcat (28 adapters of rank 8) the dense form wins at every
+// size (whole call: 357.6 against 377.0 us at T = 12000, 918.9 against 984.8 at 32768, 1830 against 1985 at 65536);
+// with 544 rows (rank 16) it wins by 0.3-8% where the products' 128 x 320 tiles fill the CUs (T = 16384: 496.7 against
+// 515.2 us, 1631 against 1680 with d_in = 14336) and loses where they do not (T = 12000, d_in = 14336: 188 workgroups
+// of a full K sweep each, 1269 against 1231 us).
 bool route_dense_applies(int T, int d_in, int N, int r, bool bf16) {
-    return route_dense_possible(d_in, N, r, bf16) && T > 64 && T <= kRouteDenseMaxTokens &&
-           gemm_dense_splitk_ok(T, d_in, prep_wcat_rows(N, r));
+    const int CR = prep_wcat_rows(N, r);
+    if (!route_dense_possible(d_in, N, r, bf16) || T <= 64 || !gemm_dense_splitk_ok(T, d_in, CR)) return false;
+    if (T <= kRouteDenseMaxTokens || CR <= 320) return true;
+    const int64_t wgs = (int64_t)ceil_div(T, 128) * ceil_div(CR, 320) * gemm_dense_splits(T, d_in, CR);
+    return wgs * 10 >= (wgs + 255) / 256 * 256 * 9;   // at least 90% of the CUs' slots over the launch
 }
 
 size_t route_dense_part_bytes(int T, int d_in, int N, int r, bool bf16) {

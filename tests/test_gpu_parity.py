@@ -395,9 +395,13 @@ def test_layer_call_does_not_depend_on_workspace_contents(T):
             assert torch.equal(idx, idx_ref) and torch.equal(w, w_ref) and torch.equal(out, ref)
 
 
-def test_many_tokens_small_layer_sampled_rows():
-    """T = 70000 through the bucketed path (1094 bucketing chunks, whole-K shrink): index arithmetic at scale."""
-    shape = LS(70000, 256, 264, 28, 8, 2, 2.0, "bf16", "zipf", "T=70000")
+@pytest.mark.parametrize("r,N,path", [(12, 28, "bucketed"), (8, 28, "dense"), (16, 28, "rank16")],
+                         ids=["bucketed-r12", "dense-r8", "r16"])
+def test_many_tokens_small_layer_sampled_rows(r, N, path):
+    """T = 70000: index arithmetic at scale on the sequences a large batch can take.  Rank 12 goes through the
+    bucketed path (1094 bucketing chunks, whole-K shrink), rank 8 through the dense routing products (320 rows of
+    Wcat: every batch size), rank 16 through whichever of the two the tile count of the products selects."""
+    shape = LS(70000, 256, 264, N, r, 2, 2.0, "bf16", "zipf", f"T=70000-{path}")
     _check_layer(shape, seed=49, rows="sample")
 
 
