@@ -370,6 +370,8 @@ hipError_t gemm_init_kernels() {
     };
     lim(&gemm_mfma_w3_kernel<4, 4, kEpiStore>, gemm_w3_lds_bytes<4, 4>());
     lim(&gemm_mfma_w3_kernel<4, 4, kEpiAccumulate>, gemm_w3_lds_bytes<4, 4>());
+    lim(&gemm_mfma_w3_kernel<4, 2, kEpiStore>, gemm_w3_lds_bytes<4, 2>());
+    lim(&gemm_mfma_w3_kernel<4, 2, kEpiAccumulate>, gemm_w3_lds_bytes<4, 2>());
     lim(&gemm_mfma_w3_kernel<2, 2, kEpiStore>, gemm_w3_lds_bytes<2, 2>());
     lim(&gemm_mfma_w3_kernel<2, 2, kEpiAccumulate>, gemm_w3_lds_bytes<2, 2>());
     lim(&gemm_mfma_w3_kernel<2, 2, kEpiPartial>, gemm_w3_lds_bytes<2, 2>());
@@ -397,6 +399,25 @@ hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out,
         // 256 x 256 tiles once they fill most of the 256 CUs; below that 128 x 128 tiles keep more CUs busy
         // (T = 2048, 4096 -> 4096: 128 tiles of 256 x 256 take 109 us, 512 tiles of 128 x 128 take 98 us)
         if (T > 128 && big_tiles >= 160) return launch_mfma<4, 4>(a, stream);
+        // between the two: 256 x 128 tiles where 160 to 256 of them cover the output, one per CU (a wavefront's
+        // 128 x 64 piece needs 0.75 fragment reads per MFMA against 1.0 at 128 x 128).  Measured against 128 x 128
+        // tiles: T = 1280 at 4096 -> 4096 (160 tiles) 50.2 against 55.2 us, T = 2048 (256 tiles) 62.3 against 66.0,
+        // T = 512 at 4096 -> 14336 59.2 against 63.6, T = 2048 at 14336 -> 4096 199 against 219; with 128 tiles
+        // (T = 1024) 47.0 against 39.1, so not below 160
+        const int64_t mid_tiles = (int64_t)ceil_div(T, 256) * ceil_div(d_out, 128);
+        const uint64_t widest = (uint64_t)(d_in > ext_stride ? d_in : ext_stride) * 2;
+        if (T > 128 && mid_tiles >= 160 && mid_tiles <= 256 && d_in % kGemmBK == 0 &&
+            ((uint64_t)T + 256) * widest < (1ull << 32) && ((uint64_t)d_out + 128) * widest < (1ull << 32)) {
+            a.tiles_m = ceil_div(T, 256);
+            a.tiles_n = ceil_div(d_out, 128);
+            auto go = [&](auto kern) -> hipError_t {
+                const hipError_t e1 = ensure_lds_limit(reinterpret_cast<const void*>(kern), gemm_w3_lds_bytes<4, 2>());
+                if (e1 != hipSuccess) return e1;
+                kern<<<a.tiles_m * a.tiles_n, 256, gemm_w3_lds_bytes<4, 2>(), stream>>>(a);
+                return hipGetLastError();
+            };
+            return a.accumulate ? go(&gemm_mfma_w3_kernel<4, 2, kEpiAccumulate>) : go(&gemm_mfma_w3_kernel<4, 2, kEpiStore>);
+        }
         if (T > 64) return launch_mfma<2, 2>(a, stream);
         return launch_mfma<1, 1>(a, stream);
     }
