@@ -398,7 +398,11 @@ hipError_t launch_gemm(const void* x, const void* W, int T, int d_in, int d_out,
         const int64_t big_tiles = (int64_t)ceil_div(T, 256) * ceil_div(d_out, 256);
         // 256 x 256 tiles once they fill most of the 256 CUs; below that 128 x 128 tiles keep more CUs busy
         // (T = 2048, 4096 -> 4096: 128 tiles of 256 x 256 take 109 us, 512 tiles of 128 x 128 take 98 us)
-        if (T > 128 && big_tiles >= 160) return launch_mfma<4, 4>(a, stream);
+        // ... except a little more than one tile per CU (257 to 328 tiles), where the second, nearly empty round of
+        // 256 x 256 tiles costs more than the smaller tiles' lower efficiency (4096 -> 4096: T = 4608, 288 tiles, 174
+        // us against 155 with 128 x 128 tiles; T = 5120 176 against 163; 336 tiles and more: the big tiles win again,
+        // and with two rounds or more they always do: 544 tiles 275 against 279)
+        if (T > 128 && big_tiles >= 160 && !(big_tiles > 256 && big_tiles <= 328)) return launch_mfma<4, 4>(a, stream);
         // between the two: 256 x 128 tiles where 160 to 256 of them cover the output, one per CU (a wavefront's
         // 128 x 64 piece needs 0.75 fragment reads per MFMA against 1.0 at 128 x 128).  Measured against 128 x 128
         // tiles: T = 1280 at 4096 -> 4096 (160 tiles) 50.2 against 55.2 us, T = 2048 (256 tiles) 62.3 against 66.0,

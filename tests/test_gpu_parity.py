@@ -151,7 +151,8 @@ def test_lora_forward_matches_oracle(shape):
 @pytest.mark.parametrize("T,d_in,d_out,dtype", [(64, 256, 256, "f32"), (300, 520, 264, "bf16"),
                                                 (1024, 1024, 1024, "bf16"), (17, 4096, 72, "bf16"),
                                                 (1300, 192, 4104, "bf16"),      # 256 x 128 tiles, ragged both ways
-                                                (2600, 128, 4104, "bf16")])     # 256 x 256 tiles, ragged both ways
+                                                (2600, 128, 4104, "bf16"),      # 256 x 256 tiles, ragged both ways
+                                                (4400, 128, 4104, "bf16")])     # 306 big tiles: 128 x 128 tiles instead
 def test_base_gemm_matches_oracle(T, d_in, d_out, dtype):
     shape = LS(T, d_in, d_out, 2, 2, 1, 1.0, dtype)
     ops, dev = util.make_case(shape, seed=31, condition=False)
