@@ -53,7 +53,7 @@ def test_workspace_regions_hold_what_the_launches_write():
     (tile and K-split counts taken from the launch decisions), regions do not overlap, and all of them lie inside
     meteora_workspace_bytes."""
     Ts = [1, 7, 33, 64, 65, 100, 128, 129, 200, 256, 300, 512, 513, 700, 1000, 1150, 1151, 1500, 2000, 2048, 3000,
-          4096, 4097, 5000, 8192, 8193, 16384, 70000]
+          4096, 4097, 5000, 8192, 8193, 12000, 16384, 20000, 32768, 70000]
     dims = [(4096, 4096), (4096, 8), (4096, 256), (4096, 512), (4096, 1024), (4096, 14336), (14336, 4096),
             (5120, 5120), (5120, 13824), (512, 264), (1088, 520), (64, 72), (256, 136)]
     checked = 0
@@ -74,7 +74,7 @@ def test_workspace_regions_hold_what_the_launches_write():
                             end_prev = off + reserved
                         checked += 1
     assert checked > 5000
-    # the shapes of the round-1 finding: the split projection has more K splits than the routing products alone
+    # shapes whose split projection has more K splits than the routing products alone (d_out of one or two tiles)
     for T, d_in, d_out in ((3000, 4096, 256), (4096, 4096, 8)):
         regs = {n: (o, rsv, w) for n, o, rsv, w in m.workspace_regions(T, d_in, d_out, 28, 8, 2, "bf16", True)}
         assert regs["dpart"][2] <= regs["dpart"][1]
