@@ -8,7 +8,8 @@ every step calls meteora_linear_forward_packed; the same loop with per-call pack
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layer 0] [--tokens T]
                     [--no-cpu-baseline] [--no-extra-configs] [--graph] [--pmc-calibration]
-    python bench.py --summarize-pmc FETCH_DIR WRITE_DIR     (no GPU: writes profiles/hbm_traffic.json)
+    python bench.py --summarize-pmc FETCH_DIR WRITE_DIR [--summarize-workload configC/layerL]
+                                                            (no GPU: writes profiles/hbm_traffic.json)
 
 `value` is the headline workload: configuration 2 (q_proj-shaped prefill) unless --config/--layer say
 otherwise.  When the headline is configuration 2, the line also carries, under `configs`, the other seeded
@@ -98,7 +99,7 @@ def measured_traffic(config, layer):
     if not ent:
         return None, None
     return ent.get("dominant_kernel_bytes"), {"file": "profiles/hbm_traffic.json", "kernel": ent.get("dominant_kernel"),
-                                              "measured_at_head": data.get("head")}
+                                              "measured_at_head": ent.get("measured_at_head", data.get("head"))}
 
 
 class Workload:
@@ -213,13 +214,16 @@ class Workload:
         if decode:
             # weight streaming: the launch that reads W (with the routing products riding in it) against HBM
             achieved = alg["gemm"]["bytes"] / (gemm_us * 1e-6) / 1e9
+            traffic, source = (None, None) if len(self.calls) > 1 else measured_traffic(self.config, self.layer)
             roofline = {"kernel": "split-K base projection (streams W once; gate logits and every adapter's shrink in the same launch)",
                         "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                        "frac": achieved / PEAK_HBM_GBS, "traffic": traffic,
                         "algorithmic_bytes": alg["gemm"]["bytes"], "us": gemm_us,
                         "whole_call": {"algorithmic_bytes": alg["layer"]["bytes"],
                                        "GB/s": alg["layer"]["bytes"] / (res["ms_per_step"] * 1e-3) / 1e9,
                                        "frac": alg["layer"]["bytes"] / (res["ms_per_step"] * 1e-3) / 1e9 / PEAK_HBM_GBS}}
+            if source:
+                roofline["traffic_source"] = source
         else:
             gemm_flops = alg["gemm"]["flops"] + (alg["expand"]["flops"] if "expand" not in stage_us else 0.0)
             achieved = gemm_flops / (gemm_us * 1e-6) / 1e12
@@ -343,7 +347,7 @@ def paper_variants(wl, ms_layer, steps):
     return res
 
 
-def summarize_pmc(fetch_dir, write_dir):
+def summarize_pmc(fetch_dir, write_dir, workload="config2/layer0"):
     """Read the counter CSVs of two rocprofv3 --pmc runs of `bench.py --pmc-calibration` (FETCH_SIZE, WRITE_SIZE)
     and write profiles/hbm_traffic.json: per kernel the average counter value per dispatch, the factor that turns it
     into KiB (from the known-size copy in the same run) and the resulting HBM bytes."""
@@ -381,25 +385,40 @@ def summarize_pmc(fetch_dir, write_dir):
         kernels[k] = {"dispatches": max(len(f), len(w)), "FETCH_SIZE_raw": fa, "WRITE_SIZE_raw": wa,
                       "read_bytes": fa * fs * 1024, "written_bytes": wa * wsc * 1024,
                       "bytes": (fa * fs + wa * wsc) * 1024}
+    # the workload's dominant kernel: the 256 x 256 GEMM, else (decode) the split-K GEMM that streams W
     gemm = [k for k in kernels if "gemm_mfma_w3_kernel<4, 4" in k or "gemm_mfma_w3_kernel<4,4" in k]
+    if not gemm:
+        gemm = sorted((k for k in kernels if "gemm_mfma" in k), key=lambda k: -kernels[k]["bytes"])[:1]
     try:
         head = subprocess.check_output(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], text=True).strip()
     except Exception:
         head = None
-    data = {"command": "rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE --output-format csv -d <dir> -o b -- python3 bench.py "
-                       "--steps 10 --warmup 3 --no-cpu-baseline --no-extra-configs --pmc-calibration",
-            "head": head,
-            "calibration": {"copy_bytes": CALIBRATION_COPY_BYTES, "FETCH_SIZE_raw_for_copy": favg,
-                            "WRITE_SIZE_raw_for_copy": wavg, "FETCH_SIZE_to_KiB": fs, "WRITE_SIZE_to_KiB": wsc,
-                            "copy_kernel": fname[:80]},
-            "workloads": {"config2/layer0": {"dominant_kernel": gemm[0] if gemm else None,
-                                             "dominant_kernel_bytes": kernels[gemm[0]]["bytes"] if gemm else None,
-                                             "kernels": kernels}}}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            data = json.load(f)        # other workloads' entries are kept
+    except (OSError, ValueError):
+        data = {}
+    data["command"] = ("rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE --output-format csv -d <dir> -o b -- python3 bench.py "
+                       "[--config C --layer L] --steps 10 --warmup 3 --no-cpu-baseline --no-extra-configs "
+                       "--pmc-calibration; then python3 bench.py --summarize-pmc <fetch dir> <write dir> "
+                       "[--summarize-workload configC/layerL]")
+    data.setdefault("workloads", {})[workload] = {
+        "dominant_kernel": gemm[0] if gemm else None,
+        "dominant_kernel_bytes": kernels[gemm[0]]["bytes"] if gemm else None,
+        "measured_at_head": head,
+        "calibration": {"copy_bytes": CALIBRATION_COPY_BYTES, "FETCH_SIZE_raw_for_copy": favg,
+                        "WRITE_SIZE_raw_for_copy": wavg, "FETCH_SIZE_to_KiB": fs, "WRITE_SIZE_to_KiB": wsc,
+                        "copy_kernel": fname[:80]},
+        "kernels": kernels}
+    if workload == "config2/layer0":
+        data["head"] = head
+        data["calibration"] = data["workloads"][workload]["calibration"]
     with open(TRAFFIC_FILE, "w") as f:
         json.dump(data, f, indent=1)
         f.write("\n")
-    print(json.dumps({"written": TRAFFIC_FILE, "head": head, "calibration": data["calibration"],
-                      "dominant_kernel_bytes": data["workloads"]["config2/layer0"]["dominant_kernel_bytes"]}))
+    print(json.dumps({"written": TRAFFIC_FILE, "workload": workload, "head": head,
+                      "dominant_kernel": data["workloads"][workload]["dominant_kernel"],
+                      "dominant_kernel_bytes": data["workloads"][workload]["dominant_kernel_bytes"]}))
 
 
 def main():
@@ -420,9 +439,11 @@ def main():
                     help="run a known-size device copy first (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
                     help="no GPU: turn two rocprofv3 --pmc output folders into profiles/hbm_traffic.json")
+    ap.add_argument("--summarize-workload", default="config2/layer0", metavar="configC/layerL",
+                    help="with --summarize-pmc: the workload the two runs profiled (its entry of the JSON is replaced)")
     args = ap.parse_args()
     if args.summarize_pmc:
-        summarize_pmc(*args.summarize_pmc)
+        summarize_pmc(*args.summarize_pmc, workload=args.summarize_workload)
         return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
