@@ -145,15 +145,20 @@ class Workload:
             self.m.linear_forward(dev["x"], dev["W"], Wg, bias, dev["A"], dev["B"], sh.k, sh.scale, out=out, ws=ws)
 
     def timed(self, fn, steps, warmup):
+        """Seconds for `steps` calls after `warmup` untimed ones: synchronised on both sides, the interval itself
+        taken with events on the stream the calls are enqueued on (a host clock would add the wake-up after the
+        final synchronisation, 2-3% of a 20-step run of this layer)."""
         torch = self.torch
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         for _ in range(steps):
             fn()
+        e1.record()
         torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        return e0.elapsed_time(e1) * 1e-3
 
     def describe(self):
         shape = self.shape
@@ -169,6 +174,11 @@ class Workload:
         m, torch = self.m, self.torch
         m.stage_timing_enable(True)
         n_prof = max(1, min(n_prof, 200 // len(self.calls)))
+        # a first window that is read and dropped: the events' own first use, and the clocks after the pause that
+        # switching the timing on makes, stay out of the window that is reported
+        for _ in range(max(3, min(n_prof, 10))):
+            self.step()
+        m.stage_timing_read()
         for _ in range(n_prof):
             self.step()
         torch.cuda.synchronize()

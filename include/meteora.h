@@ -343,11 +343,11 @@ meteora_status meteora_base_gemm(const void* x, const void* W, int T, int d_in, 
  * hipEvents on `stream` around each stage (prep, gate_logits, gate_topk,
  * bucket, shrink, gemm, expand) for up to 256 calls.  A stage's reading is its kernels' time
  * plus the dispatch gap in front of them (about 2 us per launch against a kernel trace).  A stage that a batch size
- * folds into another is not reported: for 64 < T <= 8192 (bf16) gate_logits covers
+ * folds into another is not reported: where the routing runs without bucket lists (bf16, T > 64) gate_logits covers
  * the gate logits and the shrink, gate_topk the top-k, softmax and selection (batches with few output tiles:
- * gemm covers the K-split projection with those products, expand the reduction with the expand); for
- * T <= 64 gemm covers the base projection's split-K launch (with the gate logits),
- * shrink covers top-k, softmax and shrink, expand the reduction with the expand.  meteora_stage_timing_read waits
+ * gemm covers the K-split projection with those products, shrink the launch after it); for
+ * T <= 64 gemm covers the base projection's split-K launch (with the gate logits and every adapter's shrink),
+ * shrink the launch after it (top-k, softmax, reduction, expand).  meteora_stage_timing_read waits
  * for those events, returns per stage the summed milliseconds and the number
  * of timed launches (arrays of meteora_stage_count() entries, host memory)
  * and the number of calls covered, and starts a new window.  Not thread-safe;
