@@ -864,7 +864,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) 
     }
     for (; it + 2 < nk_main; ++it) tile_step(it, Req0{}, Rt{}, No{});
     for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{}, Rt{}, No{});
-    for (; it < nk; ++it) tile_step(it, std::integral_constant<int, 2>{}, Rt{}, No{});
+    // the last extension tile may hold data in its first two k-steps only (28 adapters of rank 8: 224 of 256 columns;
+    // the rest is zero padding): those two k-steps are all it gets
+    const bool half_last = nk_ext > 0 && ((a.ext_k - 1) % kGemmBK) < kGemmBK / 2;
+    for (; it < nk - (half_last ? 1 : 0); ++it) tile_step(it, std::integral_constant<int, 2>{}, Rt{}, No{});
+    if (half_last) {   // uniform; its first fragments were read, behind the barrier, in the previous step's last phase
+        load_frags<MI, NI>(f1, xslot(it), wslot(it), wm, wn, lrow, khalf, 1);
+        mma_frags<MI, NI>(acc, f0);
+        mma_frags<MI, NI>(acc, f1);
+    }
 
     gemm_epilogue<MI, NI, EPI>(a, acc, smem_raw, m0, n0, wm, wn, wave, lane);
 }
