@@ -847,9 +847,38 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) 
     using Req0 = std::integral_constant<int, 0>;
     using Rt = std::integral_constant<int, -1>;
     using No = std::false_type;
+    // the last extension tile may hold data in its first two k-steps only (28 adapters of rank 8: 224 of 256 columns;
+    // the rest is zero padding): those two k-steps are all it gets
+    const bool half_last = nk_ext > 0 && ((a.ext_k - 1) % kGemmBK) < kGemmBK / 2;
+    // A wavefront whose whole piece of the tile lies past the matrix (ragged last tile row or column: the third
+    // 128-column tile of the 320 routing products is half empty) moves its share of the operand tiles and keeps the
+    // barriers, one per K tile like the others, and skips the fragment reads and the MFMAs.
+    const bool idle = n0 + wn >= a.d_out || m0 + wm >= a.T;   // uniform per wavefront
     int it = 0;
+    if (idle) {
+        for (; it < nk - (half_last ? 1 : 0); ++it) {
+            if (it + 2 < nk) {
+                const bool ext = it + 2 >= nk_main;
+#pragma unroll
+                for (int i = 0; i < PW; ++i) {
+                    if (ext) request_w(wslot(it + 2), it + 2, i, std::true_type{});
+                    else request_w(wslot(it + 2), it + 2, i, std::false_type{});
+                }
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PW) : "memory");
+#pragma unroll
+                for (int i = 0; i < PX; ++i) {
+                    if (ext) request_x(xslot(it + 2), it + 2, i, std::true_type{});
+                    else request_x(xslot(it + 2), it + 2, i, std::false_type{});
+                }
+            } else {
+                __builtin_amdgcn_s_waitcnt(0);
+                __syncthreads();
+            }
+        }
+        it = nk;
+    }
     if constexpr (MI == 4 && NI == 4) {   // six tiles per trip: the period of the 2-slot and 3-slot rings
-        if (nk_main > 8) {
+        if (nk_main > 8 && !idle) {
             // tile 0 on its own: its first k-step starts the accumulators; the trips then begin at tile 1
             tile_step(0, Req0{}, std::integral_constant<int, 0>{}, std::true_type{});
             for (it = 1; it + 7 < nk_main; it += 6) {
@@ -864,11 +893,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_w3_kernel(const GemmArgs a_in) 
     }
     for (; it + 2 < nk_main; ++it) tile_step(it, Req0{}, Rt{}, No{});
     for (; it + 2 < nk; ++it) tile_step(it, std::integral_constant<int, 1>{}, Rt{}, No{});
-    // the last extension tile may hold data in its first two k-steps only (28 adapters of rank 8: 224 of 256 columns;
-    // the rest is zero padding): those two k-steps are all it gets
-    const bool half_last = nk_ext > 0 && ((a.ext_k - 1) % kGemmBK) < kGemmBK / 2;
     for (; it < nk - (half_last ? 1 : 0); ++it) tile_step(it, std::integral_constant<int, 2>{}, Rt{}, No{});
-    if (half_last) {   // uniform; its first fragments were read, behind the barrier, in the previous step's last phase
+    if (half_last && !idle) {   // uniform; its first fragments were read, behind the barrier, in the previous step's last phase
         load_frags<MI, NI>(f1, xslot(it), wslot(it), wm, wn, lrow, khalf, 1);
         mma_frags<MI, NI>(acc, f0);
         mma_frags<MI, NI>(acc, f1);
