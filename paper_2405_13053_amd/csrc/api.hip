@@ -40,7 +40,8 @@ int dense_midsplit_splits(int T, int d_in, int d_out, int N, int r, bool bf16) {
     const int64_t tiles = (int64_t)ceil_div(T, 128) * ceil_div(d_out, 128);
     if (!route_dense_applies(T, d_in, N, r, bf16) || tiles > 160 || d_out % 8 != 0 || !gemm_dense_splitk_ok(T, d_in, d_out))
         return 0;
-    const int S = gemm_dense_splits(T, d_in, d_out);
+    const int S = gemm_multi_cap_splits(T, ceil_div(d_out, 128) + ceil_div(prep_wcat_rows(N, r), 128),
+                                        gemm_dense_splits(T, d_in, d_out));
     return S >= 2 ? S : 0;
 }
 
@@ -629,6 +630,9 @@ int group_mid_splits(const int* d_out, const bool* packed, int G, int T, int d_i
     int S = (int)((384 + tiles / 2) / tiles);
     if (S > nk / 4) S = nk / 4;
     if (S > 8) S = 8;
+    int col_tiles = 0;
+    for (int g = 0; g < G; ++g) col_tiles += ceil_div(d_out[g], 128) + ceil_div(cat_rows, 128);
+    S = gemm_multi_cap_splits(T, col_tiles, S);
     return S < 1 ? 1 : S;
 }
 

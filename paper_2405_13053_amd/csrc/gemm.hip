@@ -268,8 +268,19 @@ hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int 
     return dense_small_tiles(T) ? launch_dense<2, 2>(a, stream) : launch_dense<2, 5>(a, stream);
 }
 
-// Several matrices in one split-K launch of 128 x 128 tiles (few-tile batches): ops[i].partial[s][T][rows_i] =
-// x * W_i^T over the K range of split s, the column tiles of all of them in one grid.
+// Several matrices in one split-K launch (few-tile batches): ops[i].partial[s][T][rows_i] = x * W_i^T over the K
+// range of split s, the 128-column tiles of all of them in one grid.  The tiles are 128 rows high up to 128 tokens
+// and 256 rows above (a wavefront's 128 x 64 piece needs 0.75 fragment reads per MFMA against 1.0 at 128 x 128),
+// one workgroup per CU at most, so the number of K splits is capped for them.  Measured, 256 x 128 against 128 x
+// 128 tiles, whole call at 4096 -> 4096: T = 160 24.2 against 26.1 us, T = 400 34.5 against 43.6, T = 512 37.1
+// against 44.6, T = 640 44.1 against 50.7; at 14336 -> 4096 T = 512 77.3 against 97.9.
+bool gemm_multi_big_rows(int T) { return T > 128; }
+int gemm_multi_cap_splits(int T, int col_tiles, int S) {
+    if (!gemm_multi_big_rows(T)) return S;
+    const int cap = 256 / (ceil_div(T, 256) * (col_tiles > 0 ? col_tiles : 1));   // 256 CUs
+    return S > cap ? (cap > 0 ? cap : 1) : S;
+}
+
 hipError_t launch_gemm_dense_splitk_multi(const void* x, const DenseOperand* ops, int n_ops, int S, int T, int d_in,
                                           hipStream_t stream) {
     if (S < 1 || n_ops < 1 || n_ops > GemmArgs::kMaxSegments) return hipErrorInvalidValue;
@@ -284,11 +295,20 @@ hipError_t launch_gemm_dense_splitk_multi(const void* x, const DenseOperand* ops
     }
     a.nseg = n_ops;
     a.W = a.seg[0].W; a.d_out = a.seg[0].rows; a.partial = a.seg[0].partial;   // replaced per workgroup
+    a.tiles_n = tile0;
+    if (gemm_multi_big_rows(T)) {
+        if (((uint64_t)T + 256) * ((uint64_t)d_in * 2) >= (1ull << 32)) return hipErrorInvalidValue;
+        constexpr int smem = gemm_w3_lds_bytes<4, 2>();
+        const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<4, 2, kEpiPartial>), smem);
+        if (ea != hipSuccess) return ea;
+        a.tiles_m = ceil_div(T, 256);
+        gemm_mfma_w3_kernel<4, 2, kEpiPartial><<<dim3(a.tiles_m * a.tiles_n, S), 256, smem, stream>>>(a);
+        return hipGetLastError();
+    }
     constexpr int smem = gemm_w3_lds_bytes<2, 2>();
     const hipError_t ea = ensure_lds_limit(reinterpret_cast<const void*>(&gemm_mfma_w3_kernel<2, 2, kEpiPartial>), smem);
     if (ea != hipSuccess) return ea;
     a.tiles_m = ceil_div(T, 128);
-    a.tiles_n = tile0;
     gemm_mfma_w3_kernel<2, 2, kEpiPartial><<<dim3(a.tiles_m * a.tiles_n, S), 256, smem, stream>>>(a);
     return hipGetLastError();
 }
@@ -372,6 +392,7 @@ hipError_t gemm_init_kernels() {
     lim(&gemm_mfma_w3_kernel<4, 4, kEpiAccumulate>, gemm_w3_lds_bytes<4, 4>());
     lim(&gemm_mfma_w3_kernel<4, 2, kEpiStore>, gemm_w3_lds_bytes<4, 2>());
     lim(&gemm_mfma_w3_kernel<4, 2, kEpiAccumulate>, gemm_w3_lds_bytes<4, 2>());
+    lim(&gemm_mfma_w3_kernel<4, 2, kEpiPartial>, gemm_w3_lds_bytes<4, 2>());
     lim(&gemm_mfma_w3_kernel<2, 2, kEpiStore>, gemm_w3_lds_bytes<2, 2>());
     lim(&gemm_mfma_w3_kernel<2, 2, kEpiAccumulate>, gemm_w3_lds_bytes<2, 2>());
     lim(&gemm_mfma_w3_kernel<2, 2, kEpiPartial>, gemm_w3_lds_bytes<2, 2>());

@@ -73,6 +73,9 @@ hipError_t launch_route_dense_select(const float* part, const float* bias, int T
 // the GEMM behind launch_route_dense_products: partial[split][T][rows] = x * Wcat^T over the split's K range
 bool gemm_dense_splitk_ok(int T, int d_in, int rows);
 int gemm_dense_splits(int T, int d_in, int rows);
+// few-tile split-K launches over several matrices: S capped to one workgroup per CU where the tiles are 256 rows high
+// (col_tiles: the 128-column tiles of all the matrices of the launch)
+int gemm_multi_cap_splits(int T, int col_tiles, int S);
 hipError_t launch_gemm_dense_splitk(const void* x, const void* Wcat, int T, int d_in, int rows, float* partial,
                                     hipStream_t stream);
 
