@@ -33,12 +33,14 @@ bool decode_fused_applies(int T, int d_in, int d_out, int N, int r, bool bf16) {
 // projection is split along K over workgroups like the routing products (fp32 tiles), and the reduction adds the
 // LoRA expand, as for decode.  Returns the number of K splits, 0 = the fused GEMM runs instead.
 int dense_midsplit_splits(int T, int d_in, int d_out, int N, int r, bool bf16) {
-    // measured on 4096 -> 4096 and 4096 -> 14336, T = 65 ... 2048: the split form wins up to about 160 output tiles
-    // of 128 x 128 (19.0 against 56.1 us at T = 65, 44.6 against 60.1 at T = 512, 50.9 at T = 640, but 58.2 against
-    // 52.9 at T = 768 for 4096 -> 4096), beyond that the fp32 tiles it writes and reads back cost more than the
-    // idle CUs
+    // measured on 4096 -> 4096, 4096 -> 14336 and 14336 -> 4096, T = 65 ... 2048: the split form wins as long as the
+    // projection can still be cut into at least two K splits of at most one workgroup per CU (19.0 against 56.1 us
+    // at T = 65, 36.1 against 60.1 at T = 512, 45.6 against 48.7 at T = 704, 47.6 against 48.8 at T = 768 for
+    // 4096 -> 4096; 43.3 against 47.6 at T = 160 for 4096 -> 14336; 107 against 131 at T = 704 for 14336 -> 4096);
+    // up to 128 tokens, where the tiles are 128 rows high, up to about 160 output tiles
     const int64_t tiles = (int64_t)ceil_div(T, 128) * ceil_div(d_out, 128);
-    if (!route_dense_applies(T, d_in, N, r, bf16) || tiles > 160 || d_out % 8 != 0 || !gemm_dense_splitk_ok(T, d_in, d_out))
+    if (!route_dense_applies(T, d_in, N, r, bf16) || (T <= 128 && tiles > 160) || d_out % 8 != 0 ||
+        !gemm_dense_splitk_ok(T, d_in, d_out))
         return 0;
     const int S = gemm_multi_cap_splits(T, ceil_div(d_out, 128) + ceil_div(prep_wcat_rows(N, r), 128),
                                         gemm_dense_splits(T, d_in, d_out));
