@@ -52,8 +52,8 @@ def test_workspace_regions_hold_what_the_launches_write():
     bucketed): each region of the workspace is at least as large as what the selected launches write into it
     (tile and K-split counts taken from the launch decisions), regions do not overlap, and all of them lie inside
     meteora_workspace_bytes."""
-    Ts = [1, 7, 33, 64, 65, 100, 128, 129, 200, 256, 300, 512, 513, 700, 1000, 1150, 1151, 1500, 2000, 2048, 3000,
-          4096, 4097, 5000, 8192, 8193, 12000, 16384, 20000, 32768, 70000]
+    Ts = [1, 7, 33, 64, 65, 100, 128, 129, 160, 200, 256, 257, 300, 400, 512, 513, 640, 700, 704, 768, 769, 1000,
+          1024, 1150, 1151, 1500, 2000, 2048, 3000, 4096, 4097, 5000, 8192, 8193, 12000, 16384, 20000, 32768, 70000]
     dims = [(4096, 4096), (4096, 8), (4096, 256), (4096, 512), (4096, 1024), (4096, 14336), (14336, 4096),
             (5120, 5120), (5120, 13824), (512, 264), (1088, 520), (64, 72), (256, 136)]
     checked = 0
