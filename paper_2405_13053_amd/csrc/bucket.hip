@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void bucket_scatter_kernel(const int32_t* __re
         const int rank_in_wave = __popcll(peers & below);
         const int peers_in_wave = __popcll(peers);
         wave_hist[wave][lane] = 0;
-        __syncthreads();   // rows cleared (each wave clears its own); also orders against last round's reads
+        __syncthreads();   // rows cleared (each wave clears its own); also orders against the previous pass's reads
         if (valid && rank_in_wave == 0) wave_hist[wave][key] = peers_in_wave;
         __syncthreads();
         if (valid) {
