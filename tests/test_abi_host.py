@@ -307,3 +307,14 @@ def test_variant_validation(lib):
         assert call(v, ws=None) == WORKSPACE and call(v, wsb=1024) == WORKSPACE
         assert call(v, T=0) == OK
     assert call(v=7) == INVALID
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: --gpus 2 exits with a message and a non-zero status, before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
